@@ -1,0 +1,312 @@
+/*
+ * CPU oracle for one GPU's share of Ulysses sequence parallelism.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It shares no code with the GPU path and is
+ * never called by it; only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg may use it.
+ *
+ * What it follows
+ *  - Layout transforms: the paper's system design (Section 3.1, Figure 2): the
+ *    sequence is split into P contiguous shards; after the first all-to-all each
+ *    device holds the full sequence for a non-overlapping subset of heads; the
+ *    second all-to-all returns the context to sequence-parallel form.  The
+ *    transforms here are the local halves of those exchanges (the exchange
+ *    itself is a pointer shuffle done by the tests).
+ *  - Attention: Equation 1, Softmax(Q K^T / sqrt(d)) V per head, with d the head
+ *    dimension, softmax over keys, and the causal variant (Section 3.4) reading
+ *    "key j is visible to query i iff j <= i".  The backward pass is the
+ *    calculus of Equation 1 (the paper prints no gradient formulas).
+ *
+ * All floating point is fp64; sums run in index order; there is no tiling,
+ * fusion or online rescaling.  OpenMP only spreads independent rows (or
+ * columns) over cores: each output element is still produced by one thread
+ * summing in index order, so results do not depend on the thread count.
+ *
+ * Pins (tests/test_oracle_*.py): numpy reshape/transpose for the layout maps,
+ * permutation/bijectivity and round-trip identities, dense numpy softmax,
+ * closed forms under constant K, torch autograd and central finite differences
+ * for the gradients, column-sum invariants.  No function here is unpinned.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { LAYOUT_SEQ_HEAD = 0, LAYOUT_HEAD_SEQ = 1 };
+
+/* ------------------------------------------------------------------------- */
+/* Layout transforms (16-bit payloads, bit-exact)                            */
+/* ------------------------------------------------------------------------- */
+
+/* Send side of all-to-all #1.  x:[nl,H,d] -> send:[P,nl,Hl,d]; chunk p holds the
+ * heads owned by destination rank p (block-contiguous head ownership). */
+void oracle_pack(const uint16_t* x, uint16_t* send, int64_t nl, int H, int d, int P) {
+    const int Hl = H / P;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int p = 0; p < P; ++p)
+        for (int64_t n = 0; n < nl; ++n)
+            for (int hl = 0; hl < Hl; ++hl)
+                for (int c = 0; c < d; ++c)
+                    send[((p * nl + n) * Hl + hl) * d + c] = x[(n * H + p * Hl + hl) * d + c];
+}
+
+/* Receive side of all-to-all #1.  recv:[P,nl,Hl,d] (chunk q came from source rank q,
+ * which holds tokens [q*nl,(q+1)*nl)) -> y:[N,Hl,d] or [Hl,N,d], N = P*nl. */
+void oracle_unpack(const uint16_t* recv, uint16_t* y, int64_t nl, int H, int d, int P, int layout) {
+    const int Hl = H / P;
+    const int64_t N = (int64_t)P * nl;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int q = 0; q < P; ++q)
+        for (int64_t n = 0; n < nl; ++n)
+            for (int hl = 0; hl < Hl; ++hl)
+                for (int c = 0; c < d; ++c) {
+                    const int64_t t = q * nl + n;
+                    const int64_t dst = (layout == LAYOUT_HEAD_SEQ) ? (hl * N + t) * d + c
+                                                                   : (t * Hl + hl) * d + c;
+                    y[dst] = recv[((q * nl + n) * Hl + hl) * d + c];
+                }
+}
+
+/* Send side of all-to-all #2 (context back to sequence-parallel form).
+ * o:[N,Hl,d] or [Hl,N,d] -> send:[P,nl,Hl,d]; chunk q holds the tokens owned by rank q. */
+void oracle_pack_rev(const uint16_t* o, uint16_t* send, int64_t nl, int H, int d, int P, int layout) {
+    const int Hl = H / P;
+    const int64_t N = (int64_t)P * nl;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int q = 0; q < P; ++q)
+        for (int64_t n = 0; n < nl; ++n)
+            for (int hl = 0; hl < Hl; ++hl)
+                for (int c = 0; c < d; ++c) {
+                    const int64_t t = q * nl + n;
+                    const int64_t src = (layout == LAYOUT_HEAD_SEQ) ? (hl * N + t) * d + c
+                                                                   : (t * Hl + hl) * d + c;
+                    send[((q * nl + n) * Hl + hl) * d + c] = o[src];
+                }
+}
+
+/* Receive side of all-to-all #2.  recv:[P,nl,Hl,d] (chunk p came from the rank that
+ * owns heads [p*Hl,(p+1)*Hl)) -> y:[nl,H,d]. */
+void oracle_unpack_rev(const uint16_t* recv, uint16_t* y, int64_t nl, int H, int d, int P) {
+    const int Hl = H / P;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int p = 0; p < P; ++p)
+        for (int64_t n = 0; n < nl; ++n)
+            for (int hl = 0; hl < Hl; ++hl)
+                for (int c = 0; c < d; ++c)
+                    y[(n * H + p * Hl + hl) * d + c] = recv[((p * nl + n) * Hl + hl) * d + c];
+}
+
+/* ------------------------------------------------------------------------- */
+/* bf16 decode (exact)                                                       */
+/* ------------------------------------------------------------------------- */
+void oracle_bf16_to_f64(const uint16_t* in, double* out, int64_t count) {
+    for (int64_t i = 0; i < count; ++i) {
+        union { uint32_t u; float f; } v;
+        v.u = (uint32_t)in[i] << 16;
+        out[i] = (double)v.f;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Attention, Equation 1, fp64                                               */
+/* ------------------------------------------------------------------------- */
+
+/* offset of element (token t, head h, channel 0) */
+static inline int64_t row_off(int64_t t, int h, int64_t N, int Hl, int d, int layout) {
+    return (layout == LAYOUT_HEAD_SEQ) ? ((int64_t)h * N + t) * d : (t * Hl + h) * d;
+}
+
+static inline double dot(const double* a, const double* b, int d) {
+    double s = 0.0;
+    for (int c = 0; c < d; ++c) s += a[c] * b[c];
+    return s;
+}
+
+/* last visible key (exclusive) for query i */
+static inline int64_t key_end(int64_t i, int64_t N, int causal) { return causal ? i + 1 : N; }
+
+/* One query row of Equation 1: scores, max, sum, log-sum-exp, output row.
+ * s_buf has room for N scores.  Returns LSE_i; writes o_row[d]. */
+static double attn_row(const double* q, const double* k, const double* v, int64_t i, int h,
+                       int64_t N, int Hl, int d, double scale, int causal, int layout,
+                       double* s_buf, double* o_row) {
+    const double* qi = q + row_off(i, h, N, Hl, d, layout);
+    const int64_t je = key_end(i, N, causal);
+    double m = -INFINITY;
+    for (int64_t j = 0; j < je; ++j) {
+        s_buf[j] = scale * dot(qi, k + row_off(j, h, N, Hl, d, layout), d);
+        if (s_buf[j] > m) m = s_buf[j];
+    }
+    double l = 0.0;
+    for (int64_t j = 0; j < je; ++j) l += exp(s_buf[j] - m);
+    const double lse = m + log(l);
+    for (int c = 0; c < d; ++c) o_row[c] = 0.0;
+    for (int64_t j = 0; j < je; ++j) {
+        const double p = exp(s_buf[j] - lse);
+        const double* vj = v + row_off(j, h, N, Hl, d, layout);
+        for (int c = 0; c < d; ++c) o_row[c] += p * vj[c];
+    }
+    return lse;
+}
+
+/* Full forward.  q,k,v,o in `layout`; lse:[Hl,N]. */
+int oracle_attn_fwd(const double* q, const double* k, const double* v, double* o, double* lse,
+                    int64_t N, int Hl, int d, double scale, int causal, int layout) {
+    int fail = 0;
+#pragma omp parallel
+    {
+        double* s_buf = (double*)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+        if (!s_buf) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for collapse(2) schedule(dynamic, 16)
+            for (int h = 0; h < Hl; ++h)
+                for (int64_t i = 0; i < N; ++i)
+                    lse[(int64_t)h * N + i] = attn_row(q, k, v, i, h, N, Hl, d, scale, causal, layout, s_buf,
+                                                       o + row_off(i, h, N, Hl, d, layout));
+        }
+        free(s_buf);
+    }
+    return fail;
+}
+
+/* Forward for a set of query rows.  o_rows:[n_rows,Hl,d], lse_rows:[Hl,n_rows]. */
+int oracle_attn_fwd_rows(const double* q, const double* k, const double* v,
+                         const int64_t* rows, int64_t n_rows, double* o_rows, double* lse_rows,
+                         int64_t N, int Hl, int d, double scale, int causal, int layout) {
+    int fail = 0;
+#pragma omp parallel
+    {
+        double* s_buf = (double*)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+        if (!s_buf) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for collapse(2) schedule(dynamic, 1)
+            for (int h = 0; h < Hl; ++h)
+                for (int64_t r = 0; r < n_rows; ++r)
+                    lse_rows[(int64_t)h * n_rows + r] =
+                        attn_row(q, k, v, rows[r], h, N, Hl, d, scale, causal, layout, s_buf,
+                                 o_rows + (r * Hl + h) * d);
+        }
+        free(s_buf);
+    }
+    return fail;
+}
+
+/* Backward for a set of query rows `rows` (pass all rows 0..N-1 for the full backward).
+ *
+ *   D_i   = sum_c dO_ic O_ic
+ *   P_ij  = exp(S_ij - LSE_i),  dP_ij = sum_c dO_ic V_jc,  dS_ij = P_ij (dP_ij - D_i)
+ *   dQ_i  = scale * sum_j dS_ij K_j         (written to dq_rows:[n_rows,Hl,d])
+ *   dK_j  = scale * sum_{i in rows} dS_ij Q_i,   dV_j = sum_{i in rows} P_ij dO_i
+ *
+ * dk, dv are full tensors in `layout`: they are the gradients for a dO that is
+ * zero outside `rows` (backward is linear in dO and rows are independent).
+ * `rows` must be strictly increasing. */
+int oracle_attn_bwd_rows(const double* q, const double* k, const double* v, const double* dout,
+                         const int64_t* rows, int64_t n_rows,
+                         double* dq_rows, double* dk, double* dv,
+                         int64_t N, int Hl, int d, double scale, int causal, int layout) {
+    double* lse = (double*)malloc(sizeof(double) * (size_t)(Hl * n_rows + 1));
+    double* Dv = (double*)malloc(sizeof(double) * (size_t)(Hl * n_rows + 1));
+    if (!lse || !Dv) { free(lse); free(Dv); return 1; }
+    int fail = 0;
+
+    /* pass 1: per-row LSE and D (needs the fp64 output row) */
+#pragma omp parallel
+    {
+        double* s_buf = (double*)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+        double* o_row = (double*)malloc(sizeof(double) * (size_t)d);
+        if (!s_buf || !o_row) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for collapse(2) schedule(dynamic, 1)
+            for (int h = 0; h < Hl; ++h)
+                for (int64_t r = 0; r < n_rows; ++r) {
+                    const int64_t i = rows[r];
+                    lse[(int64_t)h * n_rows + r] =
+                        attn_row(q, k, v, i, h, N, Hl, d, scale, causal, layout, s_buf, o_row);
+                    Dv[(int64_t)h * n_rows + r] = dot(dout + row_off(i, h, N, Hl, d, layout), o_row, d);
+                }
+        }
+        free(s_buf); free(o_row);
+    }
+    if (fail) { free(lse); free(Dv); return 1; }
+
+    /* pass 2: dQ, one query row per iteration */
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int h = 0; h < Hl; ++h)
+        for (int64_t r = 0; r < n_rows; ++r) {
+            const int64_t i = rows[r];
+            const double* qi = q + row_off(i, h, N, Hl, d, layout);
+            const double* doi = dout + row_off(i, h, N, Hl, d, layout);
+            double* dqi = dq_rows + (r * Hl + h) * d;
+            for (int c = 0; c < d; ++c) dqi[c] = 0.0;
+            const int64_t je = key_end(i, N, causal);
+            for (int64_t j = 0; j < je; ++j) {
+                const double* kj = k + row_off(j, h, N, Hl, d, layout);
+                const double* vj = v + row_off(j, h, N, Hl, d, layout);
+                const double p = exp(scale * dot(qi, kj, d) - lse[(int64_t)h * n_rows + r]);
+                const double ds = p * (dot(doi, vj, d) - Dv[(int64_t)h * n_rows + r]);
+                for (int c = 0; c < d; ++c) dqi[c] += scale * ds * kj[c];
+            }
+        }
+
+    /* pass 3: dK, dV, one key row per iteration */
+#pragma omp parallel for collapse(2) schedule(dynamic, 64)
+    for (int h = 0; h < Hl; ++h)
+        for (int64_t j = 0; j < N; ++j) {
+            const double* kj = k + row_off(j, h, N, Hl, d, layout);
+            const double* vj = v + row_off(j, h, N, Hl, d, layout);
+            double* dkj = dk + row_off(j, h, N, Hl, d, layout);
+            double* dvj = dv + row_off(j, h, N, Hl, d, layout);
+            for (int c = 0; c < d; ++c) { dkj[c] = 0.0; dvj[c] = 0.0; }
+            for (int64_t r = 0; r < n_rows; ++r) {
+                const int64_t i = rows[r];
+                if (causal && i < j) continue;
+                const double* qi = q + row_off(i, h, N, Hl, d, layout);
+                const double* doi = dout + row_off(i, h, N, Hl, d, layout);
+                const double p = exp(scale * dot(qi, kj, d) - lse[(int64_t)h * n_rows + r]);
+                const double ds = p * (dot(doi, vj, d) - Dv[(int64_t)h * n_rows + r]);
+                for (int c = 0; c < d; ++c) { dvj[c] += p * doi[c]; dkj[c] += scale * ds * qi[c]; }
+            }
+        }
+    free(lse); free(Dv);
+    return 0;
+}
+
+/* Full backward: every row.  dq, dk, dv in `layout`. */
+int oracle_attn_bwd(const double* q, const double* k, const double* v, const double* dout,
+                    double* dq, double* dk, double* dv,
+                    int64_t N, int Hl, int d, double scale, int causal, int layout) {
+    int64_t* rows = (int64_t*)malloc(sizeof(int64_t) * (size_t)(N + 1));
+    double* dq_rows = (double*)malloc(sizeof(double) * (size_t)(N * Hl * d + 1));
+    if (!rows || !dq_rows) { free(rows); free(dq_rows); return 1; }
+    for (int64_t i = 0; i < N; ++i) rows[i] = i;
+    int rc = oracle_attn_bwd_rows(q, k, v, dout, rows, N, dq_rows, dk, dv, N, Hl, d, scale, causal, layout);
+    if (!rc)
+        for (int64_t i = 0; i < N; ++i)
+            for (int h = 0; h < Hl; ++h)
+                memcpy(dq + row_off(i, h, N, Hl, d, layout), dq_rows + (i * Hl + h) * d, sizeof(double) * (size_t)d);
+    free(rows); free(dq_rows);
+    return rc;
+}
+
+int oracle_num_threads(void) {
+    int n = 1;
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    n = omp_get_max_threads();
+#endif
+    return n;
+}
