@@ -1,0 +1,119 @@
+/*
+ * ulysses.h - C ABI of the single-GPU share of Ulysses sequence parallelism on MI355X (gfx950).
+ *
+ * One GPU's work inside a sequence-parallel attention layer (paper Section 3.1, Figure 2):
+ *
+ *   x [N/P, H, d]  --ulysses_pack-->  P send chunks  ==(all-to-all, NOT in this library)==>
+ *   P received chunks  --ulysses_unpack-->  [N, H/P, d]  --ulysses_attn_fwd/bwd (Equation 1)-->
+ *   o [N, H/P, d]  --ulysses_pack_rev-->  P send chunks  ==(all-to-all)==>  --ulysses_unpack_rev--> [N/P, H, d]
+ *
+ * Conventions shared by every entry point
+ *  - All data pointers are DEVICE pointers (hipMalloc'd or equivalent), 16-byte aligned, owned by the
+ *    caller.  The library allocates nothing, keeps no state between calls and never synchronises.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
+ *    asynchronously on it; outputs are valid once the stream reaches the end of the enqueued work.
+ *  - Tensors are dense, row-major, last index fastest.  Sources and destinations must not overlap.
+ *  - Every function returns a ULY_* status.  All argument validation happens before the first HIP
+ *    call, so bad arguments are reported without touching the device.  Nothing is printed, thrown
+ *    or aborted.  A size of zero tokens is valid, does nothing, and does not look at the pointers.
+ *  - Head ownership is block-contiguous (rank p owns heads [p*H/P, (p+1)*H/P)) and sequence shards
+ *    are contiguous in rank order (rank q holds tokens [q*N/P, (q+1)*N/P)).  The paper only requires
+ *    non-overlapping head subsets and a partitioned sequence; these are the fixed choices that make
+ *    the byte layout unique.  H must be a multiple of P.
+ */
+#ifndef ULYSSES_H
+#define ULYSSES_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ULY_OK = 0,
+    ULY_ERR_NULL = 1,        /* a required pointer is NULL                                   */
+    ULY_ERR_SHAPE = 2,       /* zero/negative dimension, H % P != 0, size overflow           */
+    ULY_ERR_UNSUPPORTED = 3, /* head dim not in {64,128}, layout enum, element size, scale<=0 */
+    ULY_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                             */
+    ULY_ERR_ALIAS = 5,       /* an output range overlaps an input (or another output) range  */
+    ULY_ERR_WORKSPACE = 6,   /* workspace NULL or smaller than the *_workspace_bytes() value */
+    ULY_ERR_LAUNCH = 7       /* the HIP runtime refused a launch                             */
+};
+
+enum {
+    ULY_LAYOUT_SEQ_HEAD = 0, /* [N, Hl, d]  token-major (default)  */
+    ULY_LAYOUT_HEAD_SEQ = 1  /* [Hl, N, d]  head-major             */
+};
+
+/* ---------------------------------------------------------------------------------------------
+ * Layout transforms around the two all-to-alls (Section 3.1; message sizes in Section 3.2).
+ * Pure data movement of `elem_bytes`-sized elements (1, 2 or 4); results are bit-exact.
+ * n_local = N/P tokens held by this rank, H total heads, d head dimension, P ranks, Hl = H/P.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Send side of the first all-to-all.
+ *   x    [n_local, H, d]        in
+ *   send [P, n_local, Hl, d]    out;  send[p, n, hl, :] = x[n, p*Hl + hl, :]
+ * Chunk p is the contiguous message for destination rank p. */
+int ulysses_pack(const void* x, void* send, int64_t n_local, int H, int d, int P,
+                 int elem_bytes, void* stream);
+
+/* Receive side of the first all-to-all.
+ *   recv [P, n_local, Hl, d]    in;  chunk q arrived from source rank q
+ *   y    [P*n_local, Hl, d]     out  (ULY_LAYOUT_SEQ_HEAD):  y[q*n_local + n, hl, :] = recv[q, n, hl, :]
+ *        [Hl, P*n_local, d]     out  (ULY_LAYOUT_HEAD_SEQ):  y[hl, q*n_local + n, :] = recv[q, n, hl, :] */
+int ulysses_unpack(const void* recv, void* y, int64_t n_local, int H, int d, int P,
+                   int elem_bytes, int out_layout, void* stream);
+
+/* Send side of the second all-to-all (attention output back to sequence-parallel form).
+ *   o    [P*n_local, Hl, d] or [Hl, P*n_local, d] (in_layout)   in
+ *   send [P, n_local, Hl, d]    out;  send[q, n, hl, :] = o(token q*n_local + n, head hl) */
+int ulysses_pack_rev(const void* o, void* send, int64_t n_local, int H, int d, int P,
+                     int elem_bytes, int in_layout, void* stream);
+
+/* Receive side of the second all-to-all.
+ *   recv [P, n_local, Hl, d]    in;  chunk p arrived from the rank owning heads [p*Hl, (p+1)*Hl)
+ *   y    [n_local, H, d]        out; y[n, p*Hl + hl, :] = recv[p, n, hl, :] */
+int ulysses_unpack_rev(const void* recv, void* y, int64_t n_local, int H, int d, int P,
+                       int elem_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Exact softmax attention per local head, Equation 1:  O = Softmax(Q K^T * scale) V,
+ * softmax over keys.  causal != 0 restricts query i to keys j <= i (global token positions,
+ * diagonal included).  q, k, v, o, dout, dq, dk, dv are bf16 in `layout`; arithmetic is bf16
+ * MFMA with fp32 accumulation and fp32 softmax; outputs are rounded to bf16 (nearest even).
+ * N tokens (any N >= 0), Hl local heads, d in {64, 128}.  `scale` is normally 1/sqrt(d) and must
+ * be finite and > 0 (anything else is ULY_ERR_UNSUPPORTED).
+ * ------------------------------------------------------------------------------------------- */
+
+/* Forward.
+ *   lse [Hl, N] fp32 out: natural-log sum-exp of the scaled, masked logits of every query row.
+ *   It is the only state besides o that the backward pass needs. */
+int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                     int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream);
+
+/* Bytes of device scratch the backward pass needs (one fp32 per query row and head). */
+size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d);
+
+/* Backward: gradients of sum(O * dout) with respect to q, k, v.  The probabilities are recomputed
+ * from q, k and the saved lse; o is used only for the row terms D_i = dout_i . o_i.
+ *   workspace: device scratch of at least ulysses_attn_bwd_workspace_bytes() bytes, 16-byte aligned;
+ *   its contents on entry are ignored and on exit unspecified.
+ * Results are deterministic (no atomics): the same inputs give the same bits. */
+int ulysses_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                     const float* lse, void* dq, void* dk, void* dv,
+                     void* workspace, size_t workspace_bytes,
+                     int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char* ulysses_status_string(int status);
+
+/* Library ABI version (bumped when a signature changes). */
+int ulysses_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ULYSSES_H */

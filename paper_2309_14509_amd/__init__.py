@@ -1,0 +1,168 @@
+"""Python binding of libulysses (MI355X / gfx950): argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their device pointers and
+the current HIP stream through the C ABI declared in ``include/ulysses.h`` and returns the output
+tensors.  PyTorch is used for device memory and streams; all computation happens in the library's
+kernels.  There is no CPU fallback: if the library is missing or a call fails, an exception is
+raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from . import build as _build
+
+LAYOUT_SEQ_HEAD = 0   # [N, Hl, d]
+LAYOUT_HEAD_SEQ = 1   # [Hl, N, d]
+
+EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
+           "ulysses_attn_fwd", "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd",
+           "ulysses_status_string", "ulysses_abi_version")
+
+_lib = None
+
+
+class UlyssesError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+def load(path: str | None = None):
+    """Load libulysses.so (built in-tree by ``build.build_library``).  Raises if it is absent."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or _build.LIB
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} not found: build it with __graft_entry__.build() "
+                                "(python -m paper_2309_14509_amd.build)")
+    lib = ctypes.CDLL(path)
+    vp, i64, ci, cf, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.ulysses_pack.argtypes = [vp, vp, i64, ci, ci, ci, ci, vp]
+    lib.ulysses_unpack.argtypes = [vp, vp, i64, ci, ci, ci, ci, ci, vp]
+    lib.ulysses_pack_rev.argtypes = [vp, vp, i64, ci, ci, ci, ci, ci, vp]
+    lib.ulysses_unpack_rev.argtypes = [vp, vp, i64, ci, ci, ci, ci, vp]
+    lib.ulysses_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, cf, ci, ci, vp]
+    lib.ulysses_attn_bwd_workspace_bytes.argtypes = [i64, ci, ci]
+    lib.ulysses_attn_bwd_workspace_bytes.restype = sz
+    lib.ulysses_attn_bwd.argtypes = [vp] * 10 + [sz, i64, ci, ci, cf, ci, ci, vp]
+    lib.ulysses_status_string.argtypes = [ci]
+    lib.ulysses_status_string.restype = ctypes.c_char_p
+    for name in ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
+                 "ulysses_attn_fwd", "ulysses_attn_bwd", "ulysses_abi_version"):
+        getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().ulysses_status_string(status).decode()
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise UlyssesError(rc, where)
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, where):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{where}: tensors must be contiguous GPU tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+# ---- layout transforms ------------------------------------------------------------------------
+def ulysses_pack(x, P: int):
+    """x [n_local, H, d] -> send [P, n_local, H/P, d]."""
+    import torch
+    nl, H, d = x.shape
+    send = torch.empty((P, nl, H // max(P, 1) if P > 0 else 0, d), dtype=x.dtype, device=x.device)
+    _check(load().ulysses_pack(_dev(x, "pack"), _dev(send, "pack"), nl, H, d, P, x.element_size(), _stream()),
+           "ulysses_pack")
+    return send
+
+
+def ulysses_unpack(recv, out_layout: int = LAYOUT_SEQ_HEAD):
+    """recv [P, n_local, Hl, d] -> y [P*n_local, Hl, d] (or [Hl, P*n_local, d])."""
+    import torch
+    P, nl, Hl, d = recv.shape
+    shape = (Hl, P * nl, d) if out_layout == LAYOUT_HEAD_SEQ else (P * nl, Hl, d)
+    y = torch.empty(shape, dtype=recv.dtype, device=recv.device)
+    _check(load().ulysses_unpack(_dev(recv, "unpack"), _dev(y, "unpack"), nl, Hl * P, d, P, recv.element_size(),
+                                 out_layout, _stream()), "ulysses_unpack")
+    return y
+
+
+def ulysses_pack_rev(o, P: int, in_layout: int = LAYOUT_SEQ_HEAD):
+    """o [N, Hl, d] (or [Hl, N, d]) -> send [P, N/P, Hl, d]."""
+    import torch
+    if in_layout == LAYOUT_HEAD_SEQ:
+        Hl, N, d = o.shape
+    else:
+        N, Hl, d = o.shape
+    if P <= 0 or N % P:
+        raise ValueError("N must be a multiple of P")
+    send = torch.empty((P, N // P, Hl, d), dtype=o.dtype, device=o.device)
+    _check(load().ulysses_pack_rev(_dev(o, "pack_rev"), _dev(send, "pack_rev"), N // P, Hl * P, d, P,
+                                   o.element_size(), in_layout, _stream()), "ulysses_pack_rev")
+    return send
+
+
+def ulysses_unpack_rev(recv):
+    """recv [P, n_local, Hl, d] -> y [n_local, P*Hl, d]."""
+    import torch
+    P, nl, Hl, d = recv.shape
+    y = torch.empty((nl, P * Hl, d), dtype=recv.dtype, device=recv.device)
+    _check(load().ulysses_unpack_rev(_dev(recv, "unpack_rev"), _dev(y, "unpack_rev"), nl, Hl * P, d, P,
+                                     recv.element_size(), _stream()), "ulysses_unpack_rev")
+    return y
+
+
+# ---- attention ----------------------------------------------------------------------------------
+def _attn_dims(q, layout):
+    if layout == LAYOUT_HEAD_SEQ:
+        Hl, N, d = q.shape
+    else:
+        N, Hl, d = q.shape
+    return N, Hl, d
+
+
+def ulysses_attn_fwd(q, k, v, scale: float, causal: bool = True, layout: int = LAYOUT_SEQ_HEAD, out=None, lse=None):
+    """bf16 q, k, v in ``layout`` -> (o bf16 in ``layout``, lse fp32 [Hl, N])."""
+    import torch
+    if q.dtype != torch.bfloat16:
+        raise ValueError("attention tensors must be bfloat16")
+    N, Hl, d = _attn_dims(q, layout)
+    o = torch.empty_like(q) if out is None else out
+    lse = torch.empty((Hl, N), dtype=torch.float32, device=q.device) if lse is None else lse
+    _check(load().ulysses_attn_fwd(_dev(q, "attn_fwd"), _dev(k, "attn_fwd"), _dev(v, "attn_fwd"), _dev(o, "attn_fwd"),
+                                   _dev(lse, "attn_fwd"), N, Hl, d, scale, int(causal), layout, _stream()),
+           "ulysses_attn_fwd")
+    return o, lse
+
+
+def ulysses_attn_bwd_workspace_bytes(N: int, Hl: int, d: int) -> int:
+    return int(load().ulysses_attn_bwd_workspace_bytes(N, Hl, d))
+
+
+def ulysses_attn_bwd(q, k, v, o, dout, lse, scale: float, causal: bool = True, layout: int = LAYOUT_SEQ_HEAD,
+                     workspace=None, out=None):
+    """-> (dq, dk, dv) bf16 in ``layout``."""
+    import torch
+    N, Hl, d = _attn_dims(q, layout)
+    need = ulysses_attn_bwd_workspace_bytes(N, Hl, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    dq, dk, dv = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)) if out is None else out
+    _check(load().ulysses_attn_bwd(_dev(q, "attn_bwd"), _dev(k, "attn_bwd"), _dev(v, "attn_bwd"), _dev(o, "attn_bwd"),
+                                   _dev(dout, "attn_bwd"), _dev(lse, "attn_bwd"), _dev(dq, "attn_bwd"),
+                                   _dev(dk, "attn_bwd"), _dev(dv, "attn_bwd"), _dev(workspace, "attn_bwd"),
+                                   workspace.numel() * workspace.element_size(), N, Hl, d, scale, int(causal), layout,
+                                   _stream()), "ulysses_attn_bwd")
+    return dq, dk, dv

@@ -1,0 +1,165 @@
+// C ABI of libulysses: argument validation (no HIP call is made before it passes) and dispatch.
+#include <stdint.h>
+
+#include "internal.h"
+
+namespace {
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+struct Range {
+    const void* p;
+    uint64_t bytes;
+};
+
+inline bool overlap(const Range& a, const Range& b) {
+    if (a.bytes == 0 || b.bytes == 0) return false;
+    const uintptr_t a0 = (uintptr_t)a.p, b0 = (uintptr_t)b.p;
+    return a0 < b0 + b.bytes && b0 < a0 + a.bytes;
+}
+
+// Every output against every input and every other output.
+template <int NI, int NO>
+bool any_alias(const Range (&in)[NI], const Range (&out)[NO]) {
+    for (int o = 0; o < NO; ++o) {
+        for (int i = 0; i < NI; ++i)
+            if (overlap(out[o], in[i])) return true;
+        for (int o2 = o + 1; o2 < NO; ++o2)
+            if (overlap(out[o], out[o2])) return true;
+    }
+    return false;
+}
+
+// Common checks of the four layout transforms; on success *total_bytes is the tensor size.
+int check_layout_args(const void* src, const void* dst, int64_t n_local, int H, int d, int P, int elem_bytes,
+                      int layout, uint64_t* total_bytes) {
+    if (n_local < 0 || H <= 0 || d <= 0 || P <= 0 || H % P != 0) return ULY_ERR_SHAPE;
+    if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4) return ULY_ERR_UNSUPPORTED;
+    if (layout != ULY_LAYOUT_SEQ_HEAD && layout != ULY_LAYOUT_HEAD_SEQ) return ULY_ERR_UNSUPPORTED;
+    const uint64_t row_bytes = (uint64_t)H * (uint64_t)d * (uint64_t)elem_bytes;   // < 2^64: three ints
+    if (row_bytes >= (1ull << 40)) return ULY_ERR_SHAPE;
+    if ((uint64_t)n_local >= (1ull << 62) / row_bytes) return ULY_ERR_SHAPE;
+    if ((uint64_t)n_local * (uint64_t)P >= (1ull << 40)) return ULY_ERR_SHAPE;      // N = P * n_local
+    *total_bytes = (uint64_t)n_local * row_bytes;
+    if (*total_bytes == 0) return ULY_OK;                                           // nothing to move
+    if (!src || !dst) return ULY_ERR_NULL;
+    if (misaligned(src) || misaligned(dst)) return ULY_ERR_ALIGN;
+    const Range in[1] = {{src, *total_bytes}}, out[1] = {{dst, *total_bytes}};
+    if (any_alias(in, out)) return ULY_ERR_ALIAS;
+    return ULY_OK;
+}
+
+int check_attn_common(int64_t N, int Hl, int d, int layout, uint64_t* tensor_bytes) {
+    if (N < 0 || Hl <= 0 || d <= 0) return ULY_ERR_SHAPE;
+    if (d != 64 && d != 128) return ULY_ERR_UNSUPPORTED;
+    if (layout != ULY_LAYOUT_SEQ_HEAD && layout != ULY_LAYOUT_HEAD_SEQ) return ULY_ERR_UNSUPPORTED;
+    if (N >= (1ll << 31)) return ULY_ERR_SHAPE;                       // tile counters are 32-bit
+    if ((uint64_t)N * (uint64_t)Hl >= (1ull << 40)) return ULY_ERR_SHAPE;
+    *tensor_bytes = (uint64_t)N * (uint64_t)Hl * (uint64_t)d * 2u;
+    return ULY_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ulysses_pack(const void* x, void* send, int64_t n_local, int H, int d, int P, int elem_bytes, void* stream) {
+    uint64_t bytes;
+    const int rc = check_layout_args(x, send, n_local, H, d, P, elem_bytes, ULY_LAYOUT_SEQ_HEAD, &bytes);
+    if (rc != ULY_OK) return rc;
+    return uly::regroup(x, send, n_local, P, (int64_t)(H / P) * d * elem_bytes, /*to_b=*/true, stream);
+}
+
+int ulysses_unpack_rev(const void* recv, void* y, int64_t n_local, int H, int d, int P, int elem_bytes,
+                       void* stream) {
+    uint64_t bytes;
+    const int rc = check_layout_args(recv, y, n_local, H, d, P, elem_bytes, ULY_LAYOUT_SEQ_HEAD, &bytes);
+    if (rc != ULY_OK) return rc;
+    return uly::regroup(recv, y, n_local, P, (int64_t)(H / P) * d * elem_bytes, /*to_b=*/false, stream);
+}
+
+int ulysses_unpack(const void* recv, void* y, int64_t n_local, int H, int d, int P, int elem_bytes,
+                   int out_layout, void* stream) {
+    uint64_t bytes;
+    const int rc = check_layout_args(recv, y, n_local, H, d, P, elem_bytes, out_layout, &bytes);
+    if (rc != ULY_OK) return rc;
+    const int64_t N = n_local * P;
+    const int Hl = H / P;
+    if (out_layout == ULY_LAYOUT_SEQ_HEAD || Hl == 1)       // same linear order: one straight copy
+        return uly::regroup(recv, y, N, 1, (int64_t)Hl * d * elem_bytes, true, stream);
+    return uly::regroup(recv, y, N, Hl, (int64_t)d * elem_bytes, /*to_b=*/true, stream);   // [N,Hl,d] -> [Hl,N,d]
+}
+
+int ulysses_pack_rev(const void* o, void* send, int64_t n_local, int H, int d, int P, int elem_bytes,
+                     int in_layout, void* stream) {
+    uint64_t bytes;
+    const int rc = check_layout_args(o, send, n_local, H, d, P, elem_bytes, in_layout, &bytes);
+    if (rc != ULY_OK) return rc;
+    const int64_t N = n_local * P;
+    const int Hl = H / P;
+    if (in_layout == ULY_LAYOUT_SEQ_HEAD || Hl == 1)
+        return uly::regroup(o, send, N, 1, (int64_t)Hl * d * elem_bytes, true, stream);
+    return uly::regroup(o, send, N, Hl, (int64_t)d * elem_bytes, /*to_b=*/false, stream);  // [Hl,N,d] -> [N,Hl,d]
+}
+
+int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int Hl, int d,
+                     float scale, int causal, int layout, void* stream) {
+    uint64_t tb;
+    const int rc = check_attn_common(N, Hl, d, layout, &tb);
+    if (rc != ULY_OK) return rc;
+    if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;     // scale must be finite and > 0
+    if (N == 0) return ULY_OK;
+    if (!q || !k || !v || !o || !lse) return ULY_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse)) return ULY_ERR_ALIGN;
+    const Range in[3] = {{q, tb}, {k, tb}, {v, tb}};
+    const Range out[2] = {{o, tb}, {lse, (uint64_t)N * Hl * 4u}};
+    if (any_alias(in, out)) return ULY_ERR_ALIAS;
+    return uly::attn_fwd_launch(q, k, v, o, lse, N, Hl, d, scale, causal != 0, uly::strides_for(layout, N, Hl, d),
+                                stream);
+}
+
+size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
+    (void)d;
+    if (N <= 0 || Hl <= 0) return 0;
+    return (size_t)N * (size_t)Hl * sizeof(float);
+}
+
+int ulysses_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
+                     void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int64_t N, int Hl,
+                     int d, float scale, int causal, int layout, void* stream) {
+    uint64_t tb;
+    const int rc = check_attn_common(N, Hl, d, layout, &tb);
+    if (rc != ULY_OK) return rc;
+    if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;
+    if (N == 0) return ULY_OK;
+    if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv) return ULY_ERR_NULL;
+    const size_t need = ulysses_attn_bwd_workspace_bytes(N, Hl, d);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return ULY_ERR_WORKSPACE;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(dout) || misaligned(lse) ||
+        misaligned(dq) || misaligned(dk) || misaligned(dv) || misaligned(workspace))
+        return ULY_ERR_ALIGN;
+    const uint64_t lb = (uint64_t)N * Hl * 4u;
+    const Range in[6] = {{q, tb}, {k, tb}, {v, tb}, {o, tb}, {dout, tb}, {lse, lb}};
+    const Range out[4] = {{dq, tb}, {dk, tb}, {dv, tb}, {workspace, need}};
+    if (any_alias(in, out)) return ULY_ERR_ALIAS;
+    return uly::attn_bwd_launch(q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, N, Hl, d, scale, causal != 0,
+                                uly::strides_for(layout, N, Hl, d), stream);
+}
+
+const char* ulysses_status_string(int status) {
+    switch (status) {
+        case ULY_OK: return "ok";
+        case ULY_ERR_NULL: return "a required pointer is NULL";
+        case ULY_ERR_SHAPE: return "invalid shape (non-positive dimension, H not a multiple of P, or size overflow)";
+        case ULY_ERR_UNSUPPORTED: return "unsupported head dimension, element size or layout";
+        case ULY_ERR_ALIGN: return "pointer is not 16-byte aligned";
+        case ULY_ERR_ALIAS: return "output buffer overlaps an input or another output";
+        case ULY_ERR_WORKSPACE: return "workspace is NULL or too small";
+        case ULY_ERR_LAUNCH: return "HIP kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int ulysses_abi_version(void) { return 1; }
+
+}  // extern "C"

@@ -1,0 +1,36 @@
+// Internal declarations shared by the translation units of libulysses (not part of the ABI).
+#ifndef ULY_INTERNAL_H
+#define ULY_INTERNAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/ulysses.h"
+
+namespace uly {
+
+// A[rows][groups][run_bytes] <-> B[groups][rows][run_bytes] (to_b: dst is B).  Device pointers.
+int regroup(const void* src, void* dst, int64_t rows, int64_t groups, int64_t run_bytes, bool to_b, void* stream);
+
+// Element strides (in bf16 elements) of a [token, head, channel] tensor in either layout.
+struct TensorStrides {
+    int64_t row;    // between consecutive tokens of one head
+    int64_t head;   // between consecutive heads of one token
+};
+
+inline TensorStrides strides_for(int layout, int64_t N, int Hl, int d) {
+    TensorStrides s;
+    if (layout == ULY_LAYOUT_HEAD_SEQ) { s.row = d; s.head = N * (int64_t)d; }
+    else { s.row = (int64_t)Hl * d; s.head = d; }
+    return s;
+}
+
+int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int Hl, int d,
+                    float scale, int causal, TensorStrides st, void* stream);
+
+int attn_bwd_launch(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
+                    void* dq, void* dk, void* dv, float* delta, int64_t N, int Hl, int d, float scale, int causal,
+                    TensorStrides st, void* stream);
+
+}  // namespace uly
+#endif

@@ -1,0 +1,112 @@
+// Layout transforms around the two all-to-alls of a sequence-parallel attention layer
+// (paper Section 3.1): pure, bit-exact data movement, bound by HBM bandwidth.
+//
+// All four transforms (and both output layouts) are one regrouping
+//     A[n][p][w]  <->  B[p][n][w]        n < rows,  p < groups,  w < run
+// where a "run" is the contiguous block that moves as a unit (Hl*d elements for the
+// rank-regrouping, d elements for the head-major layout).  A run is 256 B - 1.8 KB for the
+// shapes of interest, so 16-byte lanes are coalesced on both the read and the write side
+// without staging through LDS: a wavefront covers 1 KiB, i.e. whole runs or large pieces of one.
+// A workgroup takes a block of whole A-rows, so its reads are one contiguous range and its
+// writes are `groups` contiguous ranges.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "internal.h"
+
+namespace uly {
+
+// Exact n / d for n < 2^31 with one 32x32->64 multiply and a shift.
+struct FastDiv {
+    uint32_t mul, shift;
+};
+
+static FastDiv make_fastdiv(uint32_t d) {
+    uint32_t L = 0;
+    while ((1ull << L) < d) ++L;
+    FastDiv f;
+    f.shift = 31 + L;
+    f.mul = (uint32_t)(((1ull << f.shift) / d) + 1);
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv f) {
+    return (uint32_t)(((uint64_t)n * f.mul) >> f.shift);
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 8;
+
+// TO_B = true : dst(B) <- src(A)      TO_B = false : dst(A) <- src(B)
+template <typename Vec, bool TO_B>
+__global__ __launch_bounds__(kThreads) void regroup_kernel(const Vec* __restrict__ src, Vec* __restrict__ dst,
+                                                           int64_t rows, uint32_t row_vecs, uint32_t run_vecs,
+                                                           FastDiv div_row, FastDiv div_run, uint32_t tile_rows) {
+    const int64_t n0 = (int64_t)blockIdx.x * tile_rows;
+    const int64_t rem = rows - n0;
+    const uint32_t my_rows = rem < (int64_t)tile_rows ? (uint32_t)rem : tile_rows;
+    const uint32_t tile_vecs = my_rows * row_vecs;
+    const Vec* a_src = src + n0 * row_vecs;     // used when TO_B
+    Vec* a_dst = dst + n0 * row_vecs;           // used when !TO_B
+
+    for (uint32_t base = threadIdx.x; base < tile_vecs; base += kThreads * kUnroll) {
+        Vec val[kUnroll];
+        int64_t b_idx[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint32_t f = base + u * kThreads;
+            if (f < tile_vecs) {
+                const uint32_t r = fastdiv(f, div_row);
+                const uint32_t w = f - r * row_vecs;
+                const uint32_t p = fastdiv(w, div_run);
+                const uint32_t ww = w - p * run_vecs;
+                b_idx[u] = ((int64_t)p * rows + n0 + r) * run_vecs + ww;
+                val[u] = TO_B ? __builtin_nontemporal_load(a_src + f) : __builtin_nontemporal_load(src + b_idx[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint32_t f = base + u * kThreads;
+            if (f < tile_vecs) {
+                if (TO_B) __builtin_nontemporal_store(val[u], dst + b_idx[u]);
+                else __builtin_nontemporal_store(val[u], a_dst + f);
+            }
+        }
+    }
+}
+
+template <typename Vec>
+static int launch_regroup(const void* src, void* dst, int64_t rows, int64_t groups, int64_t run_bytes, bool to_b,
+                          hipStream_t stream) {
+    const int64_t run_vecs = run_bytes / (int64_t)sizeof(Vec);
+    const int64_t row_vecs = run_vecs * groups;
+    if (row_vecs >= (1ll << 24)) return ULY_ERR_SHAPE;   // keeps every in-tile index far below 2^31
+    uint32_t tile_rows = (uint32_t)(row_vecs >= 2048 ? 1 : 2048 / row_vecs);
+    const int64_t blocks = (rows + tile_rows - 1) / tile_rows;
+    if (blocks <= 0) return ULY_OK;
+    if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
+    const FastDiv div_row = make_fastdiv((uint32_t)row_vecs), div_run = make_fastdiv((uint32_t)run_vecs);
+    if (to_b)
+        regroup_kernel<Vec, true><<<dim3((uint32_t)blocks), dim3(kThreads), 0, stream>>>(
+            (const Vec*)src, (Vec*)dst, rows, (uint32_t)row_vecs, (uint32_t)run_vecs, div_row, div_run, tile_rows);
+    else
+        regroup_kernel<Vec, false><<<dim3((uint32_t)blocks), dim3(kThreads), 0, stream>>>(
+            (const Vec*)src, (Vec*)dst, rows, (uint32_t)row_vecs, (uint32_t)run_vecs, div_row, div_run, tile_rows);
+    return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
+}
+
+// A[rows][groups][run_bytes] <-> B[groups][rows][run_bytes]; to_b selects the direction.
+int regroup(const void* src, void* dst, int64_t rows, int64_t groups, int64_t run_bytes, bool to_b, void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    if (rows == 0 || groups == 0 || run_bytes == 0) return ULY_OK;
+    if (run_bytes % 16 == 0) return launch_regroup<u32x4>(src, dst, rows, groups, run_bytes, to_b, s);
+    if (run_bytes % 8 == 0) return launch_regroup<u32x2>(src, dst, rows, groups, run_bytes, to_b, s);
+    if (run_bytes % 4 == 0) return launch_regroup<uint32_t>(src, dst, rows, groups, run_bytes, to_b, s);
+    if (run_bytes % 2 == 0) return launch_regroup<uint16_t>(src, dst, rows, groups, run_bytes, to_b, s);
+    return launch_regroup<uint8_t>(src, dst, rows, groups, run_bytes, to_b, s);
+}
+
+}  // namespace uly

@@ -1,0 +1,94 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and rejects
+bad arguments before touching the device (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2309_14509_amd as uly
+from paper_2309_14509_amd import build as uly_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if uly_build.is_stale():
+        uly_build.build_library()
+    return uly.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "ulysses.h")).read()
+    declared = set(re.findall(r"\b(ulysses_[a-z_]+)\s*\(", header))
+    assert declared == set(uly.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.ulysses_abi_version() == 1
+
+
+def test_status_strings(lib):
+    seen = {uly.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and uly.status_string(0) == "ok"
+    assert uly.status_string(1234) == "unknown status"
+
+
+A, B, C_, D_ = 0x10000, 0x20000000, 0x40000000, 0x60000000   # fake, aligned, far apart "device" addresses
+
+
+def _pack(lib, x=A, s=B, nl=16, H=8, d=64, P=4, eb=2):
+    return lib.ulysses_pack(x, s, nl, H, d, P, eb, None)
+
+
+def test_layout_validation_happens_before_any_device_call(lib):
+    assert _pack(lib, x=None) == 1 and _pack(lib, s=None) == 1
+    assert _pack(lib, P=3) == 2 and _pack(lib, P=0) == 2 and _pack(lib, nl=-1) == 2 and _pack(lib, d=0) == 2
+    assert _pack(lib, P=16) == 2                       # more ranks than heads
+    assert _pack(lib, eb=3) == 3 and _pack(lib, eb=8) == 3
+    assert _pack(lib, x=A + 2) == 4 and _pack(lib, s=B + 8) == 4
+    assert _pack(lib, s=A) == 5 and _pack(lib, s=A + 16 * 8 * 64 * 2 - 16) == 5
+    assert lib.ulysses_unpack(A, B, 16, 8, 64, 4, 2, 7, None) == 3
+    assert lib.ulysses_pack_rev(A, B, 16, 8, 64, 4, 2, -1, None) == 3
+    assert lib.ulysses_unpack_rev(A, A, 16, 8, 64, 4, 2, None) == 5
+    assert lib.ulysses_pack(A, B, 1 << 61, 8, 64, 4, 2, None) == 2          # size overflow
+
+
+def _fwd(lib, q=A, k=B, v=C_, o=D_, lse=0x7000000, N=128, Hl=2, d=64, scale=0.125, causal=1, layout=0):
+    return lib.ulysses_attn_fwd(q, k, v, o, lse, N, Hl, d, scale, causal, layout, None)
+
+
+def test_attention_forward_validation(lib):
+    assert _fwd(lib, q=None) == 1 and _fwd(lib, lse=None) == 1
+    assert _fwd(lib, N=-5) == 2 and _fwd(lib, Hl=0) == 2 and _fwd(lib, N=1 << 31) == 2
+    assert _fwd(lib, d=96) == 3 and _fwd(lib, layout=2) == 3
+    assert _fwd(lib, scale=0.0) == 3 and _fwd(lib, scale=-1.0) == 3
+    assert _fwd(lib, scale=float("nan")) == 3 and _fwd(lib, scale=float("inf")) == 3
+    assert _fwd(lib, k=B + 4) == 4
+    assert _fwd(lib, o=A) == 5 and _fwd(lib, lse=D_) == 5
+    assert _fwd(lib, N=0) == 0                                               # empty: ok, no launch
+
+
+def test_attention_backward_validation(lib):
+    ws_need = lib.ulysses_attn_bwd_workspace_bytes(128, 2, 64)
+    assert ws_need == 128 * 2 * 4
+    assert lib.ulysses_attn_bwd_workspace_bytes(0, 2, 64) == 0
+    base = dict(q=A, k=B, v=C_, o=D_, dout=0x80000000, lse=0x7000000, dq=0xA0000000, dk=0xC0000000,
+                dv=0xE0000000, ws=0x9000000, wsb=ws_need, N=128, Hl=2, d=64, scale=0.125, causal=1, layout=0)
+
+    def call(**kw):
+        a = dict(base); a.update(kw)
+        return lib.ulysses_attn_bwd(a["q"], a["k"], a["v"], a["o"], a["dout"], a["lse"], a["dq"], a["dk"], a["dv"],
+                                    a["ws"], a["wsb"], a["N"], a["Hl"], a["d"], a["scale"], a["causal"],
+                                    a["layout"], None)
+    assert call(dout=None) == 1 and call(dv=None) == 1
+    assert call(d=32) == 3 and call(scale=-0.5) == 3
+    assert call(ws=None) == 6 and call(wsb=ws_need - 1) == 6
+    assert call(dq=0xA0000008) == 4
+    assert call(dk=A) == 5 and call(dq=0xC0000000) == 5 and call(ws=0x7000000) == 5
+    assert call(N=0, ws=None, wsb=0) == 0
+
+
+def test_binding_refuses_a_missing_library(tmp_path):
+    with pytest.raises(FileNotFoundError):
+        uly.load(str(tmp_path / "nope.so"))

@@ -1,0 +1,140 @@
+"""GPU parity of attention forward/backward against the fp64 oracle, through the C ABI.
+
+Tolerances (bf16 inputs, stated by the target): max-abs 1e-2 on O, relative L2 2e-2 on each of
+dQ, dK, dV.  O is stored in bf16, so where |O| >= 4 half an output ulp (0.0156) already exceeds
+1e-2; there the bound is 0.65 ulp (see _util.o_tolerance).  LSE is fp32 on the GPU: max-abs 2e-3.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as synth
+from _util import f64_of, max_abs, o_within_tolerance, rel_l2, sample_rows, to_gpu_bf16
+
+pytestmark = pytest.mark.gpu
+
+TOL_O, TOL_G, TOL_LSE = 1e-2, 2e-2, 2e-3
+
+
+def _run_gpu(uly, q, k, v, do, scale, causal, layout):
+    tq, tk, tv, tdo = (to_gpu_bf16(a) for a in (q, k, v, do))
+    o, lse = uly.ulysses_attn_fwd(tq, tk, tv, scale, causal, layout)
+    dq, dk, dv = uly.ulysses_attn_bwd(tq, tk, tv, o, tdo, lse, scale, causal, layout)
+    torch.cuda.synchronize()
+    return o, lse, dq, dk, dv
+
+
+def _full_parity(uly, N, Hl, d, causal=True, layout=0, seed=1, mult=1.0, scale=None):
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    q, k, v, do = synth.attention_inputs(N, Hl, d, seed, mult)           # [N,Hl,d]
+    if layout == 1:
+        q, k, v, do = (np.ascontiguousarray(a.transpose(1, 0, 2)) for a in (q, k, v, do))
+    o, lse, dq, dk, dv = _run_gpu(uly, q, k, v, do, scale, causal, layout)
+    fq, fk, fv, fdo = (oracle.bf16_to_f64(a) for a in (q, k, v, do))
+    o_ref, lse_ref = oracle.attn_fwd(fq, fk, fv, scale, causal, layout)
+    dq_ref, dk_ref, dv_ref = oracle.attn_bwd(fq, fk, fv, fdo, scale, causal, layout)
+    ok, worst, n_bad = o_within_tolerance(f64_of(o), o_ref, TOL_O)
+    assert ok, (worst, n_bad)
+    assert max_abs(f64_of(lse), lse_ref) <= TOL_LSE
+    for name, got, ref in (("dq", dq, dq_ref), ("dk", dk, dk_ref), ("dv", dv, dv_ref)):
+        err = rel_l2(f64_of(got), ref)
+        assert err <= TOL_G, (name, err)
+
+
+def test_tiny_config_full(gpu_lib):
+    c = synth.CONFIGS["tiny"]
+    _full_parity(gpu_lib, c["N"], c["H"] // c["P"], c["d"], seed=synth.config_seed("tiny"))
+
+
+@pytest.mark.parametrize("N", [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 200, 257, 333, 700])
+@pytest.mark.parametrize("d", [64, 128])
+def test_ragged_sizes(gpu_lib, N, d):
+    _full_parity(gpu_lib, N, 3, d, seed=N)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("N", [65, 384, 777])
+def test_non_causal(gpu_lib, N, d):
+    _full_parity(gpu_lib, N, 2, d, causal=False, seed=N + 1)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_head_major_layout(gpu_lib, causal):
+    _full_parity(gpu_lib, 300, 3, 128, causal=causal, layout=1, seed=4)
+
+
+def test_wide_logit_range(gpu_lib):
+    """Q, K scaled by 3 (logit sigma about 9): near one-hot rows, exercises the running max."""
+    _full_parity(gpu_lib, 1024, 2, 128, seed=8, mult=3.0)
+
+
+def test_multi_tile_medium(gpu_lib):
+    _full_parity(gpu_lib, 1536, 7, 128, seed=12)
+
+
+def test_backward_is_deterministic(gpu_lib):
+    q, k, v, do = synth.attention_inputs(777, 2, 128, 3)
+    a = _run_gpu(gpu_lib, q, k, v, do, 0.088, True, 0)
+    b = _run_gpu(gpu_lib, q, k, v, do, 0.088, True, 0)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_empty_sequence(gpu_lib):
+    z = torch.empty((0, 2, 64), dtype=torch.bfloat16, device="cuda")
+    o, lse = gpu_lib.ulysses_attn_fwd(z, z.clone(), z.clone(), 0.125)
+    assert o.shape == (0, 2, 64) and lse.shape == (2, 0)
+
+
+@pytest.mark.parametrize("name", ["gpt1.3b", "gpt7b", "gpt30b", "1m"])
+def test_full_size_configs_sampled_rows(gpu_lib, name):
+    """BASELINE shapes at full size, in the launch configuration the benchmark times.
+
+    (A) dense dO: O, LSE and dQ of 64 sampled query rows are exact per-row quantities the oracle
+        computes one by one; the column-sum invariants sum_j dV_j = sum_i dO_i and sum_j dK_j = 0
+        cover every row.
+    (B) dO zeroed outside the sampled rows: the whole dK and dV equal the oracle's row-sampled
+        backward (backward is linear in dO and rows are independent).
+    """
+    c = synth.CONFIGS[name]
+    N, P, d = c["N"], c["P"], c["d"]
+    Hl = c["H"] // P
+    scale = 1.0 / np.sqrt(d)
+    seed = synth.config_seed(name)
+    q, k, v, do = synth.attention_inputs(N, Hl, d, seed, c["qk_mult"])
+    rows = sample_rows(N, 64, P, seed)
+    tq, tk, tv, tdo = (to_gpu_bf16(a) for a in (q, k, v, do))
+    print(f"[{name}] N={N} Hl={Hl} d={d}: forward", flush=True)
+    o, lse = gpu_lib.ulysses_attn_fwd(tq, tk, tv, scale, True)
+    torch.cuda.synchronize()
+    print(f"[{name}] backward (dense dO)", flush=True)
+    dq, dk, dv = gpu_lib.ulysses_attn_bwd(tq, tk, tv, o, tdo, lse, scale, True)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(rows).cuda()
+    o_s, lse_s, dq_s = f64_of(o[idx]), f64_of(lse[:, idx]), f64_of(dq[idx])
+    sum_dv = dv.double().sum(0).cpu().numpy(); sum_dk = dk.double().sum(0).cpu().numpy()
+    sum_do = tdo.double().sum(0).cpu().numpy()
+    dk_rms = float(dk.double().pow(2).mean().sqrt())
+    # (B) masked dO
+    tdo_m = torch.zeros_like(tdo); tdo_m[idx] = tdo[idx]
+    print(f"[{name}] backward (masked dO)", flush=True)
+    _, dk_m, dv_m = gpu_lib.ulysses_attn_bwd(tq, tk, tv, o, tdo_m, lse, scale, True)
+    torch.cuda.synchronize()
+    dk_m, dv_m = f64_of(dk_m), f64_of(dv_m)
+    del tq, tk, tv, tdo, tdo_m, o, lse, dq, dk, dv
+    torch.cuda.empty_cache()
+
+    print(f"[{name}] oracle on {rows.size} rows", flush=True)
+    fq, fk, fv, fdo = (oracle.bf16_to_f64(a) for a in (q, k, v, do))
+    o_ref, lse_ref = oracle.attn_fwd_rows(fq, fk, fv, rows, scale, True)
+    dq_ref, dk_ref, dv_ref = oracle.attn_bwd_rows(fq, fk, fv, fdo, rows, scale, True)
+    ok, worst, n_bad = o_within_tolerance(o_s, o_ref, TOL_O)
+    assert ok, (worst, n_bad)
+    assert max_abs(lse_s, lse_ref) <= TOL_LSE
+    assert rel_l2(dq_s, dq_ref) <= TOL_G
+    assert rel_l2(dk_m, dk_ref) <= TOL_G
+    assert rel_l2(dv_m, dv_ref) <= TOL_G
+    # invariants over all rows (bf16 output rounding: N independent errors of relative size 2^-9)
+    assert rel_l2(sum_dv, sum_do) <= 1e-2
+    assert np.abs(sum_dk).max() <= 0.05 * dk_rms * np.sqrt(N)

@@ -1,0 +1,78 @@
+"""GPU parity of the layout transforms against the oracle: bit-exact, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as synth
+from _util import bits_of, to_gpu_u16
+
+pytestmark = pytest.mark.gpu
+
+# nl, H, d, P  (small enough for the index-loop oracle to finish in seconds)
+SMALL = [
+    (512, 8, 64, 4),        # the tiny config
+    (333, 6, 128, 3),       # ragged rows, non-power-of-two groups
+    (257, 56, 128, 8),      # 7 local heads
+    (1000, 32, 128, 32),    # one local head
+    (77, 4, 8, 2),          # 16-byte runs
+    (5, 6, 4, 3),           # run of 16 bytes with 2 heads
+    (129, 3, 2, 3),         # 4-byte runs: narrow-vector path
+    (64, 5, 1, 5),          # 2-byte runs
+    (1, 1, 64, 1), (3, 16, 64, 1),
+]
+
+
+@pytest.mark.parametrize("nl,H,d,P", SMALL)
+def test_pack_and_unpack_rev_bit_exact(gpu_lib, nl, H, d, P):
+    x = synth.bits_u16((nl, H, d), 99, synth.TID_X)
+    ref = oracle.pack(x, P)
+    got = gpu_lib.ulysses_pack(to_gpu_u16(x), P)
+    assert np.array_equal(bits_of(got), ref)
+    back = gpu_lib.ulysses_unpack_rev(got)
+    assert np.array_equal(bits_of(back), x)
+    assert np.array_equal(bits_of(back), oracle.unpack_rev(ref))
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("nl,H,d,P", SMALL)
+def test_unpack_and_pack_rev_bit_exact(gpu_lib, nl, H, d, P, layout):
+    r = synth.bits_u16((P, nl, H // P, d), 99, synth.TID_R)
+    ref = oracle.unpack(r, layout)
+    got = gpu_lib.ulysses_unpack(to_gpu_u16(r), layout)
+    assert np.array_equal(bits_of(got), ref)
+    back = gpu_lib.ulysses_pack_rev(got, P, layout)
+    assert np.array_equal(bits_of(back), r)
+    assert np.array_equal(bits_of(back), oracle.pack_rev(ref, P, layout))
+
+
+@pytest.mark.parametrize("elem", [torch.uint8, torch.int32])
+def test_other_element_sizes(gpu_lib, elem):
+    nl, H, d, P = 37, 6, 24, 3
+    g = torch.Generator().manual_seed(5)
+    x = torch.randint(0, 127, (nl, H, d), generator=g, dtype=torch.int32).to(elem)
+    got = gpu_lib.ulysses_pack(x.cuda(), P).cpu()
+    ref = x.reshape(nl, P, H // P, d).permute(1, 0, 2, 3)
+    assert torch.equal(got, ref)
+    assert torch.equal(gpu_lib.ulysses_unpack_rev(got.cuda()).cpu(), x)
+
+
+def test_empty_input_is_a_no_op(gpu_lib):
+    x = torch.empty((0, 8, 64), dtype=torch.int16, device="cuda")
+    assert gpu_lib.ulysses_pack(x, 4).shape == (4, 0, 2, 64)
+
+
+@pytest.mark.parametrize("name", ["gpt1.3b", "gpt7b", "gpt30b", "1m"])
+def test_full_size_configs_bit_exact(gpu_lib, name):
+    """Full BASELINE shapes in the launch configuration the benchmark times, whole-tensor compare."""
+    c = synth.CONFIGS[name]
+    nl, H, d, P = c["N"] // c["P"], c["H"], c["d"], c["P"]
+    x = synth.bits_u16((nl, H, d), synth.config_seed(name), synth.TID_X)
+    got = gpu_lib.ulysses_pack(to_gpu_u16(x), P)
+    assert np.array_equal(bits_of(got), oracle.pack(x, P))
+    del got
+    r = synth.bits_u16((P, nl, H // P, d), synth.config_seed(name), synth.TID_R)
+    for layout in (0, 1):
+        got = gpu_lib.ulysses_unpack(to_gpu_u16(r), layout)
+        assert np.array_equal(bits_of(got), oracle.unpack(r, layout))
+        del got
