@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of one GPU's share of Ulysses sequence parallelism on MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+    pack(x_q), pack(x_k), pack(x_v)          [N/P, H, d]      -> P send chunks each
+    unpack(r_q), unpack(r_k), unpack(r_v)    P received chunks -> [N, H/P, d] each   (the exchange itself
+                                                                is not part of this library)
+    attention forward, attention backward over the unpacked q, k, v (causal, batch 1)
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config gpt7b] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="gpt7b", help="workload name from synth_inputs.CONFIGS")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--cpu-rows", type=int, default=640, help="query rows the CPU oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU's share only (no collectives, no second GPU); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2309_14509_amd as uly
+    import synth_inputs as synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    uly.load()     # raises if libulysses.so is not built: there is no fallback path
+    torch.cuda.set_device(0)
+
+    c = synth.CONFIGS[args.config]
+    N, P, H, d = c["N"], c["P"], c["H"], c["d"]
+    nl, Hl = N // P, H // P
+    scale = 1.0 / math.sqrt(d)
+    seed = synth.config_seed(args.config)
+
+    def dev_bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    # ---- synthetic inputs, resident in HBM ---------------------------------------------------
+    # sequence-sharded activations this rank would send (3 tensors: q, k, v projections)
+    xs = [dev_bf16(synth.normal_bf16((nl, H, d), seed, synth.TID_X + 10 * i)) for i in range(3)]
+    # chunks this rank would have received: they ARE q, k, v of the local heads for the full sequence
+    q_bits, k_bits, v_bits, do_bits = synth.attention_inputs(N, Hl, d, seed, c["qk_mult"])
+    recvs = [dev_bf16(b.reshape(P, nl, Hl, d)) for b in (q_bits, k_bits, v_bits)]
+    dout = dev_bf16(do_bits)
+    sends = [torch.empty((P, nl, Hl, d), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    qkv = [torch.empty((N, Hl, d), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    o = torch.empty((N, Hl, d), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((Hl, N), dtype=torch.float32, device="cuda")
+    grads = tuple(torch.empty((N, Hl, d), dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    ws = torch.empty(max(uly.ulysses_attn_bwd_workspace_bytes(N, Hl, d), 16), dtype=torch.uint8, device="cuda")
+
+    lib = uly.load()
+    stream = torch.cuda.current_stream()
+    sp = uly._stream()
+
+    def ptr(t):
+        return t.data_ptr()
+
+    # Events bracket each kernel on the stream the kernels run on (torch's current stream is the one
+    # handed to the library).
+    names = ["pack", "unpack", "attn_fwd", "attn_bwd_delta", "attn_bwd_dkv", "attn_bwd_dq"]
+
+    def step(record=None):
+        def mark():
+            if record is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record(stream)
+                record.append(e)
+        mark()
+        for x, s in zip(xs, sends):
+            uly._check(lib.ulysses_pack(ptr(x), ptr(s), nl, H, d, P, 2, sp), "pack")
+        mark()
+        for r, y in zip(recvs, qkv):
+            uly._check(lib.ulysses_unpack(ptr(r), ptr(y), nl, H, d, P, 2, uly.LAYOUT_SEQ_HEAD, sp), "unpack")
+        mark()
+        uly._check(lib.ulysses_attn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse), N, Hl, d, scale, 1,
+                                        uly.LAYOUT_SEQ_HEAD, sp), "attn_fwd")
+        mark()
+        for stage in (uly.BWD_STAGE_DELTA, uly.BWD_STAGE_DKV, uly.BWD_STAGE_DQ):
+            uly._check(lib.ulysses_attn_bwd_stage(stage, ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(dout),
+                                                  ptr(lse), ptr(grads[0]), ptr(grads[1]), ptr(grads[2]), ptr(ws),
+                                                  ws.numel(), N, Hl, d, scale, 1, uly.LAYOUT_SEQ_HEAD, sp), "attn_bwd")
+            mark()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    per_step_events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev = []
+        step(ev)
+        per_step_events.append(ev)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = wall_ms / args.steps
+
+    seg_ms = {n: 0.0 for n in names}
+    for ev in per_step_events:
+        for i, n in enumerate(names):
+            seg_ms[n] += ev[i].elapsed_time(ev[i + 1])
+    seg_ms = {n: v / args.steps for n, v in seg_ms.items()}
+
+    # ---- algorithmic work -----------------------------------------------------------------------
+    unit = float(N) * N * d * Hl                     # one causal contraction (2 * N^2/2 * d * Hl)
+    flop_fwd, flop_bwd = 2 * unit, 5 * unit          # recomputed contractions do not count
+    attn_ms = seg_ms["attn_fwd"] + seg_ms["attn_bwd_delta"] + seg_ms["attn_bwd_dkv"] + seg_ms["attn_bwd_dq"]
+    tensor_bytes = nl * H * d * 2
+    pack_gbs = 3 * 2 * tensor_bytes / (seg_ms["pack"] * 1e-3) / 1e9
+    unpack_gbs = 3 * 2 * tensor_bytes / (seg_ms["unpack"] * 1e-3) / 1e9
+    # the dominant kernel: dK/dV.  It owns 4 of the backward's 5 algorithmic contractions (S, dP, dV, dK);
+    # the dQ kernel owns 1 (its S and dP are the recomputed ones).
+    dkv_tflops = 4 * unit / (seg_ms["attn_bwd_dkv"] * 1e-3) / 1e12
+    result = {
+        "metric": "attn fwd+bwd TFLOP/s and % bf16 MFMA peak at N=128K shard; pack/unpack GB/s",
+        "value": (flop_fwd + flop_bwd) / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.config}: one GPU's share, N={N} tokens, P={P}, H={H} ({Hl} local heads), "
+                               f"d={d}, batch 1, causal; per step 3x pack + 3x unpack of [{nl},{H},{d}] bf16 and "
+                               "attention fwd+bwd",
+                   "N": N, "P": P, "H": H, "local_heads": Hl, "d": d},
+        "attn_fwd_bwd_tflops": (flop_fwd + flop_bwd) / (attn_ms * 1e-3) / 1e12,
+        "attn_frac_of_mfma_peak": (flop_fwd + flop_bwd) / (attn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "attn_fwd_tflops": flop_fwd / (seg_ms["attn_fwd"] * 1e-3) / 1e12,
+        "attn_bwd_tflops": flop_bwd / ((attn_ms - seg_ms["attn_fwd"]) * 1e-3) / 1e12,
+        "pack_gbs": pack_gbs, "pack_frac_of_hbm_peak": pack_gbs / HBM_PEAK_GBS,
+        "unpack_gbs": unpack_gbs, "unpack_frac_of_hbm_peak": unpack_gbs / HBM_PEAK_GBS,
+        "kernel_ms": seg_ms,
+        "roofline": {"kernel": "attn_bwd_dkv_kernel", "bound": "mfma", "achieved": dkv_tflops,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dkv_tflops / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None},
+    }
+
+    # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = np.unique(np.linspace(0, N - 1, args.cpu_rows).astype(np.int64))
+        fq, fk, fv, fdo = (oracle.bf16_to_f64(b) for b in (q_bits, k_bits, v_bits, do_bits))
+        t0 = time.perf_counter()
+        oracle.attn_fwd_rows(fq, fk, fv, rows, scale, True)
+        oracle.attn_bwd_rows(fq, fk, fv, fdo, rows, scale, True)
+        cpu_s = time.perf_counter() - t0
+        cpu_flop = 14.0 * float((rows + 1).sum()) * d * Hl       # 7 contractions x 2 flop per row/key/channel
+        result["cpu_baseline"] = {
+            "value": cpu_flop / cpu_s / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"fp64 oracle forward+backward on {rows.size} evenly spaced query rows of the same tensors "
+                      f"({cpu_s:.1f} s); flops counted as 14*(i+1)*d*Hl per row i",
+        }
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

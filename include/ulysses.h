@@ -107,6 +107,20 @@ int ulysses_attn_bwd(const void* q, const void* k, const void* v, const void* o,
                      void* workspace, size_t workspace_bytes,
                      int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream);
 
+/* One stage of ulysses_attn_bwd, with the same arguments and the same checks.  Calling stages
+ * ULY_BWD_STAGE_DELTA, ULY_BWD_STAGE_DKV, ULY_BWD_STAGE_DQ in that order on one stream is exactly
+ * ulysses_attn_bwd; they exist so that a caller can time or overlap the kernels separately.
+ *   DELTA: workspace[h, i] = dout_i . o_i   (reads o, dout; writes workspace)
+ *   DKV  : dk, dv                            (reads q, k, v, dout, lse, workspace)
+ *   DQ   : dq                                (reads q, k, v, dout, lse, workspace)
+ * An unknown stage is ULY_ERR_UNSUPPORTED. */
+enum { ULY_BWD_STAGE_DELTA = 0, ULY_BWD_STAGE_DKV = 1, ULY_BWD_STAGE_DQ = 2 };
+int ulysses_attn_bwd_stage(int stage,
+                           const void* q, const void* k, const void* v, const void* o, const void* dout,
+                           const float* lse, void* dq, void* dk, void* dv,
+                           void* workspace, size_t workspace_bytes,
+                           int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream);
+
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* ulysses_status_string(int status);
 

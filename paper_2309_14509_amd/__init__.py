@@ -17,7 +17,7 @@ LAYOUT_SEQ_HEAD = 0   # [N, Hl, d]
 LAYOUT_HEAD_SEQ = 1   # [Hl, N, d]
 
 EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
-           "ulysses_attn_fwd", "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd",
+           "ulysses_attn_fwd", "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd", "ulysses_attn_bwd_stage",
            "ulysses_status_string", "ulysses_abi_version")
 
 _lib = None
@@ -48,10 +48,11 @@ def load(path: str | None = None):
     lib.ulysses_attn_bwd_workspace_bytes.argtypes = [i64, ci, ci]
     lib.ulysses_attn_bwd_workspace_bytes.restype = sz
     lib.ulysses_attn_bwd.argtypes = [vp] * 10 + [sz, i64, ci, ci, cf, ci, ci, vp]
+    lib.ulysses_attn_bwd_stage.argtypes = [ci] + [vp] * 10 + [sz, i64, ci, ci, cf, ci, ci, vp]
     lib.ulysses_status_string.argtypes = [ci]
     lib.ulysses_status_string.restype = ctypes.c_char_p
     for name in ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
-                 "ulysses_attn_fwd", "ulysses_attn_bwd", "ulysses_abi_version"):
+                 "ulysses_attn_fwd", "ulysses_attn_bwd", "ulysses_attn_bwd_stage", "ulysses_abi_version"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -151,18 +152,25 @@ def ulysses_attn_bwd_workspace_bytes(N: int, Hl: int, d: int) -> int:
     return int(load().ulysses_attn_bwd_workspace_bytes(N, Hl, d))
 
 
+BWD_STAGE_DELTA, BWD_STAGE_DKV, BWD_STAGE_DQ = 0, 1, 2
+
+
 def ulysses_attn_bwd(q, k, v, o, dout, lse, scale: float, causal: bool = True, layout: int = LAYOUT_SEQ_HEAD,
-                     workspace=None, out=None):
-    """-> (dq, dk, dv) bf16 in ``layout``."""
+                     workspace=None, out=None, stage=None):
+    """-> (dq, dk, dv) bf16 in ``layout``.  ``stage`` (one of BWD_STAGE_*) runs a single stage of the
+    backward pass through ulysses_attn_bwd_stage; the caller then supplies ``workspace`` and ``out``."""
     import torch
     N, Hl, d = _attn_dims(q, layout)
     need = ulysses_attn_bwd_workspace_bytes(N, Hl, d)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
     dq, dk, dv = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)) if out is None else out
-    _check(load().ulysses_attn_bwd(_dev(q, "attn_bwd"), _dev(k, "attn_bwd"), _dev(v, "attn_bwd"), _dev(o, "attn_bwd"),
-                                   _dev(dout, "attn_bwd"), _dev(lse, "attn_bwd"), _dev(dq, "attn_bwd"),
-                                   _dev(dk, "attn_bwd"), _dev(dv, "attn_bwd"), _dev(workspace, "attn_bwd"),
-                                   workspace.numel() * workspace.element_size(), N, Hl, d, scale, int(causal), layout,
-                                   _stream()), "ulysses_attn_bwd")
+    args = (_dev(q, "attn_bwd"), _dev(k, "attn_bwd"), _dev(v, "attn_bwd"), _dev(o, "attn_bwd"),
+            _dev(dout, "attn_bwd"), _dev(lse, "attn_bwd"), _dev(dq, "attn_bwd"), _dev(dk, "attn_bwd"),
+            _dev(dv, "attn_bwd"), _dev(workspace, "attn_bwd"), workspace.numel() * workspace.element_size(),
+            N, Hl, d, scale, int(causal), layout, _stream())
+    if stage is None:
+        _check(load().ulysses_attn_bwd(*args), "ulysses_attn_bwd")
+    else:
+        _check(load().ulysses_attn_bwd_stage(int(stage), *args), "ulysses_attn_bwd_stage")
     return dq, dk, dv

@@ -124,9 +124,10 @@ size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
     return (size_t)N * (size_t)Hl * sizeof(float);
 }
 
-int ulysses_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
-                     void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int64_t N, int Hl,
-                     int d, float scale, int causal, int layout, void* stream) {
+static int attn_bwd_checked(int stage_mask, const void* q, const void* k, const void* v, const void* o,
+                            const void* dout, const float* lse, void* dq, void* dk, void* dv, void* workspace,
+                            size_t workspace_bytes, int64_t N, int Hl, int d, float scale, int causal, int layout,
+                            void* stream) {
     uint64_t tb;
     const int rc = check_attn_common(N, Hl, d, layout, &tb);
     if (rc != ULY_OK) return rc;
@@ -142,8 +143,24 @@ int ulysses_attn_bwd(const void* q, const void* k, const void* v, const void* o,
     const Range in[6] = {{q, tb}, {k, tb}, {v, tb}, {o, tb}, {dout, tb}, {lse, lb}};
     const Range out[4] = {{dq, tb}, {dk, tb}, {dv, tb}, {workspace, need}};
     if (any_alias(in, out)) return ULY_ERR_ALIAS;
-    return uly::attn_bwd_launch(q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, N, Hl, d, scale, causal != 0,
-                                uly::strides_for(layout, N, Hl, d), stream);
+    return uly::attn_bwd_launch(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, N, Hl, d, scale,
+                                causal != 0, uly::strides_for(layout, N, Hl, d), stream);
+}
+
+int ulysses_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
+                     void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int64_t N, int Hl,
+                     int d, float scale, int causal, int layout, void* stream) {
+    return attn_bwd_checked(7, q, k, v, o, dout, lse, dq, dk, dv, workspace, workspace_bytes, N, Hl, d, scale,
+                            causal, layout, stream);
+}
+
+int ulysses_attn_bwd_stage(int stage, const void* q, const void* k, const void* v, const void* o, const void* dout,
+                           const float* lse, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                           int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream) {
+    if (stage != ULY_BWD_STAGE_DELTA && stage != ULY_BWD_STAGE_DKV && stage != ULY_BWD_STAGE_DQ)
+        return ULY_ERR_UNSUPPORTED;
+    return attn_bwd_checked(1 << stage, q, k, v, o, dout, lse, dq, dk, dv, workspace, workspace_bytes, N, Hl, d,
+                            scale, causal, layout, stream);
 }
 
 const char* ulysses_status_string(int status) {

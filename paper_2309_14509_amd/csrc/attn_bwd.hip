@@ -299,42 +299,50 @@ __global__ __launch_bounds__(kBwdThreads, 1) void attn_bwd_dkv_kernel(
 }
 
 template <int D>
-static int launch_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
-                      void* dq, void* dk, void* dv, float* delta, int64_t N, int Hl, float scale, int causal,
-                      TensorStrides st, hipStream_t stream) {
+static int launch_bwd(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
+                      const float* lse, void* dq, void* dk, void* dv, float* delta, int64_t N, int Hl, float scale,
+                      int causal, TensorStrides st, hipStream_t stream) {
     const int64_t pairs = N * Hl;
     const int64_t delta_blocks = (pairs * (D / 8) + 255) / 256;
     const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (N + kDkvBK - 1) / kDkvBK;
     if (delta_blocks > 0x7FFFFFFFll || n_qtiles * Hl > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     const bf16 *Q = (const bf16*)q, *K = (const bf16*)k, *V = (const bf16*)v, *dO = (const bf16*)dout;
+    const dim3 gkv((uint32_t)(n_ktiles * Hl)), gq((uint32_t)(n_qtiles * Hl)), block(kBwdThreads);
 
-    attn_bwd_delta_kernel<D><<<dim3((uint32_t)delta_blocks), dim3(256), 0, stream>>>((const bf16*)o, dO, delta, (int)N,
-                                                                                     Hl, st.row, st.head);
-    if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
-
-    dim3 gkv((uint32_t)(n_ktiles * Hl)), gq((uint32_t)(n_qtiles * Hl)), block(kBwdThreads);
-    if (causal) {
-        attn_bwd_dkv_kernel<D, true><<<gkv, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dk, (bf16*)dv, (int)N,
-                                                                (int)n_ktiles, st.row, st.head, scale);
+    if (stage_mask & 1) {
+        attn_bwd_delta_kernel<D><<<dim3((uint32_t)delta_blocks), dim3(256), 0, stream>>>((const bf16*)o, dO, delta,
+                                                                                         (int)N, Hl, st.row, st.head);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
-        attn_bwd_dq_kernel<D, true><<<gq, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dq, (int)N, (int)n_qtiles,
-                                                              st.row, st.head, scale);
-    } else {
-        attn_bwd_dkv_kernel<D, false><<<gkv, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dk, (bf16*)dv, (int)N,
-                                                                 (int)n_ktiles, st.row, st.head, scale);
-        if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
-        attn_bwd_dq_kernel<D, false><<<gq, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dq, (int)N,
-                                                               (int)n_qtiles, st.row, st.head, scale);
     }
-    return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
+    if (stage_mask & 2) {
+        if (causal)
+            attn_bwd_dkv_kernel<D, true><<<gkv, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dk, (bf16*)dv,
+                                                                    (int)N, (int)n_ktiles, st.row, st.head, scale);
+        else
+            attn_bwd_dkv_kernel<D, false><<<gkv, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dk, (bf16*)dv,
+                                                                     (int)N, (int)n_ktiles, st.row, st.head, scale);
+        if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+    }
+    if (stage_mask & 4) {
+        if (causal)
+            attn_bwd_dq_kernel<D, true><<<gq, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dq, (int)N,
+                                                                  (int)n_qtiles, st.row, st.head, scale);
+        else
+            attn_bwd_dq_kernel<D, false><<<gq, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dq, (int)N,
+                                                                   (int)n_qtiles, st.row, st.head, scale);
+        if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+    }
+    return ULY_OK;
 }
 
-int attn_bwd_launch(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
-                    void* dq, void* dk, void* dv, float* delta, int64_t N, int Hl, int d, float scale, int causal,
-                    TensorStrides st, void* stream) {
+int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
+                    const float* lse, void* dq, void* dk, void* dv, float* delta, int64_t N, int Hl, int d,
+                    float scale, int causal, TensorStrides st, void* stream) {
     if (d == 128)
-        return launch_bwd<128>(q, k, v, o, dout, lse, dq, dk, dv, delta, N, Hl, scale, causal, st, (hipStream_t)stream);
-    return launch_bwd<64>(q, k, v, o, dout, lse, dq, dk, dv, delta, N, Hl, scale, causal, st, (hipStream_t)stream);
+        return launch_bwd<128>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, delta, N, Hl, scale, causal, st,
+                               (hipStream_t)stream);
+    return launch_bwd<64>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, delta, N, Hl, scale, causal, st,
+                          (hipStream_t)stream);
 }
 
 }  // namespace uly
