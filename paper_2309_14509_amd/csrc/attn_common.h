@@ -45,6 +45,7 @@ __device__ __forceinline__ bf16x4 lds_read_tr4(const bf16* p) {
     return __builtin_bit_cast(bf16x4, t);
 }
 
+// (padded-tile variant, kept for tiles staged through registers)
 // A-operand (32 rows x 16 contraction) of the transpose of a row-major LDS tile:
 // rows of the operand are tile COLUMNS col0 + (l%32), contraction runs over tile ROWS
 //   row0 + 8*(e/4) + 4g + (e%4),  e = 0..7
@@ -94,6 +95,79 @@ __device__ __forceinline__ float xhalf_sum(float x) {
 
 // C/D row index of register r for lane-half g.
 __device__ __forceinline__ int crow(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
+
+// ------------------------------------------------------------------------------------------
+// LDS tiles filled straight from global memory (global_load_lds_dwordx4: no VGPR staging).
+//
+// A tile is ROWS x D bf16, rows unpadded (D*2 bytes); the 16-byte chunk c of row r is stored at
+// chunk position c ^ swz(r).  One wave-wide load writes 1 KiB of consecutive LDS (lane L -> byte
+// 16*L), so the swizzle is applied by choosing which global chunk each lane fetches.  swz is
+// chosen so that both access patterns are bank-conflict free:
+//   row reads  (16 lanes = 16 consecutive rows, same logical chunk)       -> 16 distinct chunks
+//   transposing reads (16 lanes = 4 consecutive rows x 2 chunks)            -> 8 distinct chunks
+// It only depends on r mod 16, so tile-row offsets that are multiples of 16 are plain immediates.
+// ------------------------------------------------------------------------------------------
+template <int D> __device__ __forceinline__ int swz(int r);
+template <> __device__ __forceinline__ int swz<128>(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+template <> __device__ __forceinline__ int swz<64>(int r) {
+    const int i = (r >> 1) & 7;
+    return (i & 4) | ((i & 1) << 1) | ((i >> 1) & 1);
+}
+
+// element offset of (row r, logical chunk c) inside a swizzled tile
+template <int D> __device__ __forceinline__ int tile_off(int r, int c) { return r * D + ((c ^ swz<D>(r)) << 3); }
+
+template <int D, int ROWS, int WAVES> struct DirectTile {
+    static constexpr int kChunksPerRow = D / 8;
+    static constexpr int kRowsPerSlab = 64 / kChunksPerRow;          // rows written by one wave-wide load
+    static constexpr int kSlabs = ROWS / kRowsPerSlab;
+    static constexpr int kPerWave = kSlabs / WAVES;
+    static_assert(kSlabs % WAVES == 0, "tile must divide evenly over the waves");
+
+    // Per-lane byte offsets (from the first row of a tile) of the chunks this lane fetches: they do
+    // not change from tile to tile, so a tile load is a uniform base plus these.
+    struct LaneOffsets {
+        uint32_t off[kPerWave];
+    };
+    __device__ static __forceinline__ LaneOffsets lane_offsets(int64_t row_stride, int wave, int lane) {
+        LaneOffsets lo;
+        const int lr = lane / kChunksPerRow, pc = lane % kChunksPerRow;
+#pragma unroll
+        for (int i = 0; i < kPerWave; ++i) {
+            const int r = (wave + i * WAVES) * kRowsPerSlab + lr;    // row inside the tile
+            lo.off[i] = (uint32_t)(r * row_stride * 2) + (uint32_t)(((pc ^ swz<D>(r)) << 4));
+        }
+        return lo;
+    }
+    // Issue this wave's loads of a full tile whose first row is at `tile_base` (all rows valid).
+    __device__ static __forceinline__ void issue(bf16* tile, const bf16* tile_base, const LaneOffsets& lo, int wave) {
+#pragma unroll
+        for (int i = 0; i < kPerWave; ++i) {
+            const char* src = reinterpret_cast<const char*>(tile_base) + lo.off[i];
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             ULY_LDS(void, tile + (wave + i * WAVES) * kRowsPerSlab * D), 16, 0, 0);
+        }
+    }
+    // Same for a tile that may run past the end of the tensor: rows at or beyond n_rows are clamped
+    // to the last valid row (callers mask them out).
+    __device__ static __forceinline__ void issue_clamped(bf16* tile, const bf16* base, int64_t row_stride, int row0,
+                                                         int n_rows, int wave, int lane) {
+        const int lr = lane / kChunksPerRow, pc = lane % kChunksPerRow;
+#pragma unroll
+        for (int i = 0; i < kPerWave; ++i) {
+            const int slab = wave + i * WAVES;
+            const int r = slab * kRowsPerSlab + lr;
+            int gr = row0 + r;
+            gr = gr < n_rows ? gr : n_rows - 1;
+            const bf16* src = base + (int64_t)gr * row_stride + ((pc ^ swz<D>(r)) << 3);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             ULY_LDS(void, tile + slab * kRowsPerSlab * D), 16, 0, 0);
+        }
+    }
+};
+
+// Wait until every direct-to-LDS load this wave has issued has landed.
+__device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // LDS row strides (elements).  Row reads (16 B per lane, 16 lanes of consecutive rows per bank
 // pass) want stride/4B = 4 mod 8 banks; transposing reads (4 rows x 64 B per 32 lanes) want
