@@ -113,37 +113,53 @@ template <> __device__ __forceinline__ int swz<64>(int r) {
     const int i = (r >> 1) & 7;
     return (i & 4) | ((i & 1) << 1) | ((i >> 1) & 1);
 }
+// Swizzle for tiles that are only read through transposing reads: it depends on r mod 4 (D = 128) or
+// r mod 8 (D = 64) only, so rows 8 apart sit a constant distance apart and one address register
+// serves both 4-row groups of a transposing operand.
+template <int D> __device__ __forceinline__ int swz_tr(int r);
+template <> __device__ __forceinline__ int swz_tr<128>(int r) { return (r & 3) << 2; }
+template <> __device__ __forceinline__ int swz_tr<64>(int r) { return ((r >> 1) & 1) << 1; }
+
+struct SwzBoth {
+    template <int D> __device__ static __forceinline__ int f(int r) { return swz<D>(r); }
+};
+struct SwzTr {
+    template <int D> __device__ static __forceinline__ int f(int r) { return swz_tr<D>(r); }
+};
 
 // element offset of (row r, logical chunk c) inside a swizzled tile
-template <int D> __device__ __forceinline__ int tile_off(int r, int c) { return r * D + ((c ^ swz<D>(r)) << 3); }
+template <int D, typename S = SwzBoth> __device__ __forceinline__ int tile_off(int r, int c) {
+    return r * D + ((c ^ S::template f<D>(r)) << 3);
+}
 
-template <int D, int ROWS, int WAVES> struct DirectTile {
+template <int D, int ROWS, int WAVES, typename S = SwzBoth> struct DirectTile {
     static constexpr int kChunksPerRow = D / 8;
     static constexpr int kRowsPerSlab = 64 / kChunksPerRow;          // rows written by one wave-wide load
     static constexpr int kSlabs = ROWS / kRowsPerSlab;
     static constexpr int kPerWave = kSlabs / WAVES;
     static_assert(kSlabs % WAVES == 0, "tile must divide evenly over the waves");
 
-    // Per-lane byte offsets (from the first row of a tile) of the chunks this lane fetches: they do
-    // not change from tile to tile, so a tile load is a uniform base plus these.
+    // Per-lane byte offset (from the first row of a tile) of the chunk this lane fetches in its first
+    // load; the wave's further loads are WAVES*kRowsPerSlab rows (a multiple of 16, so the same
+    // swizzle) further down, a uniform step.  Neither changes from tile to tile.
     struct LaneOffsets {
-        uint32_t off[kPerWave];
+        uint32_t off0;
+        int64_t step_bytes;
     };
+    static_assert((WAVES * kRowsPerSlab) % 16 == 0, "loads of one wave must share their swizzle");
     __device__ static __forceinline__ LaneOffsets lane_offsets(int64_t row_stride, int wave, int lane) {
         LaneOffsets lo;
         const int lr = lane / kChunksPerRow, pc = lane % kChunksPerRow;
-#pragma unroll
-        for (int i = 0; i < kPerWave; ++i) {
-            const int r = (wave + i * WAVES) * kRowsPerSlab + lr;    // row inside the tile
-            lo.off[i] = (uint32_t)(r * row_stride * 2) + (uint32_t)(((pc ^ swz<D>(r)) << 4));
-        }
+        const int r = wave * kRowsPerSlab + lr;                      // row inside the tile
+        lo.off0 = (uint32_t)(r * row_stride * 2) + (uint32_t)(((pc ^ S::template f<D>(r)) << 4));
+        lo.step_bytes = (int64_t)WAVES * kRowsPerSlab * row_stride * 2;
         return lo;
     }
     // Issue this wave's loads of a full tile whose first row is at `tile_base` (all rows valid).
     __device__ static __forceinline__ void issue(bf16* tile, const bf16* tile_base, const LaneOffsets& lo, int wave) {
 #pragma unroll
         for (int i = 0; i < kPerWave; ++i) {
-            const char* src = reinterpret_cast<const char*>(tile_base) + lo.off[i];
+            const char* src = reinterpret_cast<const char*>(tile_base) + i * lo.step_bytes + lo.off0;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              ULY_LDS(void, tile + (wave + i * WAVES) * kRowsPerSlab * D), 16, 0, 0);
         }
@@ -152,6 +168,9 @@ template <int D, int ROWS, int WAVES> struct DirectTile {
     // to the last valid row (callers mask them out).
     __device__ static __forceinline__ void issue_clamped(bf16* tile, const bf16* base, int64_t row_stride, int row0,
                                                          int n_rows, int wave, int lane) {
+        // This path runs at most once per workgroup.  The lane id is made opaque here so that none of
+        // its address arithmetic is hoisted out of the caller's loop (where it would pin ~30 VGPRs).
+        asm volatile("" : "+v"(lane));
         const int lr = lane / kChunksPerRow, pc = lane % kChunksPerRow;
 #pragma unroll
         for (int i = 0; i < kPerWave; ++i) {
@@ -159,12 +178,46 @@ template <int D, int ROWS, int WAVES> struct DirectTile {
             const int r = slab * kRowsPerSlab + lr;
             int gr = row0 + r;
             gr = gr < n_rows ? gr : n_rows - 1;
-            const bf16* src = base + (int64_t)gr * row_stride + ((pc ^ swz<D>(r)) << 3);
+            const bf16* src = base + (int64_t)gr * row_stride + ((pc ^ S::template f<D>(r)) << 3);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              ULY_LDS(void, tile + slab * kRowsPerSlab * D), 16, 0, 0);
         }
     }
 };
+
+// ------------------------------------------------------------------------------------------
+// Hand-placed LDS reads.  The hot loops issue their operand reads a full phase before the MFMAs that
+// consume them; the reads are inline asm (per-lane byte address + immediate) so that their position
+// in the instruction stream is fixed and each address costs no VALU work.  The compiler does not
+// count these in lgkmcnt, so every consumer is preceded by lds_wait<N>(regs...), which both waits
+// and ties the registers to the wait (nothing that uses them can be scheduled above it).
+// ------------------------------------------------------------------------------------------
+template <int IMM> __device__ __forceinline__ bf16x8 lds_b128(uint32_t addr) {
+    bf16x8 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(IMM));
+    return r;
+}
+template <int IMM> __device__ __forceinline__ bf16x4 lds_tr_b64(uint32_t addr) {
+    bf16x4 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(IMM));
+    return r;
+}
+template <int N> __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b, bf16x8& c, bf16x8& d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+template <int N> __device__ __forceinline__ void lds_wait(bf16x4& a, bf16x4& b, bf16x4& c, bf16x4& d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+template <int N> __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+template <int N> __device__ __forceinline__ void lds_wait(bf16x4& a, bf16x4& b) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+// byte address of an LDS object as the hardware sees it
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)ULY_LDS(const char, p);
+}
 
 // Wait until every direct-to-LDS load this wave has issued has landed.
 __device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }

@@ -12,38 +12,47 @@
 // (no VGPR staging); one barrier per tile.  The rescale of the output accumulator is skipped for
 // every tile in which no row of the wave sees a new maximum (most tiles of a long sequence); the
 // reference maximum of a row is always its exact running maximum, so its largest weight is exactly 1.
+#include <type_traits>
+
 #include "attn_common.h"
 #include "internal.h"
 
 namespace uly {
 
-constexpr int kFwdThreads = 256;
-constexpr int kFwdWaves = 4;
-constexpr int kFwdBQ = 128;   // queries per workgroup
+constexpr int kFwdThreads = 512;
+constexpr int kFwdWaves = 8;
+constexpr int kFwdBQ = 256;   // queries per workgroup
 constexpr int kFwdBK = 64;    // keys per LDS tile
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(kFwdThreads, 2) void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+__global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                                    const bf16* __restrict__ V, bf16* __restrict__ O,
                                                                    float* __restrict__ LSE, int N, int n_qtiles,
                                                                    int64_t row_stride, int64_t head_stride,
                                                                    float scale) {
-    constexpr int NT = D / 16;          // contraction steps over the head dim
-    constexpr int NKB = kFwdBK / 32;    // 32-key blocks per tile
-    constexpr int NCB = D / 32;         // 32-channel blocks of the output
-    constexpr int TILE = kFwdBK * D;    // elements per LDS tile
-    using Loader = DirectTile<D, kFwdBK, kFwdWaves>;
+    constexpr int NT = D / 16;              // contraction steps over the head dim
+    constexpr int NCB = D / 32;             // 32-channel blocks of the output
+    constexpr int TILE = kFwdBK * D;        // elements per LDS tile
+    constexpr int TB = TILE * 2;            // bytes per LDS tile
+    constexpr int BLK = 32 * D * 2;         // bytes per 32-key block inside a tile
+    constexpr int HALF = 16 * D * 2;        // bytes per 16 keys
+    // byte offsets of the four tile buffers inside one LDS object: K0 K1 V0 V1
+    constexpr int K0 = 0, K1 = TB, V0 = 2 * TB, V1 = 3 * TB;
+    using KLoader = DirectTile<D, kFwdBK, kFwdWaves, SwzBoth>;     // K: row reads
+    using VLoader = DirectTile<D, kFwdBK, kFwdWaves, SwzTr>;       // V: transposing reads only
 
-    // two buffers per tensor, as separate objects so that reads of one are known not to touch the other
-    __shared__ __attribute__((aligned(1024))) bf16 k_lds0[TILE];
-    __shared__ __attribute__((aligned(1024))) bf16 k_lds1[TILE];
-    __shared__ __attribute__((aligned(1024))) bf16 v_lds0[TILE];
-    __shared__ __attribute__((aligned(1024))) bf16 v_lds1[TILE];
+    // The last NQL of the NT query operand chunks live in LDS instead of registers (the kernel is a few
+    // registers short of keeping all of Q, the O accumulators and one block of operands resident).
+    constexpr int NQL = (D == 128) ? 2 : 0;
+    constexpr int NQR = NT - NQL;
+    constexpr int QROW = NQL * 32 + 16;      // bytes per query row in LDS, padded: conflict-free row reads
+    __shared__ __attribute__((aligned(1024))) bf16 smem[4 * TILE];
+    __shared__ __attribute__((aligned(16))) char q_lds[NQL ? kFwdBQ * QROW : 16];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ln = lane & 31;
     // head-major order, heaviest (last) query tile of a head first
     const int head = blockIdx.x / n_qtiles;
-    const int qt = n_qtiles - 1 - (blockIdx.x - head * n_qtiles);
+    const int qt = CAUSAL ? n_qtiles - 1 - (blockIdx.x - head * n_qtiles) : blockIdx.x - head * n_qtiles;
     const int q0 = qt * kFwdBQ;
     const int64_t hoff = (int64_t)head * head_stride;
     const bf16* Qh = Q + hoff;
@@ -54,34 +63,49 @@ __global__ __launch_bounds__(kFwdThreads, 2) void attn_fwd_kernel(const bf16* __
     if (CAUSAL) { const int lim = q0 + kFwdBQ; k_end = lim < N ? lim : N; }
     const int n_kt = (k_end + kFwdBK - 1) / kFwdBK;
 
-    const typename Loader::LaneOffsets ld_off = Loader::lane_offsets(row_stride, wave, lane);
-    Loader::issue_clamped(k_lds0, Kh, row_stride, 0, N, wave, lane);
-    Loader::issue_clamped(v_lds0, Vh, row_stride, 0, N, wave, lane);
+    const typename KLoader::LaneOffsets k_ld = KLoader::lane_offsets(row_stride, wave, lane);
+    const typename VLoader::LaneOffsets v_ld = VLoader::lane_offsets(row_stride, wave, lane);
+    auto load_tile = [&](int kbuf, int vbuf, int kt) __attribute__((always_inline)) {     // buffer byte offsets
+        const int r0 = kt * kFwdBK;
+        if (r0 + kFwdBK <= N) {
+            KLoader::issue(smem + kbuf / 2, Kh + (int64_t)r0 * row_stride, k_ld, wave);
+            VLoader::issue(smem + vbuf / 2, Vh + (int64_t)r0 * row_stride, v_ld, wave);
+        } else {
+            KLoader::issue_clamped(smem + kbuf / 2, Kh, row_stride, r0, N, wave, lane);
+            VLoader::issue_clamped(smem + vbuf / 2, Vh, row_stride, r0, N, wave, lane);
+        }
+    };
+    load_tile(K0, V0, 0);
+    if (n_kt > 1) load_tile(K1, V1, 1);
 
     const int q_row = q0 + wave * 32 + ln;                     // this lane's query
     const int q_ld = q_row < N ? q_row : N - 1;
-    bf16x8 qreg[NT];
+    bf16x8 qreg[NQR];
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int t = 0; t < NQR; ++t)
         qreg[t] = *reinterpret_cast<const bf16x8*>(Qh + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
-
-    // per-lane LDS element offsets (tile-row offsets that are multiples of 16 are added as immediates)
-    int k_off[NT];                      // row read of K: row ln, chunk 2t+g
+    const uint32_t q_adr = lds_addr(q_lds) + (wave * 32 + ln) * QROW + g * 16;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) k_off[t] = tile_off<D>(ln, 2 * t + g);
-    int v_off[NCB][2];                  // transposing read of V: rows 4g+(i>>2) (+8), channels 32cb+16h+4(i&3)
+    for (int t = NQR; t < NT; ++t)      // only this wave reads these rows back: no barrier needed
+        *reinterpret_cast<bf16x8*>(q_lds + (wave * 32 + ln) * QROW + (2 * (t - NQR) + g) * 16) =
+            *reinterpret_cast<const bf16x8*>(Qh + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
+
+    // per-lane LDS byte addresses inside a tile (buffer, block and half-block offsets are immediates)
+    const uint32_t sbase = lds_addr(smem);
+    uint32_t k_adr[NT];                 // row read of K: row ln, chunk 2t+g
+#pragma unroll
+    for (int t = 0; t < NT; ++t) k_adr[t] = sbase + 2 * tile_off<D>(ln, 2 * t + g);
+    uint32_t v_adr[NCB];                // transposing read of V: rows 4g+(i>>2) (+8: immediate), channels 32cb+16h+4(i&3)
     {
         const int i = lane & 15, h = (lane >> 4) & 1;
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh)
-                v_off[cb][hh] = tile_off<D>(4 * g + (i >> 2) + 8 * hh, 4 * cb + 2 * h + ((i & 3) >> 1)) + 4 * (i & 1);
+            v_adr[cb] = sbase + 2 * (tile_off<D, SwzTr>(4 * g + (i >> 2), 4 * cb + 2 * h + ((i & 3) >> 1)) + 4 * (i & 1));
     }
+    constexpr int ROW8 = 8 * D * 2;     // bytes between the two 4-row groups of a transposing operand
 
     const float sl2 = scale * kLog2e;
     float m_used = -INFINITY;    // reference maximum (raw logits) that the exponentials are taken against
-    float ms = 0.f;              // m_used * sl2 (0 while m_used is -inf)
     float l_run = 0.f;           // this lane's share of the running sum
     f32x16 oacc[NCB];
 #pragma unroll
@@ -89,123 +113,175 @@ __global__ __launch_bounds__(kFwdThreads, 2) void attn_fwd_kernel(const bf16* __
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
 
-    const int wave_qmin = q0 + wave * 32;
+    // K operands of one 32-key block.  The first half is read one phase ahead (during the PV MFMAs of
+    // the previous block), the second half at the start of the block itself, behind the first half's
+    // MFMAs: only half of them are live while the register pressure peaks.
+    bf16x8 ka[NT];
+    auto read_k = [&](auto off_tag, auto half_tag) __attribute__((always_inline)) {
+        constexpr int OFF = decltype(off_tag)::value;
+        constexpr int H = decltype(half_tag)::value;
+#pragma unroll
+        for (int t = H * (NT / 2); t < (H + 1) * (NT / 2); ++t) ka[t] = lds_b128<OFF>(k_adr[t]);
+    };
+    auto wait_k = [&](auto half_tag) __attribute__((always_inline)) {
+        constexpr int H = decltype(half_tag)::value;
+        if constexpr (NT / 2 == 4) {
+            lds_wait<0>(ka[4 * H], ka[4 * H + 1], ka[4 * H + 2], ka[4 * H + 3]);
+        } else {
+            lds_wait<0>(ka[2 * H], ka[2 * H + 1]);
+        }
+    };
+    using First = std::integral_constant<int, 0>;
+    using Second = std::integral_constant<int, 1>;
 
-    wait_direct_loads();
+    // tile 0 was issued first: wait for it alone (the loads of tile 1 may still be in flight)
+    if (n_kt > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * KLoader::kPerWave) : "memory");
+    else wait_direct_loads();
     __syncthreads();
+    read_k(std::integral_constant<int, K0>{}, First{});
 
-    auto do_tile = [&](const bf16* kt_lds, const bf16* vt_lds, bf16* kn_lds, bf16* vn_lds, int kt)
-                       __attribute__((always_inline)) {
-        const int k0 = kt * kFwdBK;
-        if (kt + 1 < n_kt) {                 // next tile -> the other buffer (everyone left it at the last barrier)
-            const int kn = k0 + kFwdBK;
-            if (kn + kFwdBK <= N) {
-                Loader::issue(kn_lds, Kh + (int64_t)kn * row_stride, ld_off, wave);
-                Loader::issue(vn_lds, Vh + (int64_t)kn * row_stride, ld_off, wave);
-            } else {
-                Loader::issue_clamped(kn_lds, Kh, row_stride, kn, N, wave, lane);
-                Loader::issue_clamped(vn_lds, Vh, row_stride, kn, N, wave, lane);
+    // One 32-key block: S^T (K operands already on their way) -> read V of the first 16 keys -> softmax
+    // -> read the next block's K -> PV of the first 16 keys -> read V of the last 16 keys -> PV of those.
+    // In the last block of a tile the barrier, the loads of tile kt+2 and the K reads of tile kt+1 sit
+    // just before the last PV: by then every wave has finished reading this tile's buffers.
+    auto do_block = [&](auto masked_tag, auto kb_tag, auto vb_tag, auto kn_tag, auto kfree_tag, auto vfree_tag, int kb0,
+                        int kt)
+                        __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        constexpr int VB = decltype(vb_tag)::value;        // this block's V rows
+        constexpr int KN = decltype(kn_tag)::value;        // next block's K rows
+        constexpr int KFREE = decltype(kfree_tag)::value;  // >= 0: last block of a tile; buffers to refill
+        constexpr int VFREE = decltype(vfree_tag)::value;
+        constexpr bool LAST = KFREE >= 0;
+
+        wait_k(First{});
+        read_k(kb_tag, Second{});
+        bf16x8 ql[NQL ? NQL : 1];
+        if constexpr (NQL == 2) {
+            ql[0] = lds_b128<0>(q_adr);
+            ql[1] = lds_b128<32>(q_adr);
+        }
+        f32x16 s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int t = 0; t < NT / 2; ++t) s = mfma32(ka[t], qreg[t], s);
+        wait_k(Second{});
+        if constexpr (NQL == 2) lds_wait<0>(ql[0], ql[1]);
+#pragma unroll
+        for (int t = NT / 2; t < NT; ++t) s = mfma32(ka[t], t < NQR ? qreg[t < NQR ? t : 0] : ql[t >= NQR ? t - NQR : 0], s);
+        __builtin_amdgcn_sched_barrier(0);      // the reads below reuse ka: keep them behind the MFMAs
+
+        // V operands of the first 16 keys: they arrive during the softmax
+        bf16x4 vlo[NCB], vhi[NCB];
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            vlo[cb] = lds_tr_b64<VB>(v_adr[cb]);
+            vhi[cb] = lds_tr_b64<VB + ROW8>(v_adr[cb]);
+        }
+
+        if (MASKED) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int j = kb0 + crow(r, g);
+                if ((CAUSAL && j > q_row) || j >= N) s[r] = -INFINITY;
             }
         }
-        // A wave whose queries all precede this tile has nothing to do (only in diagonal tiles).
-        if (!(CAUSAL && k0 > wave_qmin + 31)) {
-            // ---- S^T = K Q^T
-            f32x16 s[NKB];
+        // online softmax; the rescale runs only when some row of this wave has a new maximum
+        float m_blk = s[0];
 #pragma unroll
-            for (int b = 0; b < NKB; ++b)
+        for (int r = 1; r < 16; ++r) m_blk = fmaxf(m_blk, s[r]);
+        m_blk = xhalf_max(m_blk);
+        if (__builtin_amdgcn_ballot_w64(m_blk > m_used) != 0) {      // always taken on the first block
+            const float m_new = fmaxf(m_used, m_blk);
+            const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;  // a row with nothing visible yet
+            const float alpha = fast_exp2((m_used - m_fin) * sl2);
+            l_run *= alpha;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[b][r] = 0.f;
+            for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int b = 0; b < NKB; ++b)
-                    s[b] = mfma32(lds_read_row8(kt_lds + k_off[t] + 32 * b * D), qreg[t], s[b]);
-
-            // ---- mask (diagonal tiles and the ragged last tile only)
-            const bool need_mask = (CAUSAL && k0 + kFwdBK - 1 > wave_qmin) || (k0 + kFwdBK > N);
-            if (need_mask) {
-#pragma unroll
-                for (int b = 0; b < NKB; ++b)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int j = k0 + 32 * b + crow(r, g);
-                        if ((CAUSAL && j > q_row) || j >= N) s[b][r] = -INFINITY;
-                    }
-            }
-            // ---- online softmax; the rescale runs only when some row of this wave has a new maximum
-            float m_tile = s[0][0];
-#pragma unroll
-            for (int b = 0; b < NKB; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) m_tile = fmaxf(m_tile, s[b][r]);
-            m_tile = xhalf_max(m_tile);
-            const bool advance = m_tile > m_used;      // always true on the first tile (m_used = -inf)
-            if (__builtin_amdgcn_ballot_w64(advance) != 0) {
-                const float m_new = fmaxf(m_used, m_tile);
-                const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;          // padding rows only
-                const float alpha = fast_exp2((m_used - m_fin) * sl2);
-                l_run *= alpha;
-#pragma unroll
-                for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
-                m_used = m_new;
-                ms = m_fin * sl2;
-            }
-            float rs[4] = {0.f, 0.f, 0.f, 0.f};          // four chains instead of one 32-deep add chain
-#pragma unroll
-            for (int b = 0; b < NKB; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float p = fast_exp2(__builtin_fmaf(s[b][r], sl2, -ms));
-                    s[b][r] = p;
-                    rs[r & 3] += p;
-                }
-            l_run += (rs[0] + rs[1]) + (rs[2] + rs[3]);
-
-            // ---- O^T += V^T P^T
-            // Rows with few visible keys are where |O| is largest and where bf16 rounding of P would be
-            // the dominant error, so the diagonal tiles carry P in two bf16 pieces (P = hi + lo).
-            if (need_mask) {
-#pragma unroll
-                for (int b = 0; b < NKB; ++b)
-#pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        const bf16x8 pb = pack_b_operand(s[b], u);
-                        bf16x8 plo;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) plo[e] = (bf16)(s[b][8 * u + e] - (float)pb[e]);
-#pragma unroll
-                        for (int cb = 0; cb < NCB; ++cb) {
-                            const bf16* vp = vt_lds + (32 * b + 16 * u) * D;
-                            const bf16x4 lo = lds_read_tr4(vp + v_off[cb][0]), hi = lds_read_tr4(vp + v_off[cb][1]);
-                            const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                            oacc[cb] = mfma32(va, pb, oacc[cb]);
-                            oacc[cb] = mfma32(va, plo, oacc[cb]);
-                        }
-                    }
-            } else {
-#pragma unroll
-                for (int b = 0; b < NKB; ++b)
-#pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        const bf16x8 pb = pack_b_operand(s[b], u);
-#pragma unroll
-                        for (int cb = 0; cb < NCB; ++cb) {
-                            const bf16* vp = vt_lds + (32 * b + 16 * u) * D;
-                            const bf16x4 lo = lds_read_tr4(vp + v_off[cb][0]), hi = lds_read_tr4(vp + v_off[cb][1]);
-                            oacc[cb] = mfma32(__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7), pb, oacc[cb]);
-                        }
-                    }
-            }
+                for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
+            m_used = m_new;
         }
-        wait_direct_loads();
-        __syncthreads();
+        const float ms = (m_used == -INFINITY ? 0.f : m_used) * sl2;
+        float rs0 = 0.f, rs1 = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+            s[r] = fast_exp2(__builtin_fmaf(s[r], sl2, -ms));
+            s[r + 1] = fast_exp2(__builtin_fmaf(s[r + 1], sl2, -ms));
+            rs0 += s[r];
+            rs1 += s[r + 1];
+        }
+        l_run += rs0 + rs1;
+
+        // O^T += V^T P^T, 16 keys at a time.  MASKED: rows with few visible keys are where |O| is largest
+        // and where bf16 rounding of P would be the dominant error, so diagonal blocks carry P in two
+        // bf16 pieces (hi + lo).
+        auto pv_half = [&](int u) __attribute__((always_inline)) {
+            const bf16x8 pb = pack_b_operand(s, u);
+            bf16x8 plo;
+            if (MASKED) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) plo[e] = (bf16)(s[8 * u + e] - (float)pb[e]);
+            }
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                const bf16x8 va = __builtin_shufflevector(vlo[cb], vhi[cb], 0, 1, 2, 3, 4, 5, 6, 7);
+                oacc[cb] = mfma32(va, pb, oacc[cb]);
+                if (MASKED) oacc[cb] = mfma32(va, plo, oacc[cb]);
+            }
+        };
+        auto wait_v = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; cb += 2) lds_wait<0>(vlo[cb], vhi[cb], vlo[cb + 1], vhi[cb + 1]);
+        };
+        auto read_v_second = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                vlo[cb] = lds_tr_b64<VB + HALF>(v_adr[cb]);
+                vhi[cb] = lds_tr_b64<VB + HALF + ROW8>(v_adr[cb]);
+            }
+        };
+        wait_v();
+        if (!LAST) read_k(kn_tag, First{});  // arrives while the PV MFMAs run; not live during the softmax
+        pv_half(0);
+        __builtin_amdgcn_sched_barrier(0);  // the second half reuses the V registers of the first
+        read_v_second();
+        wait_v();
+        if (LAST) {
+            // every wave is done reading this tile's buffers once it gets here
+            wait_direct_loads();
+            __syncthreads();
+            if (kt + 2 < n_kt) load_tile(KFREE, VFREE, kt + 2);
+            if (kt + 1 < n_kt) read_k(kn_tag, First{});
+        }
+        pv_half(1);
     };
 
-    for (int kt = 0; kt < n_kt; kt += 2) {
-        do_tile(k_lds0, v_lds0, k_lds1, v_lds1, kt);
-        if (kt + 1 < n_kt) do_tile(k_lds1, v_lds1, k_lds0, v_lds0, kt + 1);
+    // Blocks entirely below the diagonal for every wave and inside the sequence need no mask.
+    int n_full = N / kFwdBK;
+    if (CAUSAL) { const int lim = q0 / kFwdBK; n_full = lim < n_full ? lim : n_full; }
+    using Plain = std::integral_constant<bool, false>;
+    using Masked = std::integral_constant<bool, true>;
+    using None = std::integral_constant<int, -1>;
+#define ULY_IC(x) std::integral_constant<int, (x)> {}
+    auto tile_even = [&](auto mt, int kt) __attribute__((always_inline)) {      // tile in K0/V0, next in K1/V1
+        do_block(mt, ULY_IC(K0), ULY_IC(V0), ULY_IC(K0 + BLK), None{}, None{}, kt * kFwdBK, kt);
+        do_block(mt, ULY_IC(K0 + BLK), ULY_IC(V0 + BLK), ULY_IC(K1), ULY_IC(K0), ULY_IC(V0), kt * kFwdBK + 32, kt);
+    };
+    auto tile_odd = [&](auto mt, int kt) __attribute__((always_inline)) {
+        do_block(mt, ULY_IC(K1), ULY_IC(V1), ULY_IC(K1 + BLK), None{}, None{}, kt * kFwdBK, kt);
+        do_block(mt, ULY_IC(K1 + BLK), ULY_IC(V1 + BLK), ULY_IC(K0), ULY_IC(K1), ULY_IC(V1), kt * kFwdBK + 32, kt);
+    };
+#undef ULY_IC
+    int kt = 0;
+    for (; kt + 1 < n_full; kt += 2) {
+        tile_even(Plain{}, kt);
+        tile_odd(Plain{}, kt + 1);
+    }
+    for (; kt < n_kt; ++kt) {
+        if (kt & 1) { if (kt < n_full) tile_odd(Plain{}, kt); else tile_odd(Masked{}, kt); }
+        else { if (kt < n_full) tile_even(Plain{}, kt); else tile_even(Masked{}, kt); }
     }
 
     // ---- epilogue: normalise, store O (bf16) and LSE (natural log)
