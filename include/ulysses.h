@@ -94,7 +94,7 @@ int ulysses_unpack_rev(const void* recv, void* y, int64_t n_local, int H, int d,
 int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                      int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream);
 
-/* Bytes of device scratch the backward pass needs (one fp32 per query row and head). */
+/* Bytes of device scratch the backward pass needs (two fp32 per query row and head, rows padded). */
 size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d);
 
 /* Backward: gradients of sum(O * dout) with respect to q, k, v.  The probabilities are recomputed
@@ -110,7 +110,7 @@ int ulysses_attn_bwd(const void* q, const void* k, const void* v, const void* o,
 /* One stage of ulysses_attn_bwd, with the same arguments and the same checks.  Calling stages
  * ULY_BWD_STAGE_DELTA, ULY_BWD_STAGE_DKV, ULY_BWD_STAGE_DQ in that order on one stream is exactly
  * ulysses_attn_bwd; they exist so that a caller can time or overlap the kernels separately.
- *   DELTA: workspace[h, i] = dout_i . o_i   (reads o, dout; writes workspace)
+ *   DELTA: workspace <- row statistics dout_i . o_i and lse_i * log2(e)   (reads o, dout, lse)
  *   DKV  : dk, dv                            (reads q, k, v, dout, lse, workspace)
  *   DQ   : dq                                (reads q, k, v, dout, lse, workspace)
  * An unknown stage is ULY_ERR_UNSUPPORTED. */

@@ -121,7 +121,7 @@ int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float
 size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
     (void)d;
     if (N <= 0 || Hl <= 0) return 0;
-    return (size_t)N * (size_t)Hl * sizeof(float);
+    return (size_t)uly::attn_bwd_workspace_floats(N, Hl) * sizeof(float);
 }
 
 static int attn_bwd_checked(int stage_mask, const void* q, const void* k, const void* v, const void* o,

@@ -8,6 +8,8 @@
 //
 // Two kernels instead of one with atomics: each output element is owned by exactly one lane, so
 // the result is deterministic and needs no fp32 dQ buffer, at the price of recomputing S and dP.
+#include <type_traits>
+
 #include "attn_common.h"
 #include "internal.h"
 
@@ -16,20 +18,26 @@ namespace uly {
 constexpr int kBwdThreads = 256;
 
 // ------------------------------------------------------------------------------------------
-// delta[h, i] = sum_c dO[i,h,c] * O[i,h,c]
+// Row statistics for the backward kernels, in a padded [Hl, stride] layout (stride >= N + 64):
+//   delta[h, i] = sum_c dO[i,h,c] * O[i,h,c]        lse2[h, i] = LSE[h, i] * log2(e)
+// Rows N .. stride-1 get delta = 0 and lse2 = +inf, so that a padding row's probability
+// exp2(s - lse2) is exactly 0 without any test in the consumers.
 // ------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const bf16* __restrict__ O, const bf16* __restrict__ dO,
-                                                             float* __restrict__ delta, int N, int Hl,
+                                                             const float* __restrict__ LSE, float* __restrict__ delta,
+                                                             float* __restrict__ lse2, int N, int Hl, int64_t stride,
                                                              int64_t row_stride, int64_t head_stride) {
     constexpr int LPR = D / 8;                                   // lanes per (token, head) row
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t pair = gid / LPR;
     const int sub = (int)(gid % LPR);
-    const bool live = pair < (int64_t)N * Hl;
-    const int64_t row = live ? pair / Hl : 0;
-    const int head = live ? (int)(pair % Hl) : 0;
-    const int64_t off = row * row_stride + head * head_stride + sub * 8;
+    const bool in_grid = pair < stride * Hl;
+    const int64_t row = in_grid ? pair / Hl : 0;
+    const int head = in_grid ? (int)(pair % Hl) : 0;
+    const bool live = in_grid && row < N;
+    const int64_t ld_row = live ? row : 0;
+    const int64_t off = ld_row * row_stride + head * head_stride + sub * 8;
     const bf16x8 a = *reinterpret_cast<const bf16x8*>(O + off);
     const bf16x8 b = *reinterpret_cast<const bf16x8*>(dO + off);
     float acc = 0.f;
@@ -37,7 +45,10 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const bf16* __restr
     for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
 #pragma unroll
     for (int m = LPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
-    if (live && sub == 0) delta[(int64_t)head * N + row] = acc;
+    if (in_grid && sub == 0) {
+        delta[(int64_t)head * stride + row] = live ? acc : 0.f;
+        lse2[(int64_t)head * stride + row] = live ? LSE[(int64_t)head * N + row] * kLog2e : INFINITY;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -49,7 +60,8 @@ constexpr int kDqBK = 64;
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(kBwdThreads, 2) void attn_bwd_dq_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dO,
-    const float* __restrict__ LSE, const float* __restrict__ DELTA, bf16* __restrict__ dQ, int N, int n_qtiles,
+    const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, bf16* __restrict__ dQ, int N,
+    int n_qtiles,
     int64_t row_stride, int64_t head_stride, float scale) {
     constexpr int RS = LdsStride<D>::row, TS = LdsStride<D>::tr;
     constexpr int NT = D / 16, NKB = kDqBK / 32, NCB = D / 32;
@@ -76,8 +88,8 @@ __global__ __launch_bounds__(kBwdThreads, 2) void attn_bwd_dq_kernel(
         doreg[t] = *reinterpret_cast<const bf16x8*>(dO + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
     }
     const float sl2 = scale * kLog2e;
-    const float lse2 = LSE[(int64_t)head * N + q_ld] * kLog2e;
-    const float delta = DELTA[(int64_t)head * N + q_ld];
+    const float lse2 = LSE2[(int64_t)head * ws_stride + q_ld];
+    const float delta = DELTA[(int64_t)head * ws_stride + q_ld];
 
     f32x16 acc[NCB];
 #pragma unroll
@@ -156,26 +168,39 @@ __global__ __launch_bounds__(kBwdThreads, 2) void attn_bwd_dq_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// dK, dV: one workgroup owns 128 keys (a lane owns one key, queries run down the C rows).
+// dK, dV: one workgroup (4 waves, one per SIMD, up to 512 registers each) owns 128 keys; a lane owns
+// one key (a column of S), queries run down the C rows.  Q and dO stream through LDS in 32-query
+// tiles (ring of 4, filled straight from global memory two iterations ahead, swizzled so that both
+// the row reads for S = Q K^T, dP = dO V^T and the transposing reads for dV^T += dO^T P,
+// dK^T += Q^T dS are conflict-free).  Software pipeline, per iteration b:
+//     matrix pipe:  S, dP of block b+1          vector pipe:  P, dS of block b      (region A)
+//     matrix pipe:  dV, dK of block b                                              (region B)
+// The two streams of region A sit in one basic block and are interleaved instruction by
+// instruction, so a single wave keeps the matrix pipe busy while it does its exponentials.
 // ------------------------------------------------------------------------------------------
+constexpr int kDkvThreads = 256;
+constexpr int kDkvWaves = 4;
 constexpr int kDkvBK = 128;   // keys per workgroup
-constexpr int kDkvBQ = 64;    // queries per LDS tile
+constexpr int kDkvBQ = 32;    // queries per LDS tile
+constexpr int kDkvRing = 4;   // LDS tiles per tensor
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(kBwdThreads, 1) void attn_bwd_dkv_kernel(
+__global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dO,
-    const float* __restrict__ LSE, const float* __restrict__ DELTA, bf16* __restrict__ dK, bf16* __restrict__ dV,
-    int N, int n_ktiles, int64_t row_stride, int64_t head_stride, float scale) {
-    constexpr int RS = LdsStride<D>::row, TS = LdsStride<D>::tr;
-    constexpr int NT = D / 16, NRB = kDkvBQ / 32, NCB = D / 32;
-    using IO = TileIO<D, kDkvBQ, kBwdThreads>;
+    const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, bf16* __restrict__ dK,
+    bf16* __restrict__ dV, int N, int n_ktiles, int64_t row_stride, int64_t head_stride, float scale) {
+    constexpr int NT = D / 16, NCB = D / 32;
+    constexpr int TILE = kDkvBQ * D;            // elements per tile
+    constexpr int TB = TILE * 2;                // bytes per tile
+    constexpr int QB = 0, DOB = kDkvRing * TB;  // byte offsets of the Q ring and the dO ring
+    constexpr int HALF = 16 * D * 2;            // bytes per 16 rows
+    constexpr int ROW8 = 8 * D * 2;
+    constexpr int STAT = 512;                   // bytes per ring slot of row statistics: 64 lse2, 64 delta
+    using Loader = DirectTile<D, kDkvBQ, kDkvWaves, SwzBoth>;
+    constexpr int LPT = 2 * Loader::kPerWave + 2;   // global loads per wave per tile (Q, dO, lse2, delta)
 
-    __shared__ __attribute__((aligned(16))) bf16 q_row_t[kDkvBQ * RS];
-    __shared__ __attribute__((aligned(16))) bf16 q_tr[kDkvBQ * TS];
-    __shared__ __attribute__((aligned(16))) bf16 do_row_t[kDkvBQ * RS];
-    __shared__ __attribute__((aligned(16))) bf16 do_tr[kDkvBQ * TS];
-    __shared__ __attribute__((aligned(16))) float lse_s[kDkvBQ];
-    __shared__ __attribute__((aligned(16))) float delta_s[kDkvBQ];
+    __shared__ __attribute__((aligned(1024))) bf16 smem[2 * kDkvRing * TILE];
+    __shared__ __attribute__((aligned(256))) float stat[kDkvRing * (STAT / 4)];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ln = lane & 31;
     const int head = blockIdx.x / n_ktiles;
@@ -184,10 +209,39 @@ __global__ __launch_bounds__(kBwdThreads, 1) void attn_bwd_dkv_kernel(
     const int64_t hoff = (int64_t)head * head_stride;
     const bf16* Qh = Q + hoff;
     const bf16* dOh = dO + hoff;
-    const float* lse_h = LSE + (int64_t)head * N;
-    const float* delta_h = DELTA + (int64_t)head * N;
+    const float* lse_h = LSE2 + (int64_t)head * ws_stride;
+    const float* del_h = DELTA + (int64_t)head * ws_stride;
 
-    const int j_col = j0 + wave * 32 + ln;                   // this lane's key
+    const int nblk = (N + kDkvBQ - 1) / kDkvBQ;
+    const int b0 = CAUSAL ? j0 / kDkvBQ : 0;
+
+    // ---- global -> LDS tile loads (tile index clamped: past the end the last tile is simply re-read)
+    const typename Loader::LaneOffsets ld = Loader::lane_offsets(row_stride, wave, lane);
+    auto load_tile = [&](int slot, int tb) __attribute__((always_inline)) {
+        tb = tb < nblk ? tb : nblk - 1;
+        const int r0 = tb * kDkvBQ;
+        bf16* qdst = smem + slot * TILE;
+        bf16* ddst = smem + (kDkvRing + slot) * TILE;
+        if (r0 + kDkvBQ <= N) {
+            Loader::issue(qdst, Qh + (int64_t)r0 * row_stride, ld, wave);
+            Loader::issue(ddst, dOh + (int64_t)r0 * row_stride, ld, wave);
+        } else {
+            Loader::issue_clamped(qdst, Qh, row_stride, r0, N, wave, lane);
+            Loader::issue_clamped(ddst, dOh, row_stride, r0, N, wave, lane);
+        }
+        // row statistics: 64 floats each (the padded arrays make rows r0 .. r0+63 readable); every
+        // wave issues the same two loads so that all waves count the same number of loads per tile
+        float* sdst = stat + slot * (STAT / 4);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(lse_h + r0 + lane),
+                                         ULY_LDS(void, sdst), 4, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(del_h + r0 + lane),
+                                         ULY_LDS(void, sdst + 64), 4, 0, 0);
+    };
+#pragma unroll
+    for (int i = 0; i < kDkvRing; ++i) load_tile(i, b0 + i);
+
+    // ---- this lane's key: K and V rows as B operands
+    const int j_col = j0 + wave * 32 + ln;
     const int j_ld = j_col < N ? j_col : N - 1;
     bf16x8 kreg[NT], vreg[NT];
 #pragma unroll
@@ -196,6 +250,24 @@ __global__ __launch_bounds__(kBwdThreads, 1) void attn_bwd_dkv_kernel(
         vreg[t] = *reinterpret_cast<const bf16x8*>(V + hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
     }
     const float sl2 = scale * kLog2e;
+    const int jcol_g = j_col - 4 * g;            // causal test: row offset c_r is masked iff c_r < jcol_g - i0
+
+    // ---- per-lane LDS byte addresses inside a tile (ring slot, tensor and 16-row offsets are immediates)
+    const uint32_t sbase = lds_addr(smem);
+    uint32_t r_adr[NT];                 // row read: row ln, chunk 2t+g
+#pragma unroll
+    for (int t = 0; t < NT; ++t) r_adr[t] = sbase + 2 * tile_off<D>(ln, 2 * t + g);
+    uint32_t t_adr[NCB][2];             // transposing read: rows 4g+(i>>2) (+8), channels 32cb+16h+4(i&3)
+    {
+        const int i = lane & 15, h = (lane >> 4) & 1;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+                t_adr[cb][hh] = sbase + 2 * (tile_off<D>(4 * g + (i >> 2) + 8 * hh, 4 * cb + 2 * h + ((i & 3) >> 1)) +
+                                             4 * (i & 1));
+    }
+    const uint32_t st_adr = lds_addr(stat) + 16 * g;    // rows 8q+4g .. +3 of a slot: immediate 32q (+256: delta)
 
     f32x16 dk_acc[NCB], dv_acc[NCB];
 #pragma unroll
@@ -203,81 +275,149 @@ __global__ __launch_bounds__(kBwdThreads, 1) void attn_bwd_dkv_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dk_acc[cb][r] = 0.f; dv_acc[cb][r] = 0.f; }
 
-    const int n_it = (N + kDkvBQ - 1) / kDkvBQ;
-    const int it0 = CAUSAL ? j0 / kDkvBQ : 0;
-    const int wave_jmin = j0 + wave * 32;
+    // pipeline registers
+    f32x16 s[2], dp[2];                 // [parity]: scores / dP of the current and of the next block
+    bf16x8 rowq[NT], rowdo[NT];         // row operands of the block whose S, dP are computed next
+    f32x4 lse4[4], del4[4];             // statistics of the block whose P, dS are computed next
+    bf16x4 qt_lo[2][NCB], qt_hi[2][NCB], dot_lo[2][NCB], dot_hi[2][NCB];   // transposed operands of the current block
 
-    u32x4 qpre[IO::kPerThread], dopre[IO::kPerThread];
-    float lse_pre = 0.f, delta_pre = 0.f;
-    auto prefetch = [&](int it) {
-        const int i0 = it * kDkvBQ;
-        IO::load(qpre, Qh, row_stride, i0, N, tid);
-        IO::load(dopre, dOh, row_stride, i0, N, tid);
-        if (tid < kDkvBQ) {
-            int i = i0 + tid;
-            i = i < N ? i : N - 1;
-            lse_pre = lse_h[i] * kLog2e;
-            delta_pre = delta_h[i];
+    auto read_rows = [&](auto slot_tag) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            rowq[t] = lds_b128<QB + SL * TB>(r_adr[t]);
+            rowdo[t] = lds_b128<DOB + SL * TB>(r_adr[t]);
         }
     };
-    if (it0 < n_it) prefetch(it0);
-
-    for (int it = it0; it < n_it; ++it) {
-        const int i0 = it * kDkvBQ;
-        __syncthreads();
-        IO::store(qpre, q_row_t, RS, tid);
-        IO::store(qpre, q_tr, TS, tid);
-        IO::store(dopre, do_row_t, RS, tid);
-        IO::store(dopre, do_tr, TS, tid);
-        if (tid < kDkvBQ) { lse_s[tid] = lse_pre; delta_s[tid] = delta_pre; }
-        __syncthreads();
-        if (it + 1 < n_it) prefetch(it + 1);
-        // every query of this tile precedes every key of this wave: nothing visible
-        if (CAUSAL && i0 + kDkvBQ - 1 < wave_jmin) continue;
-
-        f32x16 s[NRB], dp[NRB];
+    auto read_stats = [&](auto slot_tag) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+        lse4[0] = lds_f32x4<SL * STAT + 0>(st_adr);   lse4[1] = lds_f32x4<SL * STAT + 32>(st_adr);
+        lse4[2] = lds_f32x4<SL * STAT + 64>(st_adr);  lse4[3] = lds_f32x4<SL * STAT + 96>(st_adr);
+        del4[0] = lds_f32x4<SL * STAT + 256>(st_adr); del4[1] = lds_f32x4<SL * STAT + 288>(st_adr);
+        del4[2] = lds_f32x4<SL * STAT + 320>(st_adr); del4[3] = lds_f32x4<SL * STAT + 352>(st_adr);
+    };
+    auto read_transposed = [&](auto slot_tag) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { s[rb][r] = 0.f; dp[rb][r] = 0.f; }
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                s[rb] = mfma32(lds_read_row8(q_row_t + (32 * rb + ln) * RS + 16 * t + 8 * g), kreg[t], s[rb]);
-                dp[rb] = mfma32(lds_read_row8(do_row_t + (32 * rb + ln) * RS + 16 * t + 8 * g), vreg[t], dp[rb]);
+            for (int cb = 0; cb < NCB; ++cb) {
+                if (u == 0) {
+                    dot_lo[0][cb] = lds_tr_b64<DOB + SL * TB>(t_adr[cb][0]);
+                    dot_hi[0][cb] = lds_tr_b64<DOB + SL * TB>(t_adr[cb][1]);
+                    qt_lo[0][cb] = lds_tr_b64<QB + SL * TB>(t_adr[cb][0]);
+                    qt_hi[0][cb] = lds_tr_b64<QB + SL * TB>(t_adr[cb][1]);
+                } else {
+                    dot_lo[1][cb] = lds_tr_b64<DOB + SL * TB + HALF>(t_adr[cb][0]);
+                    dot_hi[1][cb] = lds_tr_b64<DOB + SL * TB + HALF>(t_adr[cb][1]);
+                    qt_lo[1][cb] = lds_tr_b64<QB + SL * TB + HALF>(t_adr[cb][0]);
+                    qt_hi[1][cb] = lds_tr_b64<QB + SL * TB + HALF>(t_adr[cb][1]);
+                }
             }
+    };
+    auto tie_rows = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) lds_tie(rowq[t], rowdo[t]);
+        lds_tie(lse4[0], lse4[1], lse4[2], lse4[3], del4[0], del4[1], del4[2], del4[3]);
+    };
+    auto tie_transposed = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) lds_tie(dot_lo[u][cb], dot_hi[u][cb], qt_lo[u][cb], qt_hi[u][cb]);
+    };
+    // S, dP of one block from the row operands
+    auto scores = [&](f32x16& sn, f32x16& dpn) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { sn[r] = 0.f; dpn[r] = 0.f; }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            sn = mfma32(rowq[t], kreg[t], sn);
+            dpn = mfma32(rowdo[t], vreg[t], dpn);
         }
-        const bool need_mask = (CAUSAL && i0 < wave_jmin + 31) || (i0 + kDkvBQ > N);
+    };
+
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    using S2 = std::integral_constant<int, 2>;
+    using S3 = std::integral_constant<int, 3>;
+
+    // ---- prologue: tiles b0, b0+1 resident; S, dP of block b0; row operands of b0+1, statistics of b0
+    wait_vm<2 * LPT>();
+    __syncthreads();
+    read_rows(S0{});
+    wait_lgkm<0>();
+    tie_rows();
+    scores(s[0], dp[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    read_rows(S1{});
+    read_stats(S0{});
+
+    // One iteration: block b lives in ring slot SL (its parity selects the s/dp set).
+    auto iteration = [&](auto slot_tag, auto slot1_tag, auto slot2_tag, int b) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+        constexpr int PAR = SL & 1;
+        const int i0 = b * kDkvBQ;
+        wait_lgkm<0>();                               // rows of b+1 and statistics of b (issued half an iteration ago)
+        tie_rows();
+        read_transposed(slot_tag);                    // for region B; lands during region A
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- region A: S, dP of block b+1 (matrix pipe) || P, dS of block b (vector pipe)
+        scores(s[PAR ^ 1], dp[PAR ^ 1]);
+        const int jrel = jcol_g - i0;
+        bf16x8 pb[2], dsb[2];
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + 32 * rb + 8 * rq + 4 * g);
-                const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_s + 32 * rb + 8 * rq + 4 * g);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int r = 4 * rq + e;
-                    float p = fast_exp2(__builtin_fmaf(s[rb][r], sl2, -l4[e]));
-                    if (need_mask) {
-                        const int i = i0 + 32 * rb + 8 * rq + 4 * g + e;
-                        if ((CAUSAL && j_col > i) || i >= N) p = 0.f;
-                    }
-                    s[rb][r] = p;
-                    dp[rb][r] = p * (dp[rb][r] - d4[e]);
-                }
+            for (int e = 0; e < 8; ++e) {
+                const int r = 8 * u + e;
+                float x = __builtin_fmaf(s[PAR][r], sl2, -lse4[r >> 2][r & 3]);
+                if (CAUSAL) x = (8 * (r >> 2) + (r & 3) < jrel) ? -INFINITY : x;
+                const float p = fast_exp2(x);
+                const float ds = p * (dp[PAR][r] - del4[r >> 2][r & 3]);
+                pb[u][e] = (bf16)p;
+                dsb[u][e] = (bf16)ds;
             }
+        // interleave: one MFMA, then a share of the vector work
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
+        for (int i = 0; i < 2 * NT; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);    // VALU
+            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // transcendental
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- tile b+2 has landed (its loads were issued two iterations ago); everyone is done with tile b
+        wait_lgkm<0>();
+        tie_transposed();
+        wait_vm<LPT>();
+        __syncthreads();
+        load_tile(SL, b + kDkvRing);
+        read_rows(slot2_tag);                         // rows of block b+2
+        read_stats(slot1_tag);                        // statistics of block b+1
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- region B: dV^T += dO^T P, dK^T += Q^T dS
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const bf16x8 pb = pack_b_operand(s[rb], u);
-                const bf16x8 dsb = pack_b_operand(dp[rb], u);
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-                for (int cb = 0; cb < NCB; ++cb) {
-                    dv_acc[cb] = mfma32(lds_read_transposed_a(do_tr, TS, 32 * rb + 16 * u, 32 * cb, lane), pb, dv_acc[cb]);
-                    dk_acc[cb] = mfma32(lds_read_transposed_a(q_tr, TS, 32 * rb + 16 * u, 32 * cb, lane), dsb, dk_acc[cb]);
-                }
+            for (int cb = 0; cb < NCB; ++cb) {
+                const bf16x8 da = __builtin_shufflevector(dot_lo[u][cb], dot_hi[u][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 qa = __builtin_shufflevector(qt_lo[u][cb], qt_hi[u][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+                dv_acc[cb] = mfma32(da, pb[u], dv_acc[cb]);
+                dk_acc[cb] = mfma32(qa, dsb[u], dk_acc[cb]);
             }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    for (int b = b0; b < nblk; b += 4) {
+        iteration(S0{}, S1{}, S2{}, b);
+        if (b + 1 < nblk) iteration(S1{}, S2{}, S3{}, b + 1);
+        if (b + 2 < nblk) iteration(S2{}, S3{}, S0{}, b + 2);
+        if (b + 3 < nblk) iteration(S3{}, S0{}, S1{}, b + 3);
     }
+    wait_vm<0>();        // nothing may still be writing LDS when the workgroup ends
 
     if (j_col < N) {
         bf16* krow = dK + hoff + (int64_t)j_col * row_stride;
@@ -298,50 +438,57 @@ __global__ __launch_bounds__(kBwdThreads, 1) void attn_bwd_dkv_kernel(
     }
 }
 
+// padded row stride of the statistics arrays in the workspace
+inline int64_t stats_stride(int64_t N) { return ((N + 63) / 64) * 64 + 64; }
+
 template <int D>
 static int launch_bwd(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
-                      const float* lse, void* dq, void* dk, void* dv, float* delta, int64_t N, int Hl, float scale,
+                      const float* lse, void* dq, void* dk, void* dv, float* ws, int64_t N, int Hl, float scale,
                       int causal, TensorStrides st, hipStream_t stream) {
-    const int64_t pairs = N * Hl;
-    const int64_t delta_blocks = (pairs * (D / 8) + 255) / 256;
+    const int64_t stride = stats_stride(N);
+    float* delta = ws;
+    float* lse2 = ws + stride * Hl;
+    const int64_t delta_blocks = (stride * Hl * (D / 8) + 255) / 256;
     const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (N + kDkvBK - 1) / kDkvBK;
     if (delta_blocks > 0x7FFFFFFFll || n_qtiles * Hl > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     const bf16 *Q = (const bf16*)q, *K = (const bf16*)k, *V = (const bf16*)v, *dO = (const bf16*)dout;
-    const dim3 gkv((uint32_t)(n_ktiles * Hl)), gq((uint32_t)(n_qtiles * Hl)), block(kBwdThreads);
+    const dim3 gkv((uint32_t)(n_ktiles * Hl)), gq((uint32_t)(n_qtiles * Hl));
 
     if (stage_mask & 1) {
-        attn_bwd_delta_kernel<D><<<dim3((uint32_t)delta_blocks), dim3(256), 0, stream>>>((const bf16*)o, dO, delta,
-                                                                                         (int)N, Hl, st.row, st.head);
+        attn_bwd_delta_kernel<D><<<dim3((uint32_t)delta_blocks), dim3(256), 0, stream>>>(
+            (const bf16*)o, dO, lse, delta, lse2, (int)N, Hl, stride, st.row, st.head);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     if (stage_mask & 2) {
         if (causal)
-            attn_bwd_dkv_kernel<D, true><<<gkv, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dk, (bf16*)dv,
-                                                                    (int)N, (int)n_ktiles, st.row, st.head, scale);
+            attn_bwd_dkv_kernel<D, true><<<gkv, dim3(kDkvThreads), 0, stream>>>(
+                Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)n_ktiles, st.row, st.head, scale);
         else
-            attn_bwd_dkv_kernel<D, false><<<gkv, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dk, (bf16*)dv,
-                                                                     (int)N, (int)n_ktiles, st.row, st.head, scale);
+            attn_bwd_dkv_kernel<D, false><<<gkv, dim3(kDkvThreads), 0, stream>>>(
+                Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)n_ktiles, st.row, st.head, scale);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     if (stage_mask & 4) {
         if (causal)
-            attn_bwd_dq_kernel<D, true><<<gq, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dq, (int)N,
-                                                                  (int)n_qtiles, st.row, st.head, scale);
+            attn_bwd_dq_kernel<D, true><<<gq, dim3(kBwdThreads), 0, stream>>>(
+                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)n_qtiles, st.row, st.head, scale);
         else
-            attn_bwd_dq_kernel<D, false><<<gq, block, 0, stream>>>(Q, K, V, dO, lse, delta, (bf16*)dq, (int)N,
-                                                                   (int)n_qtiles, st.row, st.head, scale);
+            attn_bwd_dq_kernel<D, false><<<gq, dim3(kBwdThreads), 0, stream>>>(
+                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)n_qtiles, st.row, st.head, scale);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     return ULY_OK;
 }
 
+int64_t attn_bwd_workspace_floats(int64_t N, int Hl) { return 2 * stats_stride(N) * Hl; }
+
 int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
-                    const float* lse, void* dq, void* dk, void* dv, float* delta, int64_t N, int Hl, int d,
+                    const float* lse, void* dq, void* dk, void* dv, float* ws, int64_t N, int Hl, int d,
                     float scale, int causal, TensorStrides st, void* stream) {
     if (d == 128)
-        return launch_bwd<128>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, delta, N, Hl, scale, causal, st,
+        return launch_bwd<128>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Hl, scale, causal, st,
                                (hipStream_t)stream);
-    return launch_bwd<64>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, delta, N, Hl, scale, causal, st,
+    return launch_bwd<64>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Hl, scale, causal, st,
                           (hipStream_t)stream);
 }
 

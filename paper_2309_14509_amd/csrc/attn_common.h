@@ -214,6 +214,17 @@ template <int N> __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b) 
 template <int N> __device__ __forceinline__ void lds_wait(bf16x4& a, bf16x4& b) {
     asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
 }
+// Generic form: wait_lgkm<N>() followed by lds_tie(regs...) orders every later use of `regs` behind
+// the wait (volatile asm statements keep their order; the empty asm redefines the registers).
+template <int N> __device__ __forceinline__ void wait_lgkm() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N)); }
+template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+template <typename T> __device__ __forceinline__ void lds_tie1(T& r) { asm volatile("" : "+v"(r)); }
+template <typename... T> __device__ __forceinline__ void lds_tie(T&... r) { (lds_tie1(r), ...); }
+template <int IMM> __device__ __forceinline__ f32x4 lds_f32x4(uint32_t addr) {
+    f32x4 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(IMM));
+    return r;
+}
 // byte address of an LDS object as the hardware sees it
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return (uint32_t)(uintptr_t)ULY_LDS(const char, p);

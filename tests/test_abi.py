@@ -71,7 +71,7 @@ def test_attention_forward_validation(lib):
 
 def test_attention_backward_validation(lib):
     ws_need = lib.ulysses_attn_bwd_workspace_bytes(128, 2, 64)
-    assert ws_need == 128 * 2 * 4
+    assert ws_need >= 2 * 128 * 2 * 4
     assert lib.ulysses_attn_bwd_workspace_bytes(0, 2, 64) == 0
     base = dict(q=A, k=B, v=C_, o=D_, dout=0x80000000, lse=0x7000000, dq=0xA0000000, dk=0xC0000000,
                 dv=0xE0000000, ws=0x9000000, wsb=ws_need, N=128, Hl=2, d=64, scale=0.125, causal=1, layout=0)
