@@ -281,13 +281,15 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     f32x4 lse4[4], del4[4];             // statistics of the block whose P, dS are computed next
     bf16x4 qt_lo[2][NCB], qt_hi[2][NCB], dot_lo[2][NCB], dot_hi[2][NCB];   // transposed operands of the current block
 
-    auto read_rows = [&](auto slot_tag) __attribute__((always_inline)) {
+    auto read_rowq = [&](auto slot_tag) __attribute__((always_inline)) {
         constexpr int SL = decltype(slot_tag)::value;
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            rowq[t] = lds_b128<QB + SL * TB>(r_adr[t]);
-            rowdo[t] = lds_b128<DOB + SL * TB>(r_adr[t]);
-        }
+        for (int t = 0; t < NT; ++t) rowq[t] = lds_b128<QB + SL * TB>(r_adr[t]);
+    };
+    auto read_rowdo = [&](auto slot_tag) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) rowdo[t] = lds_b128<DOB + SL * TB>(r_adr[t]);
     };
     auto read_stats = [&](auto slot_tag) __attribute__((always_inline)) {
         constexpr int SL = decltype(slot_tag)::value;
@@ -299,26 +301,28 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     auto read_transposed = [&](auto slot_tag) __attribute__((always_inline)) {
         constexpr int SL = decltype(slot_tag)::value;
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int cb = 0; cb < NCB; ++cb) {
+            dot_lo[0][cb] = lds_tr_b64<DOB + SL * TB>(t_adr[cb][0]);
+            dot_hi[0][cb] = lds_tr_b64<DOB + SL * TB>(t_adr[cb][1]);
+            qt_lo[0][cb] = lds_tr_b64<QB + SL * TB>(t_adr[cb][0]);
+            qt_hi[0][cb] = lds_tr_b64<QB + SL * TB>(t_adr[cb][1]);
+        }
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-                if (u == 0) {
-                    dot_lo[0][cb] = lds_tr_b64<DOB + SL * TB>(t_adr[cb][0]);
-                    dot_hi[0][cb] = lds_tr_b64<DOB + SL * TB>(t_adr[cb][1]);
-                    qt_lo[0][cb] = lds_tr_b64<QB + SL * TB>(t_adr[cb][0]);
-                    qt_hi[0][cb] = lds_tr_b64<QB + SL * TB>(t_adr[cb][1]);
-                } else {
-                    dot_lo[1][cb] = lds_tr_b64<DOB + SL * TB + HALF>(t_adr[cb][0]);
-                    dot_hi[1][cb] = lds_tr_b64<DOB + SL * TB + HALF>(t_adr[cb][1]);
-                    qt_lo[1][cb] = lds_tr_b64<QB + SL * TB + HALF>(t_adr[cb][0]);
-                    qt_hi[1][cb] = lds_tr_b64<QB + SL * TB + HALF>(t_adr[cb][1]);
-                }
-            }
+        for (int cb = 0; cb < NCB; ++cb) {
+            dot_lo[1][cb] = lds_tr_b64<DOB + SL * TB + HALF>(t_adr[cb][0]);
+            dot_hi[1][cb] = lds_tr_b64<DOB + SL * TB + HALF>(t_adr[cb][1]);
+            qt_lo[1][cb] = lds_tr_b64<QB + SL * TB + HALF>(t_adr[cb][0]);
+            qt_hi[1][cb] = lds_tr_b64<QB + SL * TB + HALF>(t_adr[cb][1]);
+        }
     };
-    auto tie_rows = [&]() __attribute__((always_inline)) {
+    auto tie_rowq = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) lds_tie(rowq[t], rowdo[t]);
+        for (int t = 0; t < NT; ++t) lds_tie(rowq[t]);
         lds_tie(lse4[0], lse4[1], lse4[2], lse4[3], del4[0], del4[1], del4[2], del4[3]);
+    };
+    auto tie_rowdo = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) lds_tie(rowdo[t]);
     };
     auto tie_transposed = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -326,15 +330,9 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) lds_tie(dot_lo[u][cb], dot_hi[u][cb], qt_lo[u][cb], qt_hi[u][cb]);
     };
-    // S, dP of one block from the row operands
-    auto scores = [&](f32x16& sn, f32x16& dpn) __attribute__((always_inline)) {
+    auto zero = [&](f32x16& x) __attribute__((always_inline)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { sn[r] = 0.f; dpn[r] = 0.f; }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            sn = mfma32(rowq[t], kreg[t], sn);
-            dpn = mfma32(rowdo[t], vreg[t], dpn);
-        }
+        for (int r = 0; r < 16; ++r) x[r] = 0.f;
     };
 
     using S0 = std::integral_constant<int, 0>;
@@ -342,33 +340,36 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     using S2 = std::integral_constant<int, 2>;
     using S3 = std::integral_constant<int, 3>;
 
-    // ---- prologue: tiles b0, b0+1 resident; S, dP of block b0; row operands of b0+1, statistics of b0
+    // ---- prologue: tiles b0, b0+1 resident; S, dP of block b0; then (in this order) the statistics of
+    // b0 and the row operands of b0+1
     wait_vm<2 * LPT>();
     __syncthreads();
-    read_rows(S0{});
+    read_rowq(S0{});
+    read_rowdo(S0{});
     wait_lgkm<0>();
-    tie_rows();
-    scores(s[0], dp[0]);
+    tie_rowq();
+    tie_rowdo();
+    zero(s[0]); zero(dp[0]);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        s[0] = mfma32(rowq[t], kreg[t], s[0]);
+        dp[0] = mfma32(rowdo[t], vreg[t], dp[0]);
+    }
     __builtin_amdgcn_sched_barrier(0);
-    read_rows(S1{});
     read_stats(S0{});
+    read_rowq(S1{});
+    read_rowdo(S1{});
 
     // One iteration: block b lives in ring slot SL (its parity selects the s/dp set).
+    // LDS reads in flight at entry, oldest first: statistics of b, Q rows of b+1, dO rows of b+1.
     auto iteration = [&](auto slot_tag, auto slot1_tag, auto slot2_tag, int b) __attribute__((always_inline)) {
         constexpr int SL = decltype(slot_tag)::value;
         constexpr int PAR = SL & 1;
         const int i0 = b * kDkvBQ;
-        wait_lgkm<0>();                               // rows of b+1 and statistics of b (issued half an iteration ago)
-        tie_rows();
-        read_transposed(slot_tag);                    // for region B; lands during region A
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- region A: S, dP of block b+1 (matrix pipe) || P, dS of block b (vector pipe)
-        scores(s[PAR ^ 1], dp[PAR ^ 1]);
         const int jrel = jcol_g - i0;
         bf16x8 pb[2], dsb[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
+        // P and dS of 8 rows of block b (vector pipe)
+        auto softmax_half = [&](int u) __attribute__((always_inline)) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int r = 8 * u + e;
@@ -379,13 +380,36 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
                 pb[u][e] = (bf16)p;
                 dsb[u][e] = (bf16)ds;
             }
-        // interleave: one MFMA, then a share of the vector work
+        };
+        auto interleave = [&]() __attribute__((always_inline)) {     // one MFMA, then a share of the vector work
 #pragma unroll
-        for (int i = 0; i < 2 * NT; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);    // VALU
-            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // transcendental
-        }
+            for (int i = 0; i < NT; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);    // VALU
+                __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // transcendental
+            }
+        };
+
+        wait_lgkm<NT>();                              // all but the dO rows: statistics of b, Q rows of b+1
+        tie_rowq();
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- region A1: S of block b+1 (matrix pipe) || P, dS of rows 0-15 of block b (vector pipe)
+        zero(s[PAR ^ 1]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) s[PAR ^ 1] = mfma32(rowq[t], kreg[t], s[PAR ^ 1]);
+        softmax_half(0);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        wait_lgkm<0>();                               // dO rows of b+1
+        tie_rowdo();
+        read_transposed(slot_tag);                    // for region B; lands during region A2
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- region A2: dP of block b+1 || P, dS of rows 16-31 of block b
+        zero(dp[PAR ^ 1]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) dp[PAR ^ 1] = mfma32(rowdo[t], vreg[t], dp[PAR ^ 1]);
+        softmax_half(1);
+        interleave();
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- tile b+2 has landed (its loads were issued two iterations ago); everyone is done with tile b
@@ -394,21 +418,30 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         wait_vm<LPT>();
         __syncthreads();
         load_tile(SL, b + kDkvRing);
-        read_rows(slot2_tag);                         // rows of block b+2
         read_stats(slot1_tag);                        // statistics of block b+1
         __builtin_amdgcn_sched_barrier(0);
 
-        // ---- region B: dV^T += dO^T P, dK^T += Q^T dS
+        // ---- region B: dV^T += dO^T P, dK^T += Q^T dS; the row operands of block b+2 are fetched behind
+        // each half, into the registers its transposed operands leave free
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-                const bf16x8 da = __builtin_shufflevector(dot_lo[u][cb], dot_hi[u][cb], 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 qa = __builtin_shufflevector(qt_lo[u][cb], qt_hi[u][cb], 0, 1, 2, 3, 4, 5, 6, 7);
-                dv_acc[cb] = mfma32(da, pb[u], dv_acc[cb]);
-                dk_acc[cb] = mfma32(qa, dsb[u], dk_acc[cb]);
-            }
+        for (int cb = 0; cb < NCB; ++cb) {
+            const bf16x8 da = __builtin_shufflevector(dot_lo[0][cb], dot_hi[0][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8 qa = __builtin_shufflevector(qt_lo[0][cb], qt_hi[0][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+            dv_acc[cb] = mfma32(da, pb[0], dv_acc[cb]);
+            dk_acc[cb] = mfma32(qa, dsb[0], dk_acc[cb]);
+        }
         __builtin_amdgcn_sched_barrier(0);
+        read_rowq(slot2_tag);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            const bf16x8 da = __builtin_shufflevector(dot_lo[1][cb], dot_hi[1][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8 qa = __builtin_shufflevector(qt_lo[1][cb], qt_hi[1][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+            dv_acc[cb] = mfma32(da, pb[1], dv_acc[cb]);
+            dk_acc[cb] = mfma32(qa, dsb[1], dk_acc[cb]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        read_rowdo(slot2_tag);
     };
 
     for (int b = b0; b < nblk; b += 4) {
