@@ -399,6 +399,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         for (int t = 0; t < NT; ++t) s[PAR ^ 1] = mfma32(rowq[t], kreg[t], s[PAR ^ 1]);
         softmax_half(0);
         interleave();
+        lds_tie(pb[0], dsb[0]);                       // pin the vector work here (it would sink to its use)
         __builtin_amdgcn_sched_barrier(0);
         wait_lgkm<0>();                               // dO rows of b+1
         tie_rowdo();
@@ -410,6 +411,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         for (int t = 0; t < NT; ++t) dp[PAR ^ 1] = mfma32(rowdo[t], vreg[t], dp[PAR ^ 1]);
         softmax_half(1);
         interleave();
+        lds_tie(pb[1], dsb[1]);
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- tile b+2 has landed (its loads were issued two iterations ago); everyone is done with tile b
