@@ -52,33 +52,63 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const bf16* __restr
 }
 
 // ------------------------------------------------------------------------------------------
-// dQ: same tiling as the forward pass (a lane owns one query, keys run down the C rows).
+// dQ: one workgroup (4 waves, one per SIMD) owns 128 queries; a lane owns one query (a column of
+// S^T), keys run down the C rows.  K and V stream through LDS in 32-key tiles (ring of 4, filled
+// straight from global memory two iterations ahead).  Same software pipeline as the dK/dV kernel:
+//     matrix pipe:  S^T, dP^T of block b+1      vector pipe:  dS^T of block b      (region A)
+//     matrix pipe:  dQ^T += K^T dS^T of block b                                    (region B)
 // ------------------------------------------------------------------------------------------
-constexpr int kDqBQ = 128;
-constexpr int kDqBK = 64;
+constexpr int kDqThreads = 256;
+constexpr int kDqWaves = 4;
+constexpr int kDqBQ = 128;    // queries per workgroup
+constexpr int kDqBK = 32;     // keys per LDS tile
+constexpr int kDqRing = 4;
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(kBwdThreads, 2) void attn_bwd_dq_kernel(
+__global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dO,
     const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, bf16* __restrict__ dQ, int N,
-    int n_qtiles,
-    int64_t row_stride, int64_t head_stride, float scale) {
-    constexpr int RS = LdsStride<D>::row, TS = LdsStride<D>::tr;
-    constexpr int NT = D / 16, NKB = kDqBK / 32, NCB = D / 32;
-    using IO = TileIO<D, kDqBK, kBwdThreads>;
+    int n_qtiles, int64_t row_stride, int64_t head_stride, float scale) {
+    constexpr int NT = D / 16, NCB = D / 32;
+    constexpr int TILE = kDqBK * D;
+    constexpr int TB = TILE * 2;
+    constexpr int KB = 0, VB = kDqRing * TB;    // byte offsets of the K ring and the V ring
+    constexpr int HALF = 16 * D * 2;
+    using Loader = DirectTile<D, kDqBK, kDqWaves, SwzBoth>;
+    constexpr int LPT = 2 * Loader::kPerWave;   // global loads per wave per tile
 
-    __shared__ __attribute__((aligned(16))) bf16 k_row[kDqBK * RS];   // K for S^T      (row reads)
-    __shared__ __attribute__((aligned(16))) bf16 k_tr[kDqBK * TS];    // K for dQ^T     (transposing reads)
-    __shared__ __attribute__((aligned(16))) bf16 v_row[kDqBK * RS];   // V for dP^T     (row reads)
+    __shared__ __attribute__((aligned(1024))) bf16 smem[2 * kDqRing * TILE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ln = lane & 31;
     const int head = blockIdx.x / n_qtiles;
-    const int qt = n_qtiles - 1 - (blockIdx.x - head * n_qtiles);
+    const int qt = CAUSAL ? n_qtiles - 1 - (blockIdx.x - head * n_qtiles) : blockIdx.x - head * n_qtiles;
     const int q0 = qt * kDqBQ;
     const int64_t hoff = (int64_t)head * head_stride;
     const bf16* Kh = K + hoff;
     const bf16* Vh = V + hoff;
 
+    int k_end = N;
+    if (CAUSAL) { const int lim = q0 + kDqBQ; k_end = lim < N ? lim : N; }
+    const int nblk = (k_end + kDqBK - 1) / kDqBK;
+
+    const typename Loader::LaneOffsets ld = Loader::lane_offsets(row_stride, wave, lane);
+    auto load_tile = [&](int slot, int tb) __attribute__((always_inline)) {
+        tb = tb < nblk ? tb : nblk - 1;          // past the end the last tile is simply re-read
+        const int r0 = tb * kDqBK;
+        bf16* kdst = smem + slot * TILE;
+        bf16* vdst = smem + (kDqRing + slot) * TILE;
+        if (r0 + kDqBK <= N) {
+            Loader::issue(kdst, Kh + (int64_t)r0 * row_stride, ld, wave);
+            Loader::issue(vdst, Vh + (int64_t)r0 * row_stride, ld, wave);
+        } else {
+            Loader::issue_clamped(kdst, Kh, row_stride, r0, N, wave, lane);
+            Loader::issue_clamped(vdst, Vh, row_stride, r0, N, wave, lane);
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < kDqRing; ++i) load_tile(i, i);
+
+    // ---- this lane's query: Q and dO rows as B operands, its two row statistics
     const int q_row = q0 + wave * 32 + ln;
     const int q_ld = q_row < N ? q_row : N - 1;
     bf16x8 qreg[NT], doreg[NT];
@@ -88,8 +118,25 @@ __global__ __launch_bounds__(kBwdThreads, 2) void attn_bwd_dq_kernel(
         doreg[t] = *reinterpret_cast<const bf16x8*>(dO + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
     }
     const float sl2 = scale * kLog2e;
-    const float lse2 = LSE2[(int64_t)head * ws_stride + q_ld];
-    const float delta = DELTA[(int64_t)head * ws_stride + q_ld];
+    const float lse2 = LSE2[(int64_t)head * ws_stride + q_row];     // padded: +inf for q_row >= N
+    const float delta = DELTA[(int64_t)head * ws_stride + q_row];
+    // key offset c_r (inside a block starting at k0) is masked iff c_r > klim - k0
+    const int klim = (CAUSAL ? (q_row < N - 1 ? q_row : N - 1) : N - 1) - 4 * g;
+
+    const uint32_t sbase = lds_addr(smem);
+    uint32_t r_adr[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) r_adr[t] = sbase + 2 * tile_off<D>(ln, 2 * t + g);
+    uint32_t t_adr[NCB][2];
+    {
+        const int i = lane & 15, h = (lane >> 4) & 1;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+                t_adr[cb][hh] = sbase + 2 * (tile_off<D>(4 * g + (i >> 2) + 8 * hh, 4 * cb + 2 * h + ((i & 3) >> 1)) +
+                                             4 * (i & 1));
+    }
 
     f32x16 acc[NCB];
 #pragma unroll
@@ -97,61 +144,147 @@ __global__ __launch_bounds__(kBwdThreads, 2) void attn_bwd_dq_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
 
-    int k_end = N;
-    if (CAUSAL) { const int lim = q0 + kDqBQ; k_end = lim < N ? lim : N; }
-    const int n_kt = (k_end + kDqBK - 1) / kDqBK;
-    const int wave_qmin = q0 + wave * 32;
+    f32x16 s[2], dp[2];
+    bf16x8 krow[NT], vrow[NT];
+    bf16x4 kt_lo[2][NCB], kt_hi[2][NCB];
 
-    u32x4 kreg[IO::kPerThread], vreg[IO::kPerThread];
-    IO::load(kreg, Kh, row_stride, 0, N, tid);
-    IO::load(vreg, Vh, row_stride, 0, N, tid);
-
-    for (int kt = 0; kt < n_kt; ++kt) {
-        const int k0 = kt * kDqBK;
-        __syncthreads();
-        IO::store(kreg, k_row, RS, tid);
-        IO::store(kreg, k_tr, TS, tid);
-        IO::store(vreg, v_row, RS, tid);
-        __syncthreads();
-        if (kt + 1 < n_kt) {
-            IO::load(kreg, Kh, row_stride, k0 + kDqBK, N, tid);
-            IO::load(vreg, Vh, row_stride, k0 + kDqBK, N, tid);
+    auto read_krow = [&](auto slot_tag) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) krow[t] = lds_b128<KB + SL * TB>(r_adr[t]);
+    };
+    auto read_vrow = [&](auto slot_tag) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) vrow[t] = lds_b128<VB + SL * TB>(r_adr[t]);
+    };
+    auto read_transposed = [&](auto slot_tag) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            kt_lo[0][cb] = lds_tr_b64<KB + SL * TB>(t_adr[cb][0]);
+            kt_hi[0][cb] = lds_tr_b64<KB + SL * TB>(t_adr[cb][1]);
         }
-        if (CAUSAL && k0 > wave_qmin + 31) continue;
-
-        f32x16 s[NKB], dp[NKB];
 #pragma unroll
-        for (int b = 0; b < NKB; ++b) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { s[b][r] = 0.f; dp[b][r] = 0.f; }
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                s[b] = mfma32(lds_read_row8(k_row + (32 * b + ln) * RS + 16 * t + 8 * g), qreg[t], s[b]);
-                dp[b] = mfma32(lds_read_row8(v_row + (32 * b + ln) * RS + 16 * t + 8 * g), doreg[t], dp[b]);
-            }
+        for (int cb = 0; cb < NCB; ++cb) {
+            kt_lo[1][cb] = lds_tr_b64<KB + SL * TB + HALF>(t_adr[cb][0]);
+            kt_hi[1][cb] = lds_tr_b64<KB + SL * TB + HALF>(t_adr[cb][1]);
         }
-        const bool need_mask = (CAUSAL && k0 + kDqBK - 1 > wave_qmin) || (k0 + kDqBK > N);
+    };
+    auto tie_krow = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int b = 0; b < NKB; ++b)
+        for (int t = 0; t < NT; ++t) lds_tie(krow[t]);
+    };
+    auto tie_vrow = [&]() __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float p = fast_exp2(__builtin_fmaf(s[b][r], sl2, -lse2));
-                if (need_mask) {
-                    const int j = k0 + 32 * b + crow(r, g);
-                    if ((CAUSAL && j > q_row) || j >= N) p = 0.f;
-                }
-                s[b][r] = p * (dp[b][r] - delta);                      // dS^T
-            }
+        for (int t = 0; t < NT; ++t) lds_tie(vrow[t]);
+    };
+    auto tie_transposed = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int b = 0; b < NKB; ++b)
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const bf16x8 dsb = pack_b_operand(s[b], u);
+            for (int cb = 0; cb < NCB; ++cb) lds_tie(kt_lo[u][cb], kt_hi[u][cb]);
+    };
+    auto zero = [&](f32x16& x) __attribute__((always_inline)) {
 #pragma unroll
-                for (int cb = 0; cb < NCB; ++cb)
-                    acc[cb] = mfma32(lds_read_transposed_a(k_tr, TS, 32 * b + 16 * u, 32 * cb, lane), dsb, acc[cb]);
-            }
+        for (int r = 0; r < 16; ++r) x[r] = 0.f;
+    };
+
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    using S2 = std::integral_constant<int, 2>;
+    using S3 = std::integral_constant<int, 3>;
+
+    // ---- prologue: tiles 0, 1 resident; S^T, dP^T of block 0; then the row operands of block 1
+    wait_vm<2 * LPT>();
+    __syncthreads();
+    read_krow(S0{});
+    read_vrow(S0{});
+    wait_lgkm<0>();
+    tie_krow();
+    tie_vrow();
+    zero(s[0]); zero(dp[0]);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        s[0] = mfma32(krow[t], qreg[t], s[0]);
+        dp[0] = mfma32(vrow[t], doreg[t], dp[0]);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    read_krow(S1{});
+    read_vrow(S1{});
+
+    // LDS reads in flight at entry, oldest first: K rows of b+1, V rows of b+1.
+    auto iteration = [&](auto slot_tag, auto slot2_tag, int b) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+        constexpr int PAR = SL & 1;
+        const int krel = klim - b * kDqBK;
+        bf16x8 dsb[2];
+        auto softmax_half = [&](int u) __attribute__((always_inline)) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int r = 8 * u + e;
+                float x = __builtin_fmaf(s[PAR][r], sl2, -lse2);
+                x = (8 * (r >> 2) + (r & 3) > krel) ? -INFINITY : x;
+                const float p = fast_exp2(x);
+                dsb[u][e] = (bf16)(p * (dp[PAR][r] - delta));
+            }
+        };
+        auto interleave = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < NT; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);    // VALU
+                __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // transcendental
+            }
+        };
+
+        wait_lgkm<NT>();                              // K rows of b+1 (the V rows may still be in flight)
+        tie_krow();
+        __builtin_amdgcn_sched_barrier(0);
+        zero(s[PAR ^ 1]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) s[PAR ^ 1] = mfma32(krow[t], qreg[t], s[PAR ^ 1]);
+        softmax_half(0);
+        interleave();
+        lds_tie(dsb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        wait_lgkm<0>();
+        tie_vrow();
+        read_transposed(slot_tag);                    // K^T of block b, for region B
+        __builtin_amdgcn_sched_barrier(0);
+        zero(dp[PAR ^ 1]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) dp[PAR ^ 1] = mfma32(vrow[t], doreg[t], dp[PAR ^ 1]);
+        softmax_half(1);
+        interleave();
+        lds_tie(dsb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+
+        wait_lgkm<0>();
+        tie_transposed();
+        wait_vm<LPT>();                               // tile b+2 has landed; everyone is done with tile b
+        __syncthreads();
+        load_tile(SL, b + kDqRing);
+        read_krow(slot2_tag);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+                acc[cb] = mfma32(__builtin_shufflevector(kt_lo[u][cb], kt_hi[u][cb], 0, 1, 2, 3, 4, 5, 6, 7), dsb[u],
+                                 acc[cb]);
+        __builtin_amdgcn_sched_barrier(0);
+        read_vrow(slot2_tag);
+    };
+
+    for (int b = 0; b < nblk; b += 4) {
+        iteration(S0{}, S2{}, b);
+        if (b + 1 < nblk) iteration(S1{}, S3{}, b + 1);
+        if (b + 2 < nblk) iteration(S2{}, S0{}, b + 2);
+        if (b + 3 < nblk) iteration(S3{}, S1{}, b + 3);
+    }
+    wait_vm<0>();        // nothing may still be writing LDS when the workgroup ends
+    wait_lgkm<0>();
 
     if (q_row < N) {
         bf16* orow = dQ + hoff + (int64_t)q_row * row_stride;
@@ -505,10 +638,10 @@ static int launch_bwd(int stage_mask, const void* q, const void* k, const void* 
     }
     if (stage_mask & 4) {
         if (causal)
-            attn_bwd_dq_kernel<D, true><<<gq, dim3(kBwdThreads), 0, stream>>>(
+            attn_bwd_dq_kernel<D, true><<<gq, dim3(kDqThreads), 0, stream>>>(
                 Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)n_qtiles, st.row, st.head, scale);
         else
-            attn_bwd_dq_kernel<D, false><<<gq, dim3(kBwdThreads), 0, stream>>>(
+            attn_bwd_dq_kernel<D, false><<<gq, dim3(kDqThreads), 0, stream>>>(
                 Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)n_qtiles, st.row, st.head, scale);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
