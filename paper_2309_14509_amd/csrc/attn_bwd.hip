@@ -92,18 +92,13 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     const int nblk = (k_end + kDqBK - 1) / kDqBK;
 
     const typename Loader::LaneOffsets ld = Loader::lane_offsets(row_stride, wave, lane);
-    auto load_tile = [&](int slot, int tb) __attribute__((always_inline)) {
+    const typename Loader::TailOffsets ld_tail = Loader::tail_offsets(row_stride, wave, lane, N);
+    auto load_tile = [&](int slot, int tb) __attribute__((always_inline)) {     // branch-free
         tb = tb < nblk ? tb : nblk - 1;          // past the end the last tile is simply re-read
         const int r0 = tb * kDqBK;
-        bf16* kdst = smem + slot * TILE;
-        bf16* vdst = smem + (kDqRing + slot) * TILE;
-        if (r0 + kDqBK <= N) {
-            Loader::issue(kdst, Kh + (int64_t)r0 * row_stride, ld, wave);
-            Loader::issue(vdst, Vh + (int64_t)r0 * row_stride, ld, wave);
-        } else {
-            Loader::issue_clamped(kdst, Kh, row_stride, r0, N, wave, lane);
-            Loader::issue_clamped(vdst, Vh, row_stride, r0, N, wave, lane);
-        }
+        const bool is_tail = r0 + kDqBK > N;
+        Loader::issue_sel(smem + slot * TILE, Kh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
+        Loader::issue_sel(smem + (kDqRing + slot) * TILE, Vh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
     };
 #pragma unroll
     for (int i = 0; i < kDqRing; ++i) load_tile(i, i);
@@ -214,7 +209,8 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     read_vrow(S1{});
 
     // LDS reads in flight at entry, oldest first: K rows of b+1, V rows of b+1.
-    auto iteration = [&](auto slot_tag, auto slot2_tag, int b) __attribute__((always_inline)) {
+    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot2_tag, int b) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr int SL = decltype(slot_tag)::value;
         constexpr int PAR = SL & 1;
         const int krel = klim - b * kDqBK;
@@ -224,7 +220,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
             for (int e = 0; e < 8; ++e) {
                 const int r = 8 * u + e;
                 float x = __builtin_fmaf(s[PAR][r], sl2, -lse2);
-                x = (8 * (r >> 2) + (r & 3) > krel) ? -INFINITY : x;
+                if (MASKED) x = (8 * (r >> 2) + (r & 3) > krel) ? -INFINITY : x;
                 const float p = fast_exp2(x);
                 dsb[u][e] = (bf16)(p * (dp[PAR][r] - delta));
             }
@@ -233,7 +229,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);    // VALU
+                __builtin_amdgcn_sched_group_barrier(0x002, MASKED ? 7 : 5, 0);    // VALU
                 __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // transcendental
             }
         };
@@ -277,14 +273,42 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         read_vrow(slot2_tag);
     };
 
-    for (int b = 0; b < nblk; b += 4) {
-        iteration(S0{}, S2{}, b);
-        if (b + 1 < nblk) iteration(S1{}, S3{}, b + 1);
-        if (b + 2 < nblk) iteration(S2{}, S0{}, b + 2);
-        if (b + 3 < nblk) iteration(S3{}, S1{}, b + 3);
+    // Only blocks that reach past some query of the workgroup (the diagonal) or past the end of the
+    // sequence need the mask; all others run the variant without it.
+    const int first_masked = (CAUSAL ? (q0 < N ? q0 : N) : N) / kDqBK;
+    using Plain = std::integral_constant<bool, false>;
+    using Masked = std::integral_constant<bool, true>;
+    int b = 0;
+    for (; b + 3 < first_masked; b += 4) {          // first_masked is a multiple of 4 (q0 is one of 128)
+        iteration(Plain{}, S0{}, S2{}, b);
+        iteration(Plain{}, S1{}, S3{}, b + 1);
+        iteration(Plain{}, S2{}, S0{}, b + 2);
+        iteration(Plain{}, S3{}, S1{}, b + 3);
     }
-    wait_vm<0>();        // nothing may still be writing LDS when the workgroup ends
+    // The compiler may move registers (copies at control-flow joins, spills) without knowing that a
+    // hand-issued LDS read into them is still in flight, so outside the steady-state loop every
+    // iteration is followed by settle(): all reads landed, their registers tied.
+    auto settle = [&]() __attribute__((always_inline)) {
+        wait_lgkm<0>();
+        tie_krow();
+        tie_vrow();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    settle();
+    for (; b < nblk; b += 4) {                      // a handful of blocks at most
+        iteration(Masked{}, S0{}, S2{}, b);
+        settle();
+        if (b + 1 < nblk) { iteration(Masked{}, S1{}, S3{}, b + 1); settle(); }
+        if (b + 2 < nblk) { iteration(Masked{}, S2{}, S0{}, b + 2); settle(); }
+        if (b + 3 < nblk) { iteration(Masked{}, S3{}, S1{}, b + 3); settle(); }
+    }
+    // Nothing may still be writing LDS when the workgroup ends, and the operand reads issued for a
+    // block that does not exist must have landed before their (now dead) registers are reused.
+    wait_vm<0>();
     wait_lgkm<0>();
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) lds_tie(acc[cb]);
+    __builtin_amdgcn_sched_barrier(0);
 
     if (q_row < N) {
         bf16* orow = dQ + hoff + (int64_t)q_row * row_stride;
@@ -350,18 +374,13 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 
     // ---- global -> LDS tile loads (tile index clamped: past the end the last tile is simply re-read)
     const typename Loader::LaneOffsets ld = Loader::lane_offsets(row_stride, wave, lane);
-    auto load_tile = [&](int slot, int tb) __attribute__((always_inline)) {
+    const typename Loader::TailOffsets ld_tail = Loader::tail_offsets(row_stride, wave, lane, N);
+    auto load_tile = [&](int slot, int tb) __attribute__((always_inline)) {     // branch-free
         tb = tb < nblk ? tb : nblk - 1;
         const int r0 = tb * kDkvBQ;
-        bf16* qdst = smem + slot * TILE;
-        bf16* ddst = smem + (kDkvRing + slot) * TILE;
-        if (r0 + kDkvBQ <= N) {
-            Loader::issue(qdst, Qh + (int64_t)r0 * row_stride, ld, wave);
-            Loader::issue(ddst, dOh + (int64_t)r0 * row_stride, ld, wave);
-        } else {
-            Loader::issue_clamped(qdst, Qh, row_stride, r0, N, wave, lane);
-            Loader::issue_clamped(ddst, dOh, row_stride, r0, N, wave, lane);
-        }
+        const bool is_tail = r0 + kDkvBQ > N;
+        Loader::issue_sel(smem + slot * TILE, Qh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
+        Loader::issue_sel(smem + (kDkvRing + slot) * TILE, dOh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
         // row statistics: 64 floats each (the padded arrays make rows r0 .. r0+63 readable); every
         // wave issues the same two loads so that all waves count the same number of loads per tile
         float* sdst = stat + slot * (STAT / 4);
@@ -495,7 +514,9 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 
     // One iteration: block b lives in ring slot SL (its parity selects the s/dp set).
     // LDS reads in flight at entry, oldest first: statistics of b, Q rows of b+1, dO rows of b+1.
-    auto iteration = [&](auto slot_tag, auto slot1_tag, auto slot2_tag, int b) __attribute__((always_inline)) {
+    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot1_tag, auto slot2_tag, int b)
+                         __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr int SL = decltype(slot_tag)::value;
         constexpr int PAR = SL & 1;
         const int i0 = b * kDkvBQ;
@@ -507,7 +528,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
             for (int e = 0; e < 8; ++e) {
                 const int r = 8 * u + e;
                 float x = __builtin_fmaf(s[PAR][r], sl2, -lse4[r >> 2][r & 3]);
-                if (CAUSAL) x = (8 * (r >> 2) + (r & 3) < jrel) ? -INFINITY : x;
+                if (MASKED && CAUSAL) x = (8 * (r >> 2) + (r & 3) < jrel) ? -INFINITY : x;
                 const float p = fast_exp2(x);
                 const float ds = p * (dp[PAR][r] - del4[r >> 2][r & 3]);
                 pb[u][e] = (bf16)p;
@@ -518,7 +539,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);    // VALU
+                __builtin_amdgcn_sched_group_barrier(0x002, MASKED ? 8 : 6, 0);    // VALU
                 __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // transcendental
             }
         };
@@ -579,13 +600,49 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         read_rowdo(slot2_tag);
     };
 
-    for (int b = b0; b < nblk; b += 4) {
-        iteration(S0{}, S1{}, S2{}, b);
-        if (b + 1 < nblk) iteration(S1{}, S2{}, S3{}, b + 1);
-        if (b + 2 < nblk) iteration(S2{}, S3{}, S0{}, b + 2);
-        if (b + 3 < nblk) iteration(S3{}, S0{}, S1{}, b + 3);
+    // Only the blocks on the diagonal (queries that precede some key of the workgroup) need the mask.
+    using Plain = std::integral_constant<bool, false>;
+    using Masked = std::integral_constant<bool, true>;
+    // The masked blocks are exactly the first group of four (j0 is a multiple of 128, so b0 is one of 4).
+    // The compiler may move registers (copies at control-flow joins, spills) without knowing that a
+    // hand-issued LDS read into them is still in flight, so outside the steady-state loop every
+    // iteration is followed by settle(): all reads landed, their registers tied.
+    auto settle = [&]() __attribute__((always_inline)) {
+        wait_lgkm<0>();
+        tie_rowq();
+        tie_rowdo();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int b = b0;
+    settle();
+    if (CAUSAL && b < nblk) {
+        iteration(Masked{}, S0{}, S1{}, S2{}, b);
+        settle();
+        if (b + 1 < nblk) { iteration(Masked{}, S1{}, S2{}, S3{}, b + 1); settle(); }
+        if (b + 2 < nblk) { iteration(Masked{}, S2{}, S3{}, S0{}, b + 2); settle(); }
+        if (b + 3 < nblk) { iteration(Masked{}, S3{}, S0{}, S1{}, b + 3); settle(); }
+        b += 4;
     }
-    wait_vm<0>();        // nothing may still be writing LDS when the workgroup ends
+    for (; b + 3 < nblk; b += 4) {
+        iteration(Plain{}, S0{}, S1{}, S2{}, b);
+        iteration(Plain{}, S1{}, S2{}, S3{}, b + 1);
+        iteration(Plain{}, S2{}, S3{}, S0{}, b + 2);
+        iteration(Plain{}, S3{}, S0{}, S1{}, b + 3);
+    }
+    settle();
+    if (b < nblk) {                                 // up to three trailing blocks
+        iteration(Plain{}, S0{}, S1{}, S2{}, b);
+        settle();
+        if (b + 1 < nblk) { iteration(Plain{}, S1{}, S2{}, S3{}, b + 1); settle(); }
+        if (b + 2 < nblk) { iteration(Plain{}, S2{}, S3{}, S0{}, b + 2); settle(); }
+    }
+    // Nothing may still be writing LDS when the workgroup ends, and the operand reads issued for a
+    // block that does not exist must have landed before their (now dead) registers are reused.
+    wait_vm<0>();
+    wait_lgkm<0>();
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) lds_tie(dk_acc[cb], dv_acc[cb]);
+    __builtin_amdgcn_sched_barrier(0);
 
     if (j_col < N) {
         bf16* krow = dK + hoff + (int64_t)j_col * row_stride;

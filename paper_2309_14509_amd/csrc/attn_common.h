@@ -164,6 +164,36 @@ template <int D, int ROWS, int WAVES, typename S = SwzBoth> struct DirectTile {
                                              ULY_LDS(void, tile + (wave + i * WAVES) * kRowsPerSlab * D), 16, 0, 0);
         }
     }
+    // Branch-free variant for loops that must stay one basic block.  `tail` holds this lane's offsets
+    // for the one tile that runs past the end of the tensor (rows clamped to the last valid row; the
+    // callers mask them out); `is_tail` is uniform.
+    struct TailOffsets {
+        uint32_t off[kPerWave];
+    };
+    __device__ static __forceinline__ TailOffsets tail_offsets(int64_t row_stride, int wave, int lane, int n_rows) {
+        TailOffsets to;
+        const int tail_r0 = (n_rows / ROWS) * ROWS;                  // first row of the ragged tile
+        const int lr = lane / kChunksPerRow, pc = lane % kChunksPerRow;
+#pragma unroll
+        for (int i = 0; i < kPerWave; ++i) {
+            const int r = (wave + i * WAVES) * kRowsPerSlab + lr;
+            int gr = tail_r0 + r;
+            gr = gr < n_rows ? gr : n_rows - 1;
+            to.off[i] = (uint32_t)((gr - tail_r0) * row_stride * 2) + (uint32_t)(((pc ^ S::template f<D>(r)) << 4));
+        }
+        return to;
+    }
+    __device__ static __forceinline__ void issue_sel(bf16* tile, const bf16* tile_base, const LaneOffsets& lo,
+                                                     const TailOffsets& to, bool is_tail, int wave) {
+#pragma unroll
+        for (int i = 0; i < kPerWave; ++i) {
+            const uint32_t voff = is_tail ? to.off[i] : lo.off0;
+            const int64_t soff = is_tail ? 0 : i * lo.step_bytes;
+            const char* src = reinterpret_cast<const char*>(tile_base) + soff + voff;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             ULY_LDS(void, tile + (wave + i * WAVES) * kRowsPerSlab * D), 16, 0, 0);
+        }
+    }
     // Same for a tile that may run past the end of the tensor: rows at or beyond n_rows are clamped
     // to the last valid row (callers mask them out).
     __device__ static __forceinline__ void issue_clamped(bf16* tile, const bf16* base, int64_t row_stride, int row0,
