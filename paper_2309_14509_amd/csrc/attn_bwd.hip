@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         wait_lgkm<0>();
         tie_transposed();
         wait_vm<LPT>();                               // tile b+2 has landed; everyone is done with tile b
-        __syncthreads();
+        barrier_no_drain();
         load_tile(SL, b + kDqRing);
         read_krow(slot2_tag);
         __builtin_amdgcn_sched_barrier(0);
@@ -375,19 +375,33 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     // ---- global -> LDS tile loads (tile index clamped: past the end the last tile is simply re-read)
     const typename Loader::LaneOffsets ld = Loader::lane_offsets(row_stride, wave, lane);
     const typename Loader::TailOffsets ld_tail = Loader::tail_offsets(row_stride, wave, lane, N);
-    auto load_tile = [&](int slot, int tb) __attribute__((always_inline)) {     // branch-free
+    // The loads of one tile, in pieces (PART 0: Q, 1: dO, 2: row statistics) so that the hot loop can
+    // spread them between its MFMAs.  Branch-free.
+    auto load_part = [&](auto part_tag, int slot, int tb) __attribute__((always_inline)) {
+        constexpr int PART = decltype(part_tag)::value;
         tb = tb < nblk ? tb : nblk - 1;
         const int r0 = tb * kDkvBQ;
         const bool is_tail = r0 + kDkvBQ > N;
-        Loader::issue_sel(smem + slot * TILE, Qh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
-        Loader::issue_sel(smem + (kDkvRing + slot) * TILE, dOh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
-        // row statistics: 64 floats each (the padded arrays make rows r0 .. r0+63 readable); every
-        // wave issues the same two loads so that all waves count the same number of loads per tile
-        float* sdst = stat + slot * (STAT / 4);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(lse_h + r0 + lane),
-                                         ULY_LDS(void, sdst), 4, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(del_h + r0 + lane),
-                                         ULY_LDS(void, sdst + 64), 4, 0, 0);
+        if (PART == 0) Loader::issue_sel(smem + slot * TILE, Qh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
+        if (PART == 1)
+            Loader::issue_sel(smem + (kDkvRing + slot) * TILE, dOh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
+        if (PART == 2) {
+            // row statistics: 64 floats each (the padded arrays make rows r0 .. r0+63 readable); every
+            // wave issues the same two loads so that all waves count the same number of loads per tile
+            float* sdst = stat + slot * (STAT / 4);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(lse_h + r0 + lane),
+                                             ULY_LDS(void, sdst), 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(del_h + r0 + lane),
+                                             ULY_LDS(void, sdst + 64), 4, 0, 0);
+        }
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using P2 = std::integral_constant<int, 2>;
+    auto load_tile = [&](int slot, int tb) __attribute__((always_inline)) {
+        load_part(P0{}, slot, tb);
+        load_part(P1{}, slot, tb);
+        load_part(P2{}, slot, tb);
     };
 #pragma unroll
     for (int i = 0; i < kDkvRing; ++i) load_tile(i, b0 + i);
@@ -438,6 +452,12 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 #pragma unroll
         for (int t = 0; t < NT; ++t) rowq[t] = lds_b128<QB + SL * TB>(r_adr[t]);
     };
+    auto read_rowq_part = [&](auto slot_tag, int t0, int t1) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            if (t >= t0 && t < t1) rowq[t] = lds_b128<QB + SL * TB>(r_adr[t]);
+    };
     auto read_rowdo = [&](auto slot_tag) __attribute__((always_inline)) {
         constexpr int SL = decltype(slot_tag)::value;
 #pragma unroll
@@ -450,22 +470,18 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         del4[0] = lds_f32x4<SL * STAT + 256>(st_adr); del4[1] = lds_f32x4<SL * STAT + 288>(st_adr);
         del4[2] = lds_f32x4<SL * STAT + 320>(st_adr); del4[3] = lds_f32x4<SL * STAT + 352>(st_adr);
     };
-    auto read_transposed = [&](auto slot_tag) __attribute__((always_inline)) {
+    // transposed operands of rows 0-15 (U = 0) or 16-31 (U = 1) of a block; one channel block cb
+    auto read_transposed = [&](auto slot_tag, auto u_tag, int cb) __attribute__((always_inline)) {
         constexpr int SL = decltype(slot_tag)::value;
+        constexpr int U = decltype(u_tag)::value;
 #pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) {
-            dot_lo[0][cb] = lds_tr_b64<DOB + SL * TB>(t_adr[cb][0]);
-            dot_hi[0][cb] = lds_tr_b64<DOB + SL * TB>(t_adr[cb][1]);
-            qt_lo[0][cb] = lds_tr_b64<QB + SL * TB>(t_adr[cb][0]);
-            qt_hi[0][cb] = lds_tr_b64<QB + SL * TB>(t_adr[cb][1]);
-        }
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) {
-            dot_lo[1][cb] = lds_tr_b64<DOB + SL * TB + HALF>(t_adr[cb][0]);
-            dot_hi[1][cb] = lds_tr_b64<DOB + SL * TB + HALF>(t_adr[cb][1]);
-            qt_lo[1][cb] = lds_tr_b64<QB + SL * TB + HALF>(t_adr[cb][0]);
-            qt_hi[1][cb] = lds_tr_b64<QB + SL * TB + HALF>(t_adr[cb][1]);
-        }
+        for (int c = 0; c < NCB; ++c)
+            if (c == cb) {
+                dot_lo[U][c] = lds_tr_b64<DOB + SL * TB + U * HALF>(t_adr[c][0]);
+                dot_hi[U][c] = lds_tr_b64<DOB + SL * TB + U * HALF>(t_adr[c][1]);
+                qt_lo[U][c] = lds_tr_b64<QB + SL * TB + U * HALF>(t_adr[c][0]);
+                qt_hi[U][c] = lds_tr_b64<QB + SL * TB + U * HALF>(t_adr[c][1]);
+            }
     };
     auto tie_rowq = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -476,12 +492,12 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 #pragma unroll
         for (int t = 0; t < NT; ++t) lds_tie(rowdo[t]);
     };
-    auto tie_transposed = [&]() __attribute__((always_inline)) {
+    auto tie_transposed = [&](int u) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) lds_tie(dot_lo[u][cb], dot_hi[u][cb], qt_lo[u][cb], qt_hi[u][cb]);
+        for (int cb = 0; cb < NCB; ++cb) lds_tie(dot_lo[u][cb], dot_hi[u][cb], qt_lo[u][cb], qt_hi[u][cb]);
     };
+    using U0 = std::integral_constant<int, 0>;
+    using U1 = std::integral_constant<int, 1>;
     auto zero = [&](f32x16& x) __attribute__((always_inline)) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) x[r] = 0.f;
@@ -557,7 +573,8 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         __builtin_amdgcn_sched_barrier(0);
         wait_lgkm<0>();                               // dO rows of b+1
         tie_rowdo();
-        read_transposed(slot_tag);                    // for region B; lands during region A2
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) read_transposed(slot_tag, U0{}, cb);   // for region B1; lands during A2
         __builtin_amdgcn_sched_barrier(0);
         // ---- region A2: dP of block b+1 || P, dS of rows 16-31 of block b
         zero(dp[PAR ^ 1]);
@@ -567,37 +584,64 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         interleave();
         lds_tie(pb[1], dsb[1]);
         __builtin_amdgcn_sched_barrier(0);
-
-        // ---- tile b+2 has landed (its loads were issued two iterations ago); everyone is done with tile b
         wait_lgkm<0>();
-        tie_transposed();
-        wait_vm<LPT>();
-        __syncthreads();
-        load_tile(SL, b + kDkvRing);
-        read_stats(slot1_tag);                        // statistics of block b+1
+        tie_transposed(0);
         __builtin_amdgcn_sched_barrier(0);
 
-        // ---- region B: dV^T += dO^T P, dK^T += Q^T dS; the row operands of block b+2 are fetched behind
-        // each half, into the registers its transposed operands leave free
+        // ---- region B: dV^T += dO^T P, dK^T += Q^T dS.  Every other instruction of the iteration is
+        // placed behind one of these MFMAs so that it issues while the matrix pipe is busy.
+        // B1 (rows 0-15): the transposed operands of rows 16-31 go into the registers the dO rows left
+        // free, early enough to have landed when B1 ends.
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
             const bf16x8 da = __builtin_shufflevector(dot_lo[0][cb], dot_hi[0][cb], 0, 1, 2, 3, 4, 5, 6, 7);
             const bf16x8 qa = __builtin_shufflevector(qt_lo[0][cb], qt_hi[0][cb], 0, 1, 2, 3, 4, 5, 6, 7);
             dv_acc[cb] = mfma32(da, pb[0], dv_acc[cb]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (2 * cb < NCB) read_transposed(slot_tag, U1{}, 2 * cb);
+            __builtin_amdgcn_sched_barrier(0);
             dk_acc[cb] = mfma32(qa, dsb[0], dk_acc[cb]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (2 * cb + 1 < NCB) read_transposed(slot_tag, U1{}, 2 * cb + 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // ---- everyone is done with tile b (its last reads have landed) and tile b+2 has landed (its
+        // loads were issued two iterations ago)
+        wait_lgkm<0>();
+        tie_transposed(1);
+        wait_vm<LPT>();
+        barrier_no_drain();
         __builtin_amdgcn_sched_barrier(0);
-        read_rowq(slot2_tag);
-        __builtin_amdgcn_sched_barrier(0);
+        // B2 (rows 16-31): Q rows of block b+2 (into the registers of the transposed operands B1 used),
+        // statistics of block b+1, and the loads of tile b+4 into the slot of tile b
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
             const bf16x8 da = __builtin_shufflevector(dot_lo[1][cb], dot_hi[1][cb], 0, 1, 2, 3, 4, 5, 6, 7);
             const bf16x8 qa = __builtin_shufflevector(qt_lo[1][cb], qt_hi[1][cb], 0, 1, 2, 3, 4, 5, 6, 7);
             dv_acc[cb] = mfma32(da, pb[1], dv_acc[cb]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (NCB == 4) {
+                if (cb == 0) read_rowq_part(slot2_tag, 0, 4);
+                if (cb == 1) read_stats(slot1_tag);
+                if (cb == 2) load_part(P1{}, SL, b + kDkvRing);
+            } else {
+                if (cb == 0) read_rowq_part(slot2_tag, 0, NT);
+                if (cb == 1) { load_part(P0{}, SL, b + kDkvRing); load_part(P1{}, SL, b + kDkvRing); }
+            }
+            __builtin_amdgcn_sched_barrier(0);
             dk_acc[cb] = mfma32(qa, dsb[1], dk_acc[cb]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (NCB == 4) {
+                if (cb == 0) read_rowq_part(slot2_tag, 4, 8);
+                if (cb == 1) load_part(P0{}, SL, b + kDkvRing);
+                if (cb == 2) load_part(P2{}, SL, b + kDkvRing);
+            } else {
+                if (cb == 0) read_stats(slot1_tag);
+                if (cb == 1) load_part(P2{}, SL, b + kDkvRing);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
-        read_rowdo(slot2_tag);
+        read_rowdo(slot2_tag);                        // dO rows of block b+2, into the registers B2's operands used
     };
 
     // Only the blocks on the diagonal (queries that precede some key of the workgroup) need the mask.

@@ -261,6 +261,10 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 }
 
 // Wait until every direct-to-LDS load this wave has issued has landed.
+// Workgroup barrier that implies no memory waits.  (__syncthreads() makes the compiler drain every
+// outstanding load first, which would collapse a ring of tiles in flight to a single one; callers of
+// this one wait for exactly the loads and LDS reads they depend on.)
+__device__ __forceinline__ void barrier_no_drain() { asm volatile("s_barrier" ::: "memory"); }
 __device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // LDS row strides (elements).  Row reads (16 B per lane, 16 lanes of consecutive rows per bank

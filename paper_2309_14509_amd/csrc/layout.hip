@@ -8,7 +8,9 @@
 // shapes of interest, so 16-byte lanes are coalesced on both the read and the write side
 // without staging through LDS: a wavefront covers 1 KiB, i.e. whole runs or large pieces of one.
 // A workgroup takes a block of whole A-rows, so its reads are one contiguous range and its
-// writes are `groups` contiguous ranges.
+// writes are `groups` contiguous ranges.  Workgroups are small (8 KiB, one 16-byte element per
+// lane): measured on MI355X, HBM streams best with very many small workgroups in flight rather
+// than with several loads in flight per lane.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -37,8 +39,9 @@ __device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv f) {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 256;
-constexpr int kUnroll = 8;
+constexpr int kThreads = 512;
+constexpr int kUnroll = 1;
+constexpr int kTileBytes = 8192;   // per workgroup (whole rows, at least one)
 
 // TO_B = true : dst(B) <- src(A)      TO_B = false : dst(A) <- src(B)
 template <typename Vec, bool TO_B>
@@ -84,7 +87,8 @@ static int launch_regroup(const void* src, void* dst, int64_t rows, int64_t grou
     const int64_t run_vecs = run_bytes / (int64_t)sizeof(Vec);
     const int64_t row_vecs = run_vecs * groups;
     if (row_vecs >= (1ll << 24)) return ULY_ERR_SHAPE;   // keeps every in-tile index far below 2^31
-    uint32_t tile_rows = (uint32_t)(row_vecs >= 2048 ? 1 : 2048 / row_vecs);
+    const int64_t tile_vecs = kTileBytes / (int64_t)sizeof(Vec);
+    uint32_t tile_rows = (uint32_t)(row_vecs >= tile_vecs ? 1 : tile_vecs / row_vecs);
     const int64_t blocks = (rows + tile_rows - 1) / tile_rows;
     if (blocks <= 0) return ULY_OK;
     if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
