@@ -18,7 +18,7 @@ namespace uly {
 constexpr int kBwdThreads = 256;
 
 // ------------------------------------------------------------------------------------------
-// Row statistics for the backward kernels, in a padded [Hl, stride] layout (stride >= N + 64):
+// Row statistics for the backward kernels, in a padded [Hl, stride] layout (stride >= N rounded up to 128, + 64):
 //   delta[h, i] = sum_c dO[i,h,c] * O[i,h,c]        lse2[h, i] = LSE[h, i] * log2(e)
 // Rows N .. stride-1 get delta = 0 and lse2 = +inf, so that a padding row's probability
 // exp2(s - lse2) is exactly 0 without any test in the consumers.
@@ -360,17 +360,24 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     __shared__ __attribute__((aligned(256))) float stat[kDkvRing * (STAT / 4)];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ln = lane & 31;
-    const int head = blockIdx.x / n_ktiles;
-    const int ktile = blockIdx.x - head * n_ktiles;          // key tile 0 is the heaviest: first
-    const int j0 = ktile * kDkvBK;
+    // Work assignment (causal): a workgroup takes key tile `pr` and then its mirror image
+    // n_ktiles-1-pr, so every workgroup does the same amount of work.  It walks the query blocks of
+    // the first tile downwards from the end of the sequence and those of the second upwards from its
+    // diagonal: at any moment all workgroups that started together read one of only two query
+    // blocks, which keeps the Q/dO stream in the L2 caches instead of re-fetching it per workgroup.
+    const int n_pairs = CAUSAL ? (n_ktiles + 1) / 2 : n_ktiles;
+    const int head = blockIdx.x / n_pairs;
+    const int pr = blockIdx.x - head * n_pairs;
     const int64_t hoff = (int64_t)head * head_stride;
     const bf16* Qh = Q + hoff;
     const bf16* dOh = dO + hoff;
     const float* lse_h = LSE2 + (int64_t)head * ws_stride;
     const float* del_h = DELTA + (int64_t)head * ws_stride;
 
+    // Query blocks are walked in whole groups of four: blocks nblk .. nblk4-1 do not exist, their rows
+    // read the padded statistics (probability exactly 0) and the data of the last real block.
     const int nblk = (N + kDkvBQ - 1) / kDkvBQ;
-    const int b0 = CAUSAL ? j0 / kDkvBQ : 0;
+    const int nblk4 = (nblk + 3) & ~3;
 
     // ---- global -> LDS tile loads (tile index clamped: past the end the last tile is simply re-read)
     const typename Loader::LaneOffsets ld = Loader::lane_offsets(row_stride, wave, lane);
@@ -379,6 +386,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     // spread them between its MFMAs.  Branch-free.
     auto load_part = [&](auto part_tag, int slot, int tb) __attribute__((always_inline)) {
         constexpr int PART = decltype(part_tag)::value;
+        const int rs = tb * kDkvBQ;                     // statistics: the block's own rows (padded past N)
         tb = tb < nblk ? tb : nblk - 1;
         const int r0 = tb * kDkvBQ;
         const bool is_tail = r0 + kDkvBQ > N;
@@ -386,12 +394,12 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         if (PART == 1)
             Loader::issue_sel(smem + (kDkvRing + slot) * TILE, dOh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
         if (PART == 2) {
-            // row statistics: 64 floats each (the padded arrays make rows r0 .. r0+63 readable); every
+            // row statistics: 64 floats each (the padded arrays make rows r0 .. r0+63 readable, also for blocks past the end); every
             // wave issues the same two loads so that all waves count the same number of loads per tile
             float* sdst = stat + slot * (STAT / 4);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(lse_h + r0 + lane),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(lse_h + rs + lane),
                                              ULY_LDS(void, sdst), 4, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(del_h + r0 + lane),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(del_h + rs + lane),
                                              ULY_LDS(void, sdst + 64), 4, 0, 0);
         }
     };
@@ -403,20 +411,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         load_part(P1{}, slot, tb);
         load_part(P2{}, slot, tb);
     };
-#pragma unroll
-    for (int i = 0; i < kDkvRing; ++i) load_tile(i, b0 + i);
-
-    // ---- this lane's key: K and V rows as B operands
-    const int j_col = j0 + wave * 32 + ln;
-    const int j_ld = j_col < N ? j_col : N - 1;
-    bf16x8 kreg[NT], vreg[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        kreg[t] = *reinterpret_cast<const bf16x8*>(K + hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
-        vreg[t] = *reinterpret_cast<const bf16x8*>(V + hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
-    }
     const float sl2 = scale * kLog2e;
-    const int jcol_g = j_col - 4 * g;            // causal test: row offset c_r is masked iff c_r < jcol_g - i0
 
     // ---- per-lane LDS byte addresses inside a tile (ring slot, tensor and 16-row offsets are immediates)
     const uint32_t sbase = lds_addr(smem);
@@ -434,6 +429,33 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
                                              4 * (i & 1));
     }
     const uint32_t st_adr = lds_addr(stat) + 16 * g;    // rows 8q+4g .. +3 of a slot: immediate 32q (+256: delta)
+
+    const int n_parts = (CAUSAL && n_ktiles - 1 - pr != pr) ? 2 : 1;
+#pragma unroll 1
+    for (int part = 0; part < n_parts; ++part) {
+    const int ktile = part == 0 ? pr : n_ktiles - 1 - pr;
+    const int dir = (CAUSAL && part == 0) ? -1 : 1;           // walking direction over the query blocks
+    const int j0 = ktile * kDkvBK;
+    const int b0 = CAUSAL ? j0 / kDkvBQ : 0;                  // first block that sees a key of this tile
+    const int cnt = nblk4 - b0;                               // blocks to process (a multiple of 4)
+    // block at walk position p; positions past the end re-read the last one (their tiles are never used)
+    auto blk = [&](int p) __attribute__((always_inline)) {
+        p = p < cnt ? p : cnt - 1;
+        return dir > 0 ? b0 + p : nblk4 - 1 - p;
+    };
+#pragma unroll
+    for (int i = 0; i < kDkvRing; ++i) load_tile(i, blk(i));
+
+    // ---- this lane's key: K and V rows as B operands
+    const int j_col = j0 + wave * 32 + ln;
+    const int j_ld = j_col < N ? j_col : N - 1;
+    bf16x8 kreg[NT], vreg[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        kreg[t] = *reinterpret_cast<const bf16x8*>(K + hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
+        vreg[t] = *reinterpret_cast<const bf16x8*>(V + hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
+    }
+    const int jcol_g = j_col - 4 * g;            // causal test: row offset c_r is masked iff c_r < jcol_g - i0
 
     f32x16 dk_acc[NCB], dv_acc[NCB];
 #pragma unroll
@@ -508,8 +530,8 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     using S2 = std::integral_constant<int, 2>;
     using S3 = std::integral_constant<int, 3>;
 
-    // ---- prologue: tiles b0, b0+1 resident; S, dP of block b0; then (in this order) the statistics of
-    // b0 and the row operands of b0+1
+    // ---- prologue: the tiles of positions 0, 1 resident; S, dP of position 0; then (in this order) the
+    // statistics of position 0 and the row operands of position 1
     wait_vm<2 * LPT>();
     __syncthreads();
     read_rowq(S0{});
@@ -528,15 +550,17 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     read_rowq(S1{});
     read_rowdo(S1{});
 
-    // One iteration: block b lives in ring slot SL (its parity selects the s/dp set).
+    // One iteration: walk position p (block b) lives in ring slot SL (its parity selects the s/dp set);
+    // "b+1", "b+2" below mean the blocks of the next positions.
     // LDS reads in flight at entry, oldest first: statistics of b, Q rows of b+1, dO rows of b+1.
-    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot1_tag, auto slot2_tag, int b)
+    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot1_tag, auto slot2_tag, int p)
                          __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr int SL = decltype(slot_tag)::value;
         constexpr int PAR = SL & 1;
-        const int i0 = b * kDkvBQ;
+        const int i0 = blk(p) * kDkvBQ;
         const int jrel = jcol_g - i0;
+        const int b_next = blk(p + kDkvRing);          // the tile fetched into this position's slot
         bf16x8 pb[2], dsb[2];
         // P and dS of 8 rows of block b (vector pipe)
         auto softmax_half = [&](int u) __attribute__((always_inline)) {
@@ -623,31 +647,31 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
             if (NCB == 4) {
                 if (cb == 0) read_rowq_part(slot2_tag, 0, 4);
                 if (cb == 1) read_stats(slot1_tag);
-                if (cb == 2) load_part(P1{}, SL, b + kDkvRing);
+                if (cb == 2) load_part(P1{}, SL, b_next);
             } else {
                 if (cb == 0) read_rowq_part(slot2_tag, 0, NT);
-                if (cb == 1) { load_part(P0{}, SL, b + kDkvRing); load_part(P1{}, SL, b + kDkvRing); }
+                if (cb == 1) { load_part(P0{}, SL, b_next); load_part(P1{}, SL, b_next); }
             }
             __builtin_amdgcn_sched_barrier(0);
             dk_acc[cb] = mfma32(qa, dsb[1], dk_acc[cb]);
             __builtin_amdgcn_sched_barrier(0);
             if (NCB == 4) {
                 if (cb == 0) read_rowq_part(slot2_tag, 4, 8);
-                if (cb == 1) load_part(P0{}, SL, b + kDkvRing);
-                if (cb == 2) load_part(P2{}, SL, b + kDkvRing);
+                if (cb == 1) load_part(P0{}, SL, b_next);
+                if (cb == 2) load_part(P2{}, SL, b_next);
             } else {
                 if (cb == 0) read_stats(slot1_tag);
-                if (cb == 1) load_part(P2{}, SL, b + kDkvRing);
+                if (cb == 1) load_part(P2{}, SL, b_next);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
         read_rowdo(slot2_tag);                        // dO rows of block b+2, into the registers B2's operands used
     };
 
-    // Only the blocks on the diagonal (queries that precede some key of the workgroup) need the mask.
+    // Only the four blocks on the diagonal (queries that precede some key of the workgroup) need the
+    // mask; they come first when walking up and last when walking down.
     using Plain = std::integral_constant<bool, false>;
     using Masked = std::integral_constant<bool, true>;
-    // The masked blocks are exactly the first group of four (j0 is a multiple of 128, so b0 is one of 4).
     // The compiler may move registers (copies at control-flow joins, spills) without knowing that a
     // hand-issued LDS read into them is still in flight, so outside the steady-state loop every
     // iteration is followed by settle(): all reads landed, their registers tied.
@@ -657,30 +681,30 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         tie_rowdo();
         __builtin_amdgcn_sched_barrier(0);
     };
-    int b = b0;
+    int p = 0;
     settle();
-    if (CAUSAL && b < nblk) {
-        iteration(Masked{}, S0{}, S1{}, S2{}, b);
-        settle();
-        if (b + 1 < nblk) { iteration(Masked{}, S1{}, S2{}, S3{}, b + 1); settle(); }
-        if (b + 2 < nblk) { iteration(Masked{}, S2{}, S3{}, S0{}, b + 2); settle(); }
-        if (b + 3 < nblk) { iteration(Masked{}, S3{}, S0{}, S1{}, b + 3); settle(); }
-        b += 4;
+    if (CAUSAL && dir > 0) {
+        iteration(Masked{}, S0{}, S1{}, S2{}, 0); settle();
+        iteration(Masked{}, S1{}, S2{}, S3{}, 1); settle();
+        iteration(Masked{}, S2{}, S3{}, S0{}, 2); settle();
+        iteration(Masked{}, S3{}, S0{}, S1{}, 3); settle();
+        p = 4;
     }
-    for (; b + 3 < nblk; b += 4) {
-        iteration(Plain{}, S0{}, S1{}, S2{}, b);
-        iteration(Plain{}, S1{}, S2{}, S3{}, b + 1);
-        iteration(Plain{}, S2{}, S3{}, S0{}, b + 2);
-        iteration(Plain{}, S3{}, S0{}, S1{}, b + 3);
+    const int plain_end = (CAUSAL && dir < 0) ? cnt - 4 : cnt;
+    for (; p < plain_end; p += 4) {
+        iteration(Plain{}, S0{}, S1{}, S2{}, p);
+        iteration(Plain{}, S1{}, S2{}, S3{}, p + 1);
+        iteration(Plain{}, S2{}, S3{}, S0{}, p + 2);
+        iteration(Plain{}, S3{}, S0{}, S1{}, p + 3);
     }
     settle();
-    if (b < nblk) {                                 // up to three trailing blocks
-        iteration(Plain{}, S0{}, S1{}, S2{}, b);
-        settle();
-        if (b + 1 < nblk) { iteration(Plain{}, S1{}, S2{}, S3{}, b + 1); settle(); }
-        if (b + 2 < nblk) { iteration(Plain{}, S2{}, S3{}, S0{}, b + 2); settle(); }
+    if (CAUSAL && dir < 0) {
+        iteration(Masked{}, S0{}, S1{}, S2{}, p); settle();
+        iteration(Masked{}, S1{}, S2{}, S3{}, p + 1); settle();
+        iteration(Masked{}, S2{}, S3{}, S0{}, p + 2); settle();
+        iteration(Masked{}, S3{}, S0{}, S1{}, p + 3); settle();
     }
-    // Nothing may still be writing LDS when the workgroup ends, and the operand reads issued for a
+    // Nothing may still be writing LDS when this key tile ends, and the operand reads issued for a
     // block that does not exist must have landed before their (now dead) registers are reused.
     wait_vm<0>();
     wait_lgkm<0>();
@@ -705,10 +729,12 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
                 *reinterpret_cast<bf16x4*>(vrow + 32 * cb + 8 * rq + 4 * g) = wv;
             }
     }
+    barrier_no_drain();          // every wave is done with the ring before the next key tile refills it
+    }   // key tiles of this workgroup
 }
 
 // padded row stride of the statistics arrays in the workspace
-inline int64_t stats_stride(int64_t N) { return ((N + 63) / 64) * 64 + 64; }
+inline int64_t stats_stride(int64_t N) { return ((N + 127) / 128) * 128 + 64; }
 
 template <int D>
 static int launch_bwd(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
@@ -721,7 +747,8 @@ static int launch_bwd(int stage_mask, const void* q, const void* k, const void* 
     const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (N + kDkvBK - 1) / kDkvBK;
     if (delta_blocks > 0x7FFFFFFFll || n_qtiles * Hl > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     const bf16 *Q = (const bf16*)q, *K = (const bf16*)k, *V = (const bf16*)v, *dO = (const bf16*)dout;
-    const dim3 gkv((uint32_t)(n_ktiles * Hl)), gq((uint32_t)(n_qtiles * Hl));
+    const int64_t n_kwg = causal ? (n_ktiles + 1) / 2 : n_ktiles;     // causal: a workgroup takes a pair of key tiles
+    const dim3 gkv((uint32_t)(n_kwg * Hl)), gq((uint32_t)(n_qtiles * Hl));
 
     if (stage_mask & 1) {
         attn_bwd_delta_kernel<D><<<dim3((uint32_t)delta_blocks), dim3(256), 0, stream>>>(
