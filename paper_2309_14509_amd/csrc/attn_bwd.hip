@@ -80,43 +80,32 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     __shared__ __attribute__((aligned(1024))) bf16 smem[2 * kDqRing * TILE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ln = lane & 31;
-    const int head = blockIdx.x / n_qtiles;
-    const int qt = CAUSAL ? n_qtiles - 1 - (blockIdx.x - head * n_qtiles) : blockIdx.x - head * n_qtiles;
-    const int q0 = qt * kDqBQ;
+    // Work assignment (causal): a workgroup takes query tile n_qtiles-1-pr and then its mirror image
+    // pr, so every workgroup does the same amount of work.  It walks the key blocks of the first tile
+    // upwards from the start of the sequence and those of the second downwards from its diagonal: at
+    // any moment all workgroups that started together read one of only two key blocks, which keeps
+    // the K/V stream in the L2 caches instead of re-fetching it per workgroup.
+    const int n_pairs = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;
+    const int head = blockIdx.x / n_pairs;
+    const int pr = blockIdx.x - head * n_pairs;
     const int64_t hoff = (int64_t)head * head_stride;
     const bf16* Kh = K + hoff;
     const bf16* Vh = V + hoff;
 
-    int k_end = N;
-    if (CAUSAL) { const int lim = q0 + kDqBQ; k_end = lim < N ? lim : N; }
-    const int nblk = (k_end + kDqBK - 1) / kDqBK;
+    // Key blocks are walked in whole groups of four; blocks nblk .. do not exist (all their keys are
+    // masked) and re-read the data of the last real block.
+    const int nblk = (N + kDqBK - 1) / kDqBK;
 
     const typename Loader::LaneOffsets ld = Loader::lane_offsets(row_stride, wave, lane);
     const typename Loader::TailOffsets ld_tail = Loader::tail_offsets(row_stride, wave, lane, N);
     auto load_tile = [&](int slot, int tb) __attribute__((always_inline)) {     // branch-free
-        tb = tb < nblk ? tb : nblk - 1;          // past the end the last tile is simply re-read
+        tb = tb < nblk ? tb : nblk - 1;          // blocks past the end re-read the last real one
         const int r0 = tb * kDqBK;
         const bool is_tail = r0 + kDqBK > N;
         Loader::issue_sel(smem + slot * TILE, Kh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
         Loader::issue_sel(smem + (kDqRing + slot) * TILE, Vh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
     };
-#pragma unroll
-    for (int i = 0; i < kDqRing; ++i) load_tile(i, i);
-
-    // ---- this lane's query: Q and dO rows as B operands, its two row statistics
-    const int q_row = q0 + wave * 32 + ln;
-    const int q_ld = q_row < N ? q_row : N - 1;
-    bf16x8 qreg[NT], doreg[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        qreg[t] = *reinterpret_cast<const bf16x8*>(Q + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
-        doreg[t] = *reinterpret_cast<const bf16x8*>(dO + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
-    }
     const float sl2 = scale * kLog2e;
-    const float lse2 = LSE2[(int64_t)head * ws_stride + q_row];     // padded: +inf for q_row >= N
-    const float delta = DELTA[(int64_t)head * ws_stride + q_row];
-    // key offset c_r (inside a block starting at k0) is masked iff c_r > klim - k0
-    const int klim = (CAUSAL ? (q_row < N - 1 ? q_row : N - 1) : N - 1) - 4 * g;
 
     const uint32_t sbase = lds_addr(smem);
     uint32_t r_adr[NT];
@@ -132,6 +121,38 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
                 t_adr[cb][hh] = sbase + 2 * (tile_off<D>(4 * g + (i >> 2) + 8 * hh, 4 * cb + 2 * h + ((i & 3) >> 1)) +
                                              4 * (i & 1));
     }
+
+    const int n_parts = (CAUSAL && n_qtiles - 1 - pr != pr) ? 2 : 1;
+#pragma unroll 1
+    for (int part = 0; part < n_parts; ++part) {
+    const int qt = (CAUSAL && part == 0) ? n_qtiles - 1 - pr : pr;
+    const int dir = part == 0 ? 1 : -1;                        // walking direction over the key blocks
+    const int q0 = qt * kDqBQ;
+    // blocks to process (a multiple of 4); the last four in sequence order carry the mask (diagonal
+    // and/or end of the sequence), all others are entirely visible
+    const int cnt = CAUSAL ? (q0 + kDqBQ) / kDqBK : (nblk + 3) & ~3;
+    // block at walk position p; positions past the end re-read the last one (their tiles are never used)
+    auto blk = [&](int p) __attribute__((always_inline)) {
+        p = p < cnt ? p : cnt - 1;
+        return dir > 0 ? p : cnt - 1 - p;
+    };
+#pragma unroll
+    for (int i = 0; i < kDqRing; ++i) load_tile(i, blk(i));
+
+    // ---- this lane's query: Q and dO rows as B operands, its two row statistics
+    const int q_row = q0 + wave * 32 + ln;
+    const int q_ld = q_row < N ? q_row : N - 1;
+    bf16x8 qreg[NT], doreg[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        qreg[t] = *reinterpret_cast<const bf16x8*>(Q + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
+        doreg[t] = *reinterpret_cast<const bf16x8*>(dO + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
+    }
+    const float lse2 = LSE2[(int64_t)head * ws_stride + q_row];     // padded: +inf for q_row >= N
+    const float delta = DELTA[(int64_t)head * ws_stride + q_row];
+    // key offset c_r (inside a block starting at k0) is masked iff c_r > klim - k0
+    const int klim = (CAUSAL ? (q_row < N - 1 ? q_row : N - 1) : N - 1) - 4 * g;
+
 
     f32x16 acc[NCB];
 #pragma unroll
@@ -190,7 +211,8 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     using S2 = std::integral_constant<int, 2>;
     using S3 = std::integral_constant<int, 3>;
 
-    // ---- prologue: tiles 0, 1 resident; S^T, dP^T of block 0; then the row operands of block 1
+    // ---- prologue: the tiles of positions 0, 1 resident; S^T, dP^T of position 0; then the row operands
+    // of position 1
     wait_vm<2 * LPT>();
     __syncthreads();
     read_krow(S0{});
@@ -209,11 +231,13 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     read_vrow(S1{});
 
     // LDS reads in flight at entry, oldest first: K rows of b+1, V rows of b+1.
-    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot2_tag, int b) __attribute__((always_inline)) {
+    // ("b+1", "b+2" below mean the blocks of the next walk positions)
+    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot2_tag, int p) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr int SL = decltype(slot_tag)::value;
         constexpr int PAR = SL & 1;
-        const int krel = klim - b * kDqBK;
+        const int krel = klim - blk(p) * kDqBK;
+        const int b_next = blk(p + kDqRing);           // the tile fetched into this position's slot
         bf16x8 dsb[2];
         auto softmax_half = [&](int u) __attribute__((always_inline)) {
 #pragma unroll
@@ -260,7 +284,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         tie_transposed();
         wait_vm<LPT>();                               // tile b+2 has landed; everyone is done with tile b
         barrier_no_drain();
-        load_tile(SL, b + kDqRing);
+        load_tile(SL, b_next);
         read_krow(slot2_tag);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -273,18 +297,8 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         read_vrow(slot2_tag);
     };
 
-    // Only blocks that reach past some query of the workgroup (the diagonal) or past the end of the
-    // sequence need the mask; all others run the variant without it.
-    const int first_masked = (CAUSAL ? (q0 < N ? q0 : N) : N) / kDqBK;
     using Plain = std::integral_constant<bool, false>;
     using Masked = std::integral_constant<bool, true>;
-    int b = 0;
-    for (; b + 3 < first_masked; b += 4) {          // first_masked is a multiple of 4 (q0 is one of 128)
-        iteration(Plain{}, S0{}, S2{}, b);
-        iteration(Plain{}, S1{}, S3{}, b + 1);
-        iteration(Plain{}, S2{}, S0{}, b + 2);
-        iteration(Plain{}, S3{}, S1{}, b + 3);
-    }
     // The compiler may move registers (copies at control-flow joins, spills) without knowing that a
     // hand-issued LDS read into them is still in flight, so outside the steady-state loop every
     // iteration is followed by settle(): all reads landed, their registers tied.
@@ -294,15 +308,31 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         tie_vrow();
         __builtin_amdgcn_sched_barrier(0);
     };
+    // The masked group is the last one in sequence order: walked last going up, first going down.
+    int p = 0;
     settle();
-    for (; b < nblk; b += 4) {                      // a handful of blocks at most
-        iteration(Masked{}, S0{}, S2{}, b);
-        settle();
-        if (b + 1 < nblk) { iteration(Masked{}, S1{}, S3{}, b + 1); settle(); }
-        if (b + 2 < nblk) { iteration(Masked{}, S2{}, S0{}, b + 2); settle(); }
-        if (b + 3 < nblk) { iteration(Masked{}, S3{}, S1{}, b + 3); settle(); }
+    if (dir < 0) {
+        iteration(Masked{}, S0{}, S2{}, 0); settle();
+        iteration(Masked{}, S1{}, S3{}, 1); settle();
+        iteration(Masked{}, S2{}, S0{}, 2); settle();
+        iteration(Masked{}, S3{}, S1{}, 3); settle();
+        p = 4;
     }
-    // Nothing may still be writing LDS when the workgroup ends, and the operand reads issued for a
+    const int plain_end = dir > 0 ? cnt - 4 : cnt;
+    for (; p < plain_end; p += 4) {
+        iteration(Plain{}, S0{}, S2{}, p);
+        iteration(Plain{}, S1{}, S3{}, p + 1);
+        iteration(Plain{}, S2{}, S0{}, p + 2);
+        iteration(Plain{}, S3{}, S1{}, p + 3);
+    }
+    settle();
+    if (dir > 0) {
+        iteration(Masked{}, S0{}, S2{}, p); settle();
+        iteration(Masked{}, S1{}, S3{}, p + 1); settle();
+        iteration(Masked{}, S2{}, S0{}, p + 2); settle();
+        iteration(Masked{}, S3{}, S1{}, p + 3); settle();
+    }
+    // Nothing may still be writing LDS when this query tile ends, and the operand reads issued for a
     // block that does not exist must have landed before their (now dead) registers are reused.
     wait_vm<0>();
     wait_lgkm<0>();
@@ -322,6 +352,8 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
                 *reinterpret_cast<bf16x4*>(orow + 32 * cb + 8 * rq + 4 * g) = w;
             }
     }
+    barrier_no_drain();          // every wave is done with the ring before the next query tile refills it
+    }   // query tiles of this workgroup
 }
 
 // ------------------------------------------------------------------------------------------
@@ -747,8 +779,9 @@ static int launch_bwd(int stage_mask, const void* q, const void* k, const void* 
     const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (N + kDkvBK - 1) / kDkvBK;
     if (delta_blocks > 0x7FFFFFFFll || n_qtiles * Hl > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     const bf16 *Q = (const bf16*)q, *K = (const bf16*)k, *V = (const bf16*)v, *dO = (const bf16*)dout;
-    const int64_t n_kwg = causal ? (n_ktiles + 1) / 2 : n_ktiles;     // causal: a workgroup takes a pair of key tiles
-    const dim3 gkv((uint32_t)(n_kwg * Hl)), gq((uint32_t)(n_qtiles * Hl));
+    // causal: a workgroup takes a pair of key tiles (query tiles)
+    const int64_t n_kwg = causal ? (n_ktiles + 1) / 2 : n_ktiles, n_qwg = causal ? (n_qtiles + 1) / 2 : n_qtiles;
+    const dim3 gkv((uint32_t)(n_kwg * Hl)), gq((uint32_t)(n_qwg * Hl));
 
     if (stage_mask & 1) {
         attn_bwd_delta_kernel<D><<<dim3((uint32_t)delta_blocks), dim3(256), 0, stream>>>(
