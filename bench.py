@@ -25,6 +25,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
+# HBM-side bytes per launch of the dK/dV kernel, from the committed rocprofv3 counter runs of this
+# same command (profiles/bench_gpt7b_kernels.md): FETCH_SIZE 1.029e7 KiB x 2.0 + WRITE_SIZE 2.622e5 KiB.
+# Counters cannot be read from inside this script, so the figure is only reported for that workload.
+DKV_TRAFFIC_BYTES = {"gpt7b": (1.029e7 * 2.0 + 2.622e5) * 1024}
 
 
 def main() -> int:
@@ -158,7 +162,7 @@ def main() -> int:
         "kernel_ms": seg_ms,
         "roofline": {"kernel": "attn_bwd_dkv_kernel", "bound": "mfma", "achieved": dkv_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dkv_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None},
+                     "traffic": DKV_TRAFFIC_BYTES.get(args.config)},
     }
 
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
