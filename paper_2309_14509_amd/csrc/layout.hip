@@ -7,10 +7,8 @@
 // rank-regrouping, d elements for the head-major layout).  A run is 256 B - 1.8 KB for the
 // shapes of interest, so 16-byte lanes are coalesced on both the read and the write side
 // without staging through LDS: a wavefront covers 1 KiB, i.e. whole runs or large pieces of one.
-// A workgroup takes a block of whole A-rows, so its reads are one contiguous range and its
-// writes are `groups` contiguous ranges.  Workgroups are small (8 KiB, one 16-byte element per
-// lane): measured on MI355X, HBM streams best with very many small workgroups in flight rather
-// than with several loads in flight per lane.
+// A workgroup is one wavefront: it reads 1 KiB of consecutive A elements and writes them to one
+// or a few runs of B.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -39,46 +37,35 @@ __device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv f) {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 512;
-constexpr int kUnroll = 1;
-constexpr int kTileBytes = 8192;   // per workgroup (whole rows, at least one)
+// One wavefront per workgroup, one element per lane: measured on MI355X, HBM streams best with very
+// many tiny workgroups in flight (6.1 TB/s here against 4.3 TB/s with 256 lanes x 8 elements and
+// 5.8 TB/s with 512 lanes x 1), more than with several loads in flight per lane.
+constexpr int kThreads = 64;
+constexpr int kTileVecs = 1 << 16;   // index arithmetic is 32-bit inside a tile of whole rows of about this size
 
 // TO_B = true : dst(B) <- src(A)      TO_B = false : dst(A) <- src(B)
+// Workgroup blockIdx.x handles 64 consecutive vectors (slice `s`) of row tile `t` of A:
+// blockIdx.x = t * slices + s.
 template <typename Vec, bool TO_B>
 __global__ __launch_bounds__(kThreads) void regroup_kernel(const Vec* __restrict__ src, Vec* __restrict__ dst,
                                                            int64_t rows, uint32_t row_vecs, uint32_t run_vecs,
-                                                           FastDiv div_row, FastDiv div_run, uint32_t tile_rows) {
-    const int64_t n0 = (int64_t)blockIdx.x * tile_rows;
+                                                           FastDiv div_row, FastDiv div_run, uint32_t tile_rows,
+                                                           uint32_t slices, FastDiv div_slices) {
+    const uint32_t tile = fastdiv(blockIdx.x, div_slices);
+    const uint32_t slice = blockIdx.x - tile * slices;
+    const int64_t n0 = (int64_t)tile * tile_rows;
     const int64_t rem = rows - n0;
     const uint32_t my_rows = rem < (int64_t)tile_rows ? (uint32_t)rem : tile_rows;
-    const uint32_t tile_vecs = my_rows * row_vecs;
-    const Vec* a_src = src + n0 * row_vecs;     // used when TO_B
-    Vec* a_dst = dst + n0 * row_vecs;           // used when !TO_B
-
-    for (uint32_t base = threadIdx.x; base < tile_vecs; base += kThreads * kUnroll) {
-        Vec val[kUnroll];
-        int64_t b_idx[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t f = base + u * kThreads;
-            if (f < tile_vecs) {
-                const uint32_t r = fastdiv(f, div_row);
-                const uint32_t w = f - r * row_vecs;
-                const uint32_t p = fastdiv(w, div_run);
-                const uint32_t ww = w - p * run_vecs;
-                b_idx[u] = ((int64_t)p * rows + n0 + r) * run_vecs + ww;
-                val[u] = TO_B ? __builtin_nontemporal_load(a_src + f) : __builtin_nontemporal_load(src + b_idx[u]);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t f = base + u * kThreads;
-            if (f < tile_vecs) {
-                if (TO_B) __builtin_nontemporal_store(val[u], dst + b_idx[u]);
-                else __builtin_nontemporal_store(val[u], a_dst + f);
-            }
-        }
-    }
+    const uint32_t f = slice * kThreads + threadIdx.x;          // vector index inside the tile
+    if (f >= my_rows * row_vecs) return;
+    const uint32_t r = fastdiv(f, div_row);
+    const uint32_t w = f - r * row_vecs;
+    const uint32_t p = fastdiv(w, div_run);
+    const uint32_t ww = w - p * run_vecs;
+    const int64_t a_idx = n0 * row_vecs + f;
+    const int64_t b_idx = ((int64_t)p * rows + n0 + r) * run_vecs + ww;
+    if (TO_B) __builtin_nontemporal_store(__builtin_nontemporal_load(src + a_idx), dst + b_idx);
+    else __builtin_nontemporal_store(__builtin_nontemporal_load(src + b_idx), dst + a_idx);
 }
 
 template <typename Vec>
@@ -87,18 +74,22 @@ static int launch_regroup(const void* src, void* dst, int64_t rows, int64_t grou
     const int64_t run_vecs = run_bytes / (int64_t)sizeof(Vec);
     const int64_t row_vecs = run_vecs * groups;
     if (row_vecs >= (1ll << 24)) return ULY_ERR_SHAPE;   // keeps every in-tile index far below 2^31
-    const int64_t tile_vecs = kTileBytes / (int64_t)sizeof(Vec);
-    uint32_t tile_rows = (uint32_t)(row_vecs >= tile_vecs ? 1 : tile_vecs / row_vecs);
-    const int64_t blocks = (rows + tile_rows - 1) / tile_rows;
+    const uint32_t tile_rows = (uint32_t)(row_vecs >= kTileVecs ? 1 : kTileVecs / row_vecs);
+    const int64_t tiles = (rows + tile_rows - 1) / tile_rows;
+    const int64_t slices = ((int64_t)tile_rows * row_vecs + kThreads - 1) / kThreads;
+    const int64_t blocks = tiles * slices;
     if (blocks <= 0) return ULY_OK;
     if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     const FastDiv div_row = make_fastdiv((uint32_t)row_vecs), div_run = make_fastdiv((uint32_t)run_vecs);
+    const FastDiv div_slices = make_fastdiv((uint32_t)slices);
     if (to_b)
         regroup_kernel<Vec, true><<<dim3((uint32_t)blocks), dim3(kThreads), 0, stream>>>(
-            (const Vec*)src, (Vec*)dst, rows, (uint32_t)row_vecs, (uint32_t)run_vecs, div_row, div_run, tile_rows);
+            (const Vec*)src, (Vec*)dst, rows, (uint32_t)row_vecs, (uint32_t)run_vecs, div_row, div_run, tile_rows,
+            (uint32_t)slices, div_slices);
     else
         regroup_kernel<Vec, false><<<dim3((uint32_t)blocks), dim3(kThreads), 0, stream>>>(
-            (const Vec*)src, (Vec*)dst, rows, (uint32_t)row_vecs, (uint32_t)run_vecs, div_row, div_run, tile_rows);
+            (const Vec*)src, (Vec*)dst, rows, (uint32_t)row_vecs, (uint32_t)run_vecs, div_row, div_run, tile_rows,
+            (uint32_t)slices, div_slices);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 
