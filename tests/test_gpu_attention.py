@@ -75,6 +75,20 @@ def test_multi_tile_medium(gpu_lib):
     _full_parity(gpu_lib, 1536, 7, 128, seed=12)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("N", [1021, 2177, 3200])
+def test_paired_tile_walks(gpu_lib, N, d):
+    """Several key/query tiles per head: the backward kernels give each workgroup a tile and its mirror
+    image and walk them in opposite directions (odd tile counts leave the middle tile on its own;
+    N not a multiple of 128 adds blocks past the end of the sequence)."""
+    _full_parity(gpu_lib, N, 1, d, seed=N + d)
+
+
+@pytest.mark.parametrize("N", [1021, 2177])
+def test_paired_tile_walks_head_major(gpu_lib, N):
+    _full_parity(gpu_lib, N, 2, 128, layout=1, seed=N)
+
+
 def test_backward_is_deterministic(gpu_lib):
     q, k, v, do = synth.attention_inputs(777, 2, 128, 3)
     a = _run_gpu(gpu_lib, q, k, v, do, 0.088, True, 0)
