@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 
@@ -14,6 +15,26 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          # packed-fp32 VALU forms are kept off for every device function of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+# The attention kernels issue LDS reads by hand (inline asm) and wait for them later.  The compiler does
+# not know that such a register is still being written, so a spill or reload of it would save or
+# restore stale data: these kernels must compile without any scratch memory.
+NO_SCRATCH = {"attn_fwd.hip", "attn_bwd.hip"}
+RESOURCE_FLAG = "-Rpass-analysis=kernel-resource-usage"
+
+
+def scratch_bytes(compiler_output: str) -> dict:
+    """{mangled kernel name: scratch bytes per lane} from hipcc's kernel-resource-usage remarks."""
+    found, name = {}, None
+    for line in compiler_output.splitlines():
+        m = re.search(r"remark: Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"remark:\s+ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name is not None:
+            found[name] = int(m.group(1))
+    return found
 
 
 def is_stale() -> bool:
@@ -31,7 +52,7 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [HIPCC, *FLAGS, *([RESOURCE_FLAG] if src in NO_SCRATCH else []), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -41,6 +62,15 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
         if p.returncode != 0:
             sys.stderr.write(out)
             raise RuntimeError(f"hipcc failed on {src}")
+        if src in NO_SCRATCH:
+            usage = scratch_bytes(out)
+            if not usage:
+                raise RuntimeError(f"no kernel resource report for {src}: cannot verify that it uses no scratch")
+            bad = {k: v for k, v in usage.items() if v != 0}
+            if bad:
+                raise RuntimeError(f"{src}: kernels with hand-issued LDS reads must not use scratch memory: {bad}")
+            if verbose:
+                print(f"{src}: {len(usage)} kernels, no scratch memory", flush=True)
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.check_call(cmd)
     return LIB

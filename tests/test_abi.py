@@ -92,3 +92,17 @@ def test_attention_backward_validation(lib):
 def test_binding_refuses_a_missing_library(tmp_path):
     with pytest.raises(FileNotFoundError):
         uly.load(str(tmp_path / "nope.so"))
+
+
+def test_build_scratch_report_parser():
+    """The build refuses attention kernels that use scratch memory; this checks the parser it relies on."""
+    from paper_2309_14509_amd import build
+    text = (
+        "a.hip:1:1: remark: Function Name: _Zk1 [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hip:1:1: remark:     VGPRs: 254 [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hip:9:1: remark: Function Name: _Zk2 [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hip:9:1: remark:     ScratchSize [bytes/lane]: 120 [-Rpass-analysis=kernel-resource-usage]\n"
+    )
+    assert build.scratch_bytes(text) == {"_Zk1": 0, "_Zk2": 120}
+    assert build.scratch_bytes("no remarks here") == {}
