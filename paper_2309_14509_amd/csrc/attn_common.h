@@ -18,47 +18,18 @@ namespace uly {
 typedef __bf16 bf16;
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 #define ULY_LDS(T, ptr) ((__attribute__((address_space(3))) T*)(ptr))
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// 16-byte row read: 8 consecutive bf16 of one LDS row.
-__device__ __forceinline__ bf16x8 lds_read_row8(const bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
-
-// Transposing LDS read (ds_read_b64_tr_b16).  Inside each group of 16 lanes, lane i supplies the
-// address of 4 consecutive bf16 of row (i / 4), columns 4*(i % 4)..+3 of a 4 x 16 block; lane n
-// of the group receives column n of that block, rows 0..3.
-__device__ __forceinline__ bf16x4 lds_read_tr4(const bf16* p) {
-    s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16(ULY_LDS(s16x4, p));
-    return __builtin_bit_cast(bf16x4, t);
-}
-
-// (padded-tile variant, kept for tiles staged through registers)
-// A-operand (32 rows x 16 contraction) of the transpose of a row-major LDS tile:
-// rows of the operand are tile COLUMNS col0 + (l%32), contraction runs over tile ROWS
-//   row0 + 8*(e/4) + 4g + (e%4),  e = 0..7
-// which is exactly the order in which a C/D register block hands its rows to the next MFMA
-// as a B operand (see pack_b_operand).  `stride` is the tile's row stride in elements.
-__device__ __forceinline__ bf16x8 lds_read_transposed_a(const bf16* tile, int stride, int row0, int col0, int lane) {
-    const int i = lane & 15;
-    const int g = lane >> 5;
-    const bf16* p = tile + (row0 + 4 * g + (i >> 2)) * stride + col0 + 16 * ((lane >> 4) & 1) + 4 * (i & 3);
-    bf16x4 lo = lds_read_tr4(p);
-    bf16x4 hi = lds_read_tr4(p + 8 * stride);
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
 
 // Registers 8u..8u+7 of a C/D block, rounded to bf16: a B operand whose contraction index e
 // is C-row 16u + 8*(e/4) + 4g + (e%4).
@@ -92,9 +63,6 @@ __device__ __forceinline__ float xhalf_sum(float x) {
     xhalf_pair(x, a, b);
     return a + b;
 }
-
-// C/D row index of register r for lane-half g.
-__device__ __forceinline__ int crow(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
 
 // ------------------------------------------------------------------------------------------
 // LDS tiles filled straight from global memory (global_load_lds_dwordx4: no VGPR staging).
@@ -260,47 +228,12 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return (uint32_t)(uintptr_t)ULY_LDS(const char, p);
 }
 
-// Wait until every direct-to-LDS load this wave has issued has landed.
 // Workgroup barrier that implies no memory waits.  (__syncthreads() makes the compiler drain every
 // outstanding load first, which would collapse a ring of tiles in flight to a single one; callers of
 // this one wait for exactly the loads and LDS reads they depend on.)
 __device__ __forceinline__ void barrier_no_drain() { asm volatile("s_barrier" ::: "memory"); }
+// Wait until every direct-to-LDS load this wave has issued has landed.
 __device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-// LDS row strides (elements).  Row reads (16 B per lane, 16 lanes of consecutive rows per bank
-// pass) want stride/4B = 4 mod 8 banks; transposing reads (4 rows x 64 B per 32 lanes) want
-// stride = 64 B mod 256 B.
-template <int D> struct LdsStride {
-    static constexpr int row = D + 8;     // +16 B
-    static constexpr int tr = D + 32;     // +64 B
-};
-
-// Copy a ROWS x D bf16 tile from registers (as loaded by load_tile_regs) into LDS.
-template <int D, int ROWS, int THREADS> struct TileIO {
-    static constexpr int kChunksPerRow = D / 8;
-    static constexpr int kChunks = ROWS * kChunksPerRow;
-    static constexpr int kPerThread = kChunks / THREADS;
-    static_assert(kChunks % THREADS == 0, "tile must divide evenly over the workgroup");
-
-    // rows beyond n_rows-1 are clamped to the last valid row (callers mask them out).
-    __device__ static __forceinline__ void load(u32x4 (&reg)[kPerThread], const bf16* base, int64_t row_stride,
-                                                int64_t row0, int64_t n_rows, int tid) {
-#pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int c = tid + i * THREADS;
-            int64_t row = row0 + c / kChunksPerRow;
-            row = row < n_rows ? row : n_rows - 1;
-            reg[i] = *reinterpret_cast<const u32x4*>(base + row * row_stride + (c % kChunksPerRow) * 8);
-        }
-    }
-    __device__ static __forceinline__ void store(const u32x4 (&reg)[kPerThread], bf16* tile, int stride, int tid) {
-#pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int c = tid + i * THREADS;
-            *reinterpret_cast<u32x4*>(tile + (c / kChunksPerRow) * stride + (c % kChunksPerRow) * 8) = reg[i];
-        }
-    }
-};
 
 }  // namespace uly
 #endif
