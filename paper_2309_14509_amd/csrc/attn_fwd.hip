@@ -1,7 +1,7 @@
 // Forward pass of exact softmax attention (paper Equation 1, causal variant of Section 3.4)
 // for the local heads of one GPU: tiled online softmax, bf16 MFMA, fp32 accumulation.
 //
-// Work decomposition: one workgroup (4 waves) owns 128 consecutive queries of one head; each wave
+// Work decomposition: one workgroup (8 waves) owns 256 consecutive queries of one head; each wave
 // owns 32 of them as the COLUMNS of its MFMA tiles:
 //     S^T (keys x queries) = K_tile (LDS, row reads) * Q^T (registers)
 //     O^T (d x queries)   += V_tile^T (LDS, transposing reads) * P^T (registers, straight from S^T)
