@@ -175,10 +175,16 @@ def main() -> int:
         oracle.attn_bwd_rows(fq, fk, fv, fdo, rows, scale, True)
         cpu_s = time.perf_counter() - t0
         cpu_flop = 14.0 * float((rows + 1).sum()) * d * Hl       # 7 contractions x 2 flop per row/key/channel
+        # layout transform of the oracle on the same [nl, H, d] tensor (bytes read + written per second)
+        x_host = xs[0].view(torch.int16).cpu().numpy().view(np.uint16)
+        t0 = time.perf_counter()
+        oracle.pack(x_host, P)
+        pack_s = time.perf_counter() - t0
         result["cpu_baseline"] = {
             "value": cpu_flop / cpu_s / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"fp64 oracle forward+backward on {rows.size} evenly spaced query rows of the same tensors "
                       f"({cpu_s:.1f} s); flops counted as 14*(i+1)*d*Hl per row i",
+            "pack_gbs": 2 * tensor_bytes / pack_s / 1e9,
         }
     print(json.dumps(result))
     return 0

@@ -89,6 +89,22 @@ def test_paired_tile_walks_head_major(gpu_lib, N):
     _full_parity(gpu_lib, N, 2, 128, layout=1, seed=N)
 
 
+def _sweep_cases():
+    rng = np.random.default_rng(20230925)
+    cases = []
+    for _ in range(36):
+        N = int(rng.integers(1, 1400))
+        cases.append((N, int(rng.choice([64, 128])), bool(rng.integers(0, 2)), int(rng.integers(0, 2)),
+                      int(rng.choice([1, 2, 3, 5]))))
+    return cases
+
+
+@pytest.mark.parametrize("N,d,causal,layout,Hl", _sweep_cases())
+def test_shape_sweep(gpu_lib, N, d, causal, layout, Hl):
+    """Seeded sweep over sequence length, head dim, mask, layout and head count."""
+    _full_parity(gpu_lib, N, Hl, d, causal=causal, layout=layout, seed=N)
+
+
 def test_backward_is_deterministic(gpu_lib):
     q, k, v, do = synth.attention_inputs(777, 2, 128, 3)
     a = _run_gpu(gpu_lib, q, k, v, do, 0.088, True, 0)
