@@ -2,9 +2,9 @@
 """Benchmark of one GPU's share of Ulysses sequence parallelism on MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic input:
-    pack(x_q), pack(x_k), pack(x_v)          [N/P, H, d]      -> P send chunks each
-    unpack(r_q), unpack(r_k), unpack(r_v)    P received chunks -> [N, H/P, d] each   (the exchange itself
-                                                                is not part of this library)
+    pack_qkv(x_q, x_k, x_v)        3 x [N/P, H, d]      -> P send chunks each, one launch
+    unpack_qkv(r_q, r_k, r_v)      3 x P received chunks -> [N, H/P, d] each, one launch   (the exchange itself
+                                                           is not part of this library)
     attention forward, attention backward over the unpacked q, k, v (causal, batch 1)
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
@@ -87,6 +87,10 @@ def main() -> int:
     def ptr(t):
         return t.data_ptr()
 
+    import ctypes
+    ptr3 = lambda ts: (ctypes.c_void_p * 3)(*[t.data_ptr() for t in ts])
+    x_ptrs, send_ptrs, recv_ptrs, qkv_ptrs = ptr3(xs), ptr3(sends), ptr3(recvs), ptr3(qkv)
+
     # Events bracket each kernel on the stream the kernels run on (torch's current stream is the one
     # handed to the library).
     names = ["pack", "unpack", "attn_fwd", "attn_bwd_delta", "attn_bwd_dkv", "attn_bwd_dq"]
@@ -98,11 +102,9 @@ def main() -> int:
                 e.record(stream)
                 record.append(e)
         mark()
-        for x, s in zip(xs, sends):
-            uly._check(lib.ulysses_pack(ptr(x), ptr(s), nl, H, d, P, 2, sp), "pack")
+        uly._check(lib.ulysses_pack_qkv(x_ptrs, send_ptrs, nl, H, d, P, 2, sp), "pack_qkv")
         mark()
-        for r, y in zip(recvs, qkv):
-            uly._check(lib.ulysses_unpack(ptr(r), ptr(y), nl, H, d, P, 2, uly.LAYOUT_SEQ_HEAD, sp), "unpack")
+        uly._check(lib.ulysses_unpack_qkv(recv_ptrs, qkv_ptrs, nl, H, d, P, 2, uly.LAYOUT_SEQ_HEAD, sp), "unpack_qkv")
         mark()
         uly._check(lib.ulysses_attn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse), N, Hl, d, scale, 1,
                                         uly.LAYOUT_SEQ_HEAD, sp), "attn_fwd")
@@ -150,7 +152,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.config}: one GPU's share, N={N} tokens, P={P}, H={H} ({Hl} local heads), "
-                               f"d={d}, batch 1, causal; per step 3x pack + 3x unpack of [{nl},{H},{d}] bf16 and "
+                               f"d={d}, batch 1, causal; per step pack and unpack of 3 x [{nl},{H},{d}] bf16 (one launch each) and "
                                "attention fwd+bwd",
                    "N": N, "P": P, "H": H, "local_heads": Hl, "d": d},
         "attn_fwd_bwd_tflops": (flop_fwd + flop_bwd) / (attn_ms * 1e-3) / 1e12,

@@ -67,6 +67,16 @@ int ulysses_pack(const void* x, void* send, int64_t n_local, int H, int d, int P
 int ulysses_unpack(const void* recv, void* y, int64_t n_local, int H, int d, int P,
                    int elem_bytes, int out_layout, void* stream);
 
+/* Q, K and V in one launch: the paper sends the three tensors as one all-to-all message of 3Nh
+ * elements (Section 3.2), so their layout transforms are issued together.  `x`, `send` (`recv`, `y`)
+ * are HOST arrays of three device pointers; tensor t is transformed exactly as by ulysses_pack
+ * (ulysses_unpack).  All three share one shape; no output may overlap any input or other output.
+ * The arrays are read before the call returns. */
+int ulysses_pack_qkv(const void* const x[3], void* const send[3], int64_t n_local, int H, int d, int P,
+                     int elem_bytes, void* stream);
+int ulysses_unpack_qkv(const void* const recv[3], void* const y[3], int64_t n_local, int H, int d, int P,
+                       int elem_bytes, int out_layout, void* stream);
+
 /* Send side of the second all-to-all (attention output back to sequence-parallel form).
  *   o    [P*n_local, Hl, d] or [Hl, P*n_local, d] (in_layout)   in
  *   send [P, n_local, Hl, d]    out;  send[q, n, hl, :] = o(token q*n_local + n, head hl) */

@@ -17,6 +17,7 @@ LAYOUT_SEQ_HEAD = 0   # [N, Hl, d]
 LAYOUT_HEAD_SEQ = 1   # [Hl, N, d]
 
 EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
+           "ulysses_pack_qkv", "ulysses_unpack_qkv",
            "ulysses_attn_fwd", "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd", "ulysses_attn_bwd_stage",
            "ulysses_status_string", "ulysses_abi_version")
 
@@ -44,6 +45,9 @@ def load(path: str | None = None):
     lib.ulysses_unpack.argtypes = [vp, vp, i64, ci, ci, ci, ci, ci, vp]
     lib.ulysses_pack_rev.argtypes = [vp, vp, i64, ci, ci, ci, ci, ci, vp]
     lib.ulysses_unpack_rev.argtypes = [vp, vp, i64, ci, ci, ci, ci, vp]
+    p3 = ctypes.POINTER(ctypes.c_void_p)      # host array of three device pointers
+    lib.ulysses_pack_qkv.argtypes = [p3, p3, i64, ci, ci, ci, ci, vp]
+    lib.ulysses_unpack_qkv.argtypes = [p3, p3, i64, ci, ci, ci, ci, ci, vp]
     lib.ulysses_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, cf, ci, ci, vp]
     lib.ulysses_attn_bwd_workspace_bytes.argtypes = [i64, ci, ci]
     lib.ulysses_attn_bwd_workspace_bytes.restype = sz
@@ -52,7 +56,7 @@ def load(path: str | None = None):
     lib.ulysses_status_string.argtypes = [ci]
     lib.ulysses_status_string.restype = ctypes.c_char_p
     for name in ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
-                 "ulysses_attn_fwd", "ulysses_attn_bwd", "ulysses_attn_bwd_stage", "ulysses_abi_version"):
+                 "ulysses_pack_qkv", "ulysses_unpack_qkv", "ulysses_attn_fwd", "ulysses_attn_bwd", "ulysses_attn_bwd_stage", "ulysses_abi_version"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -98,6 +102,37 @@ def ulysses_unpack(recv, out_layout: int = LAYOUT_SEQ_HEAD):
     _check(load().ulysses_unpack(_dev(recv, "unpack"), _dev(y, "unpack"), nl, Hl * P, d, P, recv.element_size(),
                                  out_layout, _stream()), "ulysses_unpack")
     return y
+
+
+def _ptr3(tensors, where):
+    if len(tensors) != 3:
+        raise ValueError(f"{where}: exactly three tensors (q, k, v) are expected")
+    return (ctypes.c_void_p * 3)(*[t.data_ptr() if _dev(t, where) is not None else None for t in tensors])
+
+
+def ulysses_pack_qkv(xs, P: int):
+    """Three tensors x [n_local, H, d] of one shape and dtype -> three send buffers, in one launch."""
+    import torch
+    nl, H, d = xs[0].shape
+    if any(x.shape != xs[0].shape or x.dtype != xs[0].dtype for x in xs):
+        raise ValueError("ulysses_pack_qkv: the three tensors must share shape and dtype")
+    sends = [torch.empty((P, nl, H // max(P, 1) if P > 0 else 0, d), dtype=x.dtype, device=x.device) for x in xs]
+    _check(load().ulysses_pack_qkv(_ptr3(xs, "pack_qkv"), _ptr3(sends, "pack_qkv"), nl, H, d, P,
+                                   xs[0].element_size(), _stream()), "ulysses_pack_qkv")
+    return sends
+
+
+def ulysses_unpack_qkv(recvs, out_layout: int = LAYOUT_SEQ_HEAD):
+    """Three receive buffers [P, n_local, Hl, d] -> three tensors [P*n_local, Hl, d] (or head-major), in one launch."""
+    import torch
+    P, nl, Hl, d = recvs[0].shape
+    if any(r.shape != recvs[0].shape or r.dtype != recvs[0].dtype for r in recvs):
+        raise ValueError("ulysses_unpack_qkv: the three tensors must share shape and dtype")
+    shape = (Hl, P * nl, d) if out_layout == LAYOUT_HEAD_SEQ else (P * nl, Hl, d)
+    ys = [torch.empty(shape, dtype=r.dtype, device=r.device) for r in recvs]
+    _check(load().ulysses_unpack_qkv(_ptr3(recvs, "unpack_qkv"), _ptr3(ys, "unpack_qkv"), nl, Hl * P, d, P,
+                                     recvs[0].element_size(), out_layout, _stream()), "ulysses_unpack_qkv")
+    return ys
 
 
 def ulysses_pack_rev(o, P: int, in_layout: int = LAYOUT_SEQ_HEAD):

@@ -49,6 +49,25 @@ int check_layout_args(const void* src, const void* dst, int64_t n_local, int H, 
     return ULY_OK;
 }
 
+// Checks of the three-tensor transforms: each (src, dst) pair as above, and no output may overlap any
+// input or another output.
+int check_layout_args3(const void* const src[3], void* const dst[3], int64_t n_local, int H, int d, int P,
+                       int elem_bytes, int layout, uint64_t* total_bytes) {
+    if (!src || !dst) {
+        // the pointer arrays themselves are required even for empty tensors
+        return ULY_ERR_NULL;
+    }
+    for (int t = 0; t < 3; ++t) {
+        const int rc = check_layout_args(src[t], dst[t], n_local, H, d, P, elem_bytes, layout, total_bytes);
+        if (rc != ULY_OK) return rc;
+    }
+    if (*total_bytes == 0) return ULY_OK;
+    const Range in[3] = {{src[0], *total_bytes}, {src[1], *total_bytes}, {src[2], *total_bytes}};
+    const Range out[3] = {{dst[0], *total_bytes}, {dst[1], *total_bytes}, {dst[2], *total_bytes}};
+    if (any_alias(in, out)) return ULY_ERR_ALIAS;
+    return ULY_OK;
+}
+
 int check_attn_common(int64_t N, int Hl, int d, int layout, uint64_t* tensor_bytes) {
     if (N < 0 || Hl <= 0 || d <= 0) return ULY_ERR_SHAPE;
     if (d != 64 && d != 128) return ULY_ERR_UNSUPPORTED;
@@ -68,6 +87,26 @@ int ulysses_pack(const void* x, void* send, int64_t n_local, int H, int d, int P
     const int rc = check_layout_args(x, send, n_local, H, d, P, elem_bytes, ULY_LAYOUT_SEQ_HEAD, &bytes);
     if (rc != ULY_OK) return rc;
     return uly::regroup(x, send, n_local, P, (int64_t)(H / P) * d * elem_bytes, /*to_b=*/true, stream);
+}
+
+int ulysses_pack_qkv(const void* const x[3], void* const send[3], int64_t n_local, int H, int d, int P,
+                     int elem_bytes, void* stream) {
+    uint64_t bytes = 0;
+    const int rc = check_layout_args3(x, send, n_local, H, d, P, elem_bytes, ULY_LAYOUT_SEQ_HEAD, &bytes);
+    if (rc != ULY_OK || bytes == 0) return rc;
+    return uly::regroup_multi(x, send, 3, n_local, P, (int64_t)(H / P) * d * elem_bytes, /*to_b=*/true, stream);
+}
+
+int ulysses_unpack_qkv(const void* const recv[3], void* const y[3], int64_t n_local, int H, int d, int P,
+                       int elem_bytes, int out_layout, void* stream) {
+    uint64_t bytes = 0;
+    const int rc = check_layout_args3(recv, y, n_local, H, d, P, elem_bytes, out_layout, &bytes);
+    if (rc != ULY_OK || bytes == 0) return rc;
+    const int64_t N = n_local * P;
+    const int Hl = H / P;
+    if (out_layout == ULY_LAYOUT_SEQ_HEAD || Hl == 1)
+        return uly::regroup_multi(recv, y, 3, N, 1, (int64_t)Hl * d * elem_bytes, true, stream);
+    return uly::regroup_multi(recv, y, 3, N, Hl, (int64_t)d * elem_bytes, /*to_b=*/true, stream);
 }
 
 int ulysses_unpack_rev(const void* recv, void* y, int64_t n_local, int H, int d, int P, int elem_bytes,

@@ -11,6 +11,10 @@ namespace uly {
 
 // A[rows][groups][run_bytes] <-> B[groups][rows][run_bytes] (to_b: dst is B).  Device pointers.
 int regroup(const void* src, void* dst, int64_t rows, int64_t groups, int64_t run_bytes, bool to_b, void* stream);
+// The same for `count` (<= kMaxTensors) tensors of one shape in a single launch.
+constexpr int kMaxTensors = 3;
+int regroup_multi(const void* const* src, void* const* dst, int count, int64_t rows, int64_t groups, int64_t run_bytes,
+                  bool to_b, void* stream);
 
 // Element strides (in bf16 elements) of a [token, head, channel] tensor in either layout.
 struct TensorStrides {

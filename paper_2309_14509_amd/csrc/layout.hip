@@ -43,14 +43,21 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kThreads = 64;
 constexpr int kTileVecs = 1 << 16;   // index arithmetic is 32-bit inside a tile of whole rows of about this size
 
+// Up to kMaxTensors tensors of one shape per launch (blockIdx.y selects the tensor).
+struct TensorPtrs {
+    const void* src[kMaxTensors];
+    void* dst[kMaxTensors];
+};
+
 // TO_B = true : dst(B) <- src(A)      TO_B = false : dst(A) <- src(B)
 // Workgroup blockIdx.x handles 64 consecutive vectors (slice `s`) of row tile `t` of A:
 // blockIdx.x = t * slices + s.
 template <typename Vec, bool TO_B>
-__global__ __launch_bounds__(kThreads) void regroup_kernel(const Vec* __restrict__ src, Vec* __restrict__ dst,
-                                                           int64_t rows, uint32_t row_vecs, uint32_t run_vecs,
-                                                           FastDiv div_row, FastDiv div_run, uint32_t tile_rows,
-                                                           uint32_t slices, FastDiv div_slices) {
+__global__ __launch_bounds__(kThreads) void regroup_kernel(TensorPtrs ptrs, int64_t rows, uint32_t row_vecs,
+                                                           uint32_t run_vecs, FastDiv div_row, FastDiv div_run,
+                                                           uint32_t tile_rows, uint32_t slices, FastDiv div_slices) {
+    const Vec* __restrict__ src = static_cast<const Vec*>(ptrs.src[blockIdx.y]);
+    Vec* __restrict__ dst = static_cast<Vec*>(ptrs.dst[blockIdx.y]);
     const uint32_t tile = fastdiv(blockIdx.x, div_slices);
     const uint32_t slice = blockIdx.x - tile * slices;
     const int64_t n0 = (int64_t)tile * tile_rows;
@@ -69,8 +76,8 @@ __global__ __launch_bounds__(kThreads) void regroup_kernel(const Vec* __restrict
 }
 
 template <typename Vec>
-static int launch_regroup(const void* src, void* dst, int64_t rows, int64_t groups, int64_t run_bytes, bool to_b,
-                          hipStream_t stream) {
+static int launch_regroup(const TensorPtrs& ptrs, int count, int64_t rows, int64_t groups, int64_t run_bytes,
+                          bool to_b, hipStream_t stream) {
     const int64_t run_vecs = run_bytes / (int64_t)sizeof(Vec);
     const int64_t row_vecs = run_vecs * groups;
     if (row_vecs >= (1ll << 24)) return ULY_ERR_SHAPE;   // keeps every in-tile index far below 2^31
@@ -82,26 +89,34 @@ static int launch_regroup(const void* src, void* dst, int64_t rows, int64_t grou
     if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     const FastDiv div_row = make_fastdiv((uint32_t)row_vecs), div_run = make_fastdiv((uint32_t)run_vecs);
     const FastDiv div_slices = make_fastdiv((uint32_t)slices);
+    const dim3 grid((uint32_t)blocks, (uint32_t)count);
     if (to_b)
-        regroup_kernel<Vec, true><<<dim3((uint32_t)blocks), dim3(kThreads), 0, stream>>>(
-            (const Vec*)src, (Vec*)dst, rows, (uint32_t)row_vecs, (uint32_t)run_vecs, div_row, div_run, tile_rows,
-            (uint32_t)slices, div_slices);
+        regroup_kernel<Vec, true><<<grid, dim3(kThreads), 0, stream>>>(
+            ptrs, rows, (uint32_t)row_vecs, (uint32_t)run_vecs, div_row, div_run, tile_rows, (uint32_t)slices, div_slices);
     else
-        regroup_kernel<Vec, false><<<dim3((uint32_t)blocks), dim3(kThreads), 0, stream>>>(
-            (const Vec*)src, (Vec*)dst, rows, (uint32_t)row_vecs, (uint32_t)run_vecs, div_row, div_run, tile_rows,
-            (uint32_t)slices, div_slices);
+        regroup_kernel<Vec, false><<<grid, dim3(kThreads), 0, stream>>>(
+            ptrs, rows, (uint32_t)row_vecs, (uint32_t)run_vecs, div_row, div_run, tile_rows, (uint32_t)slices, div_slices);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 
-// A[rows][groups][run_bytes] <-> B[groups][rows][run_bytes]; to_b selects the direction.
-int regroup(const void* src, void* dst, int64_t rows, int64_t groups, int64_t run_bytes, bool to_b, void* stream) {
+// A[rows][groups][run_bytes] <-> B[groups][rows][run_bytes] for `count` tensors of one shape in one
+// launch; to_b selects the direction.
+int regroup_multi(const void* const* src, void* const* dst, int count, int64_t rows, int64_t groups, int64_t run_bytes,
+                  bool to_b, void* stream) {
     hipStream_t s = (hipStream_t)stream;
-    if (rows == 0 || groups == 0 || run_bytes == 0) return ULY_OK;
-    if (run_bytes % 16 == 0) return launch_regroup<u32x4>(src, dst, rows, groups, run_bytes, to_b, s);
-    if (run_bytes % 8 == 0) return launch_regroup<u32x2>(src, dst, rows, groups, run_bytes, to_b, s);
-    if (run_bytes % 4 == 0) return launch_regroup<uint32_t>(src, dst, rows, groups, run_bytes, to_b, s);
-    if (run_bytes % 2 == 0) return launch_regroup<uint16_t>(src, dst, rows, groups, run_bytes, to_b, s);
-    return launch_regroup<uint8_t>(src, dst, rows, groups, run_bytes, to_b, s);
+    if (rows == 0 || groups == 0 || run_bytes == 0 || count == 0) return ULY_OK;
+    if (count < 0 || count > kMaxTensors) return ULY_ERR_SHAPE;
+    TensorPtrs ptrs = {};
+    for (int i = 0; i < count; ++i) { ptrs.src[i] = src[i]; ptrs.dst[i] = dst[i]; }
+    if (run_bytes % 16 == 0) return launch_regroup<u32x4>(ptrs, count, rows, groups, run_bytes, to_b, s);
+    if (run_bytes % 8 == 0) return launch_regroup<u32x2>(ptrs, count, rows, groups, run_bytes, to_b, s);
+    if (run_bytes % 4 == 0) return launch_regroup<uint32_t>(ptrs, count, rows, groups, run_bytes, to_b, s);
+    if (run_bytes % 2 == 0) return launch_regroup<uint16_t>(ptrs, count, rows, groups, run_bytes, to_b, s);
+    return launch_regroup<uint8_t>(ptrs, count, rows, groups, run_bytes, to_b, s);
+}
+
+int regroup(const void* src, void* dst, int64_t rows, int64_t groups, int64_t run_bytes, bool to_b, void* stream) {
+    return regroup_multi(&src, &dst, 1, rows, groups, run_bytes, to_b, stream);
 }
 
 }  // namespace uly

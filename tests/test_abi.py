@@ -54,6 +54,26 @@ def test_layout_validation_happens_before_any_device_call(lib):
     assert lib.ulysses_pack(A, B, 1 << 61, 8, 64, 4, 2, None) == 2          # size overflow
 
 
+def test_qkv_transform_validation(lib):
+    """Three tensors in one launch: the pointer arrays are host arrays of device pointers."""
+    import ctypes as ct
+    arr = lambda *p: (ct.c_void_p * 3)(*p)
+    size = 16 * 8 * 64 * 2
+    ins, outs = arr(A, A + size, A + 2 * size), arr(B, B + size, B + 2 * size)
+    assert lib.ulysses_pack_qkv(None, outs, 16, 8, 64, 4, 2, None) == 1
+    assert lib.ulysses_pack_qkv(arr(A, None, A + 2 * size), outs, 16, 8, 64, 4, 2, None) == 1
+    assert lib.ulysses_pack_qkv(ins, outs, 16, 8, 64, 3, 2, None) == 2
+    assert lib.ulysses_pack_qkv(ins, outs, 16, 8, 64, 4, 3, None) == 3
+    assert lib.ulysses_pack_qkv(arr(A, A + size + 4, A + 2 * size), outs, 16, 8, 64, 4, 2, None) == 4
+    # an output of one tensor overlapping the input of another, or another output
+    assert lib.ulysses_pack_qkv(ins, arr(B, A + 2 * size, B + 2 * size), 16, 8, 64, 4, 2, None) == 5
+    assert lib.ulysses_pack_qkv(ins, arr(B, B + size - 16, B + 2 * size), 16, 8, 64, 4, 2, None) == 5
+    assert lib.ulysses_unpack_qkv(ins, outs, 16, 8, 64, 4, 2, 9, None) == 3
+    # empty tensors: nothing to do, pointers inside the arrays are not looked at
+    assert lib.ulysses_pack_qkv(arr(None, None, None), arr(None, None, None), 0, 8, 64, 4, 2, None) == 0
+    assert lib.ulysses_unpack_qkv(arr(None, None, None), arr(None, None, None), 0, 8, 64, 4, 2, 0, None) == 0
+
+
 def _fwd(lib, q=A, k=B, v=C_, o=D_, lse=0x7000000, N=128, Hl=2, d=64, scale=0.125, causal=1, layout=0):
     return lib.ulysses_attn_fwd(q, k, v, o, lse, N, Hl, d, scale, causal, layout, None)
 

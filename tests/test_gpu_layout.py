@@ -46,6 +46,20 @@ def test_unpack_and_pack_rev_bit_exact(gpu_lib, nl, H, d, P, layout):
     assert np.array_equal(bits_of(back), oracle.pack_rev(ref, P, layout))
 
 
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("nl,H,d,P", SMALL[:5])
+def test_qkv_in_one_launch_bit_exact(gpu_lib, nl, H, d, P, layout):
+    """Q, K, V transformed by one launch equal the oracle applied to each tensor."""
+    xs = [synth.bits_u16((nl, H, d), 7, synth.TID_X + 10 * t) for t in range(3)]
+    sends = gpu_lib.ulysses_pack_qkv([to_gpu_u16(x) for x in xs], P)
+    for x, s_ in zip(xs, sends):
+        assert np.array_equal(bits_of(s_), oracle.pack(x, P))
+    rs = [synth.bits_u16((P, nl, H // P, d), 7, synth.TID_R + 10 * t) for t in range(3)]
+    ys = gpu_lib.ulysses_unpack_qkv([to_gpu_u16(r) for r in rs], layout)
+    for r, y in zip(rs, ys):
+        assert np.array_equal(bits_of(y), oracle.unpack(r, layout))
+
+
 @pytest.mark.parametrize("elem", [torch.uint8, torch.int32])
 def test_other_element_sizes(gpu_lib, elem):
     nl, H, d, P = 37, 6, 24, 3
