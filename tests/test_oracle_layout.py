@@ -111,3 +111,31 @@ def test_p1_is_identity():
 def test_bad_head_split_rejected():
     with pytest.raises(ValueError):
         oracle.pack(_rand((4, 6, 8)), 4)
+
+
+def _golden_comm_rows():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "comm_volume_section_3_2.txt")
+    rows = []
+    for line in open(path):
+        if line.strip() and not line.startswith("#"):
+            rows.append(tuple(int(x) for x in line.split()))
+    return rows
+
+
+@pytest.mark.parametrize("N,h,P,qkv_total,out_total,per_rank", _golden_comm_rows())
+def test_message_sizes_match_the_papers_communication_analysis(N, h, P, qkv_total, out_total, per_rank):
+    """What the transforms hand to the two all-to-alls has the sizes Section 3.2 states: 3Nh and Nh
+    elements in aggregate, 4Nh/P per rank, and every (source, destination) pair carries the same
+    share of it."""
+    d = 8
+    H = h // d
+    nl, Hl = N // P, H // P
+    x = _rand((nl, H, d))
+    sent_qkv = [oracle.pack(x, P) for _ in range(3)]                    # one rank's Q, K, V send buffers
+    y = oracle.unpack(sent_qkv[0].reshape(P, nl, Hl, d))                 # shape of a rank's attention output
+    sent_out = oracle.pack_rev(y, P)
+    rank_elems = sum(s.size for s in sent_qkv) + sent_out.size
+    assert rank_elems == per_rank
+    assert P * sum(s.size for s in sent_qkv) == qkv_total and P * sent_out.size == out_total
+    assert all(s.shape[0] == P and s[0].size * P == s.size for s in sent_qkv + [sent_out])   # equal chunks
