@@ -44,7 +44,10 @@ def _load():
         lib.oracle_attn_fwd_rows.argtypes = [vp, vp, vp, vp, i64, vp, vp, i64, ci, ci, dbl, ci, ci]
         lib.oracle_attn_bwd_rows.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp, vp, i64, ci, ci, dbl, ci, ci]
         lib.oracle_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, dbl, ci, ci]
-        for f in (lib.oracle_attn_fwd, lib.oracle_attn_fwd_rows, lib.oracle_attn_bwd_rows, lib.oracle_attn_bwd):
+        lib.oracle_xattn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, ci, ci, dbl, ci]
+        lib.oracle_xattn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, ci, ci, dbl, ci]
+        for f in (lib.oracle_attn_fwd, lib.oracle_attn_fwd_rows, lib.oracle_attn_bwd_rows, lib.oracle_attn_bwd,
+                  lib.oracle_xattn_fwd, lib.oracle_xattn_bwd):
             f.restype = ci
         lib.oracle_num_threads.restype = ci
         _lib = lib
@@ -159,6 +162,40 @@ def attn_bwd(q, k, v, dout, scale: float, causal: bool = True, layout: int = LAY
                                  int(causal), layout)
     if rc:
         raise MemoryError("oracle_attn_bwd")
+    return dq, dk, dv
+
+
+def _xdims(q, k, layout):
+    Nq, Hl, d = _dims(q, layout)
+    Nk, Hk, dk = _dims(k, layout)
+    if (Hk, dk) != (Hl, d):
+        raise ValueError("q and k must agree in heads and head dim")
+    if Nk <= 0:
+        raise ValueError("cross-attention needs at least one key")
+    return Nq, Nk, Hl, d
+
+
+def xattn_fwd(q, k, v, scale: float, layout: int = LAYOUT_SEQ_HEAD):
+    """Cross-attention, no mask: q has Nq tokens, k and v have Nk.  -> (O like q, LSE [Hl,Nq])."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    Nq, Nk, Hl, d = _xdims(q, k, layout)
+    o = np.empty_like(q); lse = np.empty((Hl, Nq), np.float64)
+    rc = _load().oracle_xattn_fwd(q.ctypes.data, k.ctypes.data, v.ctypes.data, o.ctypes.data, lse.ctypes.data,
+                                  Nq, Nk, Hl, d, scale, layout)
+    if rc:
+        raise MemoryError("oracle_xattn_fwd")
+    return o, lse
+
+
+def xattn_bwd(q, k, v, dout, scale: float, layout: int = LAYOUT_SEQ_HEAD):
+    """-> (dQ like q, dK, dV like k), fp64."""
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    Nq, Nk, Hl, d = _xdims(q, k, layout)
+    dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(k)
+    rc = _load().oracle_xattn_bwd(q.ctypes.data, k.ctypes.data, v.ctypes.data, dout.ctypes.data,
+                                  dq.ctypes.data, dk.ctypes.data, dv.ctypes.data, Nq, Nk, Hl, d, scale, layout)
+    if rc:
+        raise MemoryError("oracle_xattn_bwd")
     return dq, dk, dv
 
 

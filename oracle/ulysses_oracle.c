@@ -302,6 +302,105 @@ int oracle_attn_bwd(const double* q, const double* k, const double* v, const dou
     return rc;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Cross-attention (Section 3.4 lists it beside self- and causal attention):  */
+/* Equation 1 with Nq queries attending to Nk keys/values, no mask.           */
+/* q, o, dout, dq: Nq tokens; k, v, dk, dv: Nk tokens; all in `layout`.       */
+/* Written on its own (no code shared with the functions above).              */
+/* ------------------------------------------------------------------------- */
+
+/* Forward.  lse:[Hl,Nq]. */
+int oracle_xattn_fwd(const double* q, const double* k, const double* v, double* o, double* lse,
+                     int64_t Nq, int64_t Nk, int Hl, int d, double scale, int layout) {
+    if (Nk <= 0) return 2;                 /* softmax over an empty key set is undefined */
+    int fail = 0;
+#pragma omp parallel
+    {
+        double* s = (double*)malloc(sizeof(double) * (size_t)Nk);
+        if (!s) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for collapse(2) schedule(dynamic, 16)
+            for (int h = 0; h < Hl; ++h)
+                for (int64_t i = 0; i < Nq; ++i) {
+                    const double* qi = q + row_off(i, h, Nq, Hl, d, layout);
+                    double* oi = o + row_off(i, h, Nq, Hl, d, layout);
+                    double m = -INFINITY, l = 0.0;
+                    for (int64_t j = 0; j < Nk; ++j) {
+                        s[j] = scale * dot(qi, k + row_off(j, h, Nk, Hl, d, layout), d);
+                        if (s[j] > m) m = s[j];
+                    }
+                    for (int64_t j = 0; j < Nk; ++j) l += exp(s[j] - m);
+                    const double L = m + log(l);
+                    for (int c = 0; c < d; ++c) oi[c] = 0.0;
+                    for (int64_t j = 0; j < Nk; ++j) {
+                        const double p = exp(s[j] - L);
+                        const double* vj = v + row_off(j, h, Nk, Hl, d, layout);
+                        for (int c = 0; c < d; ++c) oi[c] += p * vj[c];
+                    }
+                    lse[(int64_t)h * Nq + i] = L;
+                }
+        }
+        free(s);
+    }
+    return fail;
+}
+
+/* Backward: gradients of sum(O * dout).  Recomputes the forward in fp64 first. */
+int oracle_xattn_bwd(const double* q, const double* k, const double* v, const double* dout,
+                     double* dq, double* dk, double* dv,
+                     int64_t Nq, int64_t Nk, int Hl, int d, double scale, int layout) {
+    if (Nk <= 0) return 2;
+    const size_t nq_elems = (size_t)(Nq * Hl * d + 1);
+    double* o = (double*)malloc(sizeof(double) * nq_elems);
+    double* lse = (double*)malloc(sizeof(double) * (size_t)(Nq * Hl + 1));
+    double* D = (double*)malloc(sizeof(double) * (size_t)(Nq * Hl + 1));
+    if (!o || !lse || !D || oracle_xattn_fwd(q, k, v, o, lse, Nq, Nk, Hl, d, scale, layout)) {
+        free(o); free(lse); free(D);
+        return 1;
+    }
+    for (int h = 0; h < Hl; ++h)
+        for (int64_t i = 0; i < Nq; ++i)
+            D[(int64_t)h * Nq + i] = dot(dout + row_off(i, h, Nq, Hl, d, layout), o + row_off(i, h, Nq, Hl, d, layout), d);
+    /* dQ_i = scale * sum_j dS_ij K_j */
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (int h = 0; h < Hl; ++h)
+        for (int64_t i = 0; i < Nq; ++i) {
+            const double* qi = q + row_off(i, h, Nq, Hl, d, layout);
+            const double* doi = dout + row_off(i, h, Nq, Hl, d, layout);
+            double* dqi = dq + row_off(i, h, Nq, Hl, d, layout);
+            for (int c = 0; c < d; ++c) dqi[c] = 0.0;
+            for (int64_t j = 0; j < Nk; ++j) {
+                const double* kj = k + row_off(j, h, Nk, Hl, d, layout);
+                const double p = exp(scale * dot(qi, kj, d) - lse[(int64_t)h * Nq + i]);
+                const double ds = p * (dot(doi, v + row_off(j, h, Nk, Hl, d, layout), d) - D[(int64_t)h * Nq + i]);
+                for (int c = 0; c < d; ++c) dqi[c] += scale * ds * kj[c];
+            }
+        }
+    /* dK_j = scale * sum_i dS_ij Q_i,  dV_j = sum_i P_ij dO_i */
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (int h = 0; h < Hl; ++h)
+        for (int64_t j = 0; j < Nk; ++j) {
+            const double* kj = k + row_off(j, h, Nk, Hl, d, layout);
+            const double* vj = v + row_off(j, h, Nk, Hl, d, layout);
+            double* dkj = dk + row_off(j, h, Nk, Hl, d, layout);
+            double* dvj = dv + row_off(j, h, Nk, Hl, d, layout);
+            for (int c = 0; c < d; ++c) { dkj[c] = 0.0; dvj[c] = 0.0; }
+            for (int64_t i = 0; i < Nq; ++i) {
+                const double* qi = q + row_off(i, h, Nq, Hl, d, layout);
+                const double* doi = dout + row_off(i, h, Nq, Hl, d, layout);
+                const double p = exp(scale * dot(qi, kj, d) - lse[(int64_t)h * Nq + i]);
+                const double ds = p * (dot(doi, vj, d) - D[(int64_t)h * Nq + i]);
+                for (int c = 0; c < d; ++c) { dvj[c] += p * doi[c]; dkj[c] += scale * ds * qi[c]; }
+            }
+        }
+    free(o); free(lse); free(D);
+    return 0;
+}
+
 int oracle_num_threads(void) {
     int n = 1;
 #ifdef _OPENMP
