@@ -131,6 +131,22 @@ int ulysses_attn_bwd_stage(int stage,
                            void* workspace, size_t workspace_bytes,
                            int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Cross-attention (Section 3.4 lists it beside self- and causal attention): Equation 1 with Nq
+ * queries attending to Nk keys/values of the same local heads, no mask.
+ *   q, o, dout, dq: Nq tokens;  k, v, dk, dv: Nk tokens;  all bf16 in `layout` (each tensor with its
+ *   own token count: [Nq, Hl, d] / [Nk, Hl, d], or head-major);  lse [Hl, Nq] fp32.
+ * Same arithmetic, precision, checks and workspace rules as the self-attention entry points.
+ * Nq == 0 does nothing; Nk == 0 with Nq > 0 is ULY_ERR_SHAPE (a softmax over no keys).
+ * ------------------------------------------------------------------------------------------- */
+int ulysses_xattn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                      int64_t Nq, int64_t Nk, int Hl, int d, float scale, int layout, void* stream);
+size_t ulysses_xattn_bwd_workspace_bytes(int64_t Nq, int64_t Nk, int Hl, int d);
+int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                      const float* lse, void* dq, void* dk, void* dv,
+                      void* workspace, size_t workspace_bytes,
+                      int64_t Nq, int64_t Nk, int Hl, int d, float scale, int layout, void* stream);
+
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* ulysses_status_string(int status);
 

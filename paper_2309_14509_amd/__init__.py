@@ -18,6 +18,7 @@ LAYOUT_HEAD_SEQ = 1   # [Hl, N, d]
 
 EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
            "ulysses_pack_qkv", "ulysses_unpack_qkv",
+           "ulysses_xattn_fwd", "ulysses_xattn_bwd_workspace_bytes", "ulysses_xattn_bwd",
            "ulysses_attn_fwd", "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd", "ulysses_attn_bwd_stage",
            "ulysses_status_string", "ulysses_abi_version")
 
@@ -53,10 +54,15 @@ def load(path: str | None = None):
     lib.ulysses_attn_bwd_workspace_bytes.restype = sz
     lib.ulysses_attn_bwd.argtypes = [vp] * 10 + [sz, i64, ci, ci, cf, ci, ci, vp]
     lib.ulysses_attn_bwd_stage.argtypes = [ci] + [vp] * 10 + [sz, i64, ci, ci, cf, ci, ci, vp]
+    lib.ulysses_xattn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, ci, ci, cf, ci, vp]
+    lib.ulysses_xattn_bwd_workspace_bytes.argtypes = [i64, i64, ci, ci]
+    lib.ulysses_xattn_bwd_workspace_bytes.restype = sz
+    lib.ulysses_xattn_bwd.argtypes = [vp] * 10 + [sz, i64, i64, ci, ci, cf, ci, vp]
     lib.ulysses_status_string.argtypes = [ci]
     lib.ulysses_status_string.restype = ctypes.c_char_p
     for name in ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
-                 "ulysses_pack_qkv", "ulysses_unpack_qkv", "ulysses_attn_fwd", "ulysses_attn_bwd", "ulysses_attn_bwd_stage", "ulysses_abi_version"):
+                 "ulysses_pack_qkv", "ulysses_unpack_qkv", "ulysses_xattn_fwd", "ulysses_xattn_bwd",
+                 "ulysses_attn_fwd", "ulysses_attn_bwd", "ulysses_attn_bwd_stage", "ulysses_abi_version"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -208,4 +214,34 @@ def ulysses_attn_bwd(q, k, v, o, dout, lse, scale: float, causal: bool = True, l
         _check(load().ulysses_attn_bwd(*args), "ulysses_attn_bwd")
     else:
         _check(load().ulysses_attn_bwd_stage(int(stage), *args), "ulysses_attn_bwd_stage")
+    return dq, dk, dv
+
+
+def ulysses_xattn_fwd(q, k, v, scale: float, layout: int = LAYOUT_SEQ_HEAD):
+    """Cross-attention, no mask: bf16 q (Nq tokens), k, v (Nk tokens) in ``layout`` -> (o like q, lse fp32 [Hl, Nq])."""
+    import torch
+    if q.dtype != torch.bfloat16:
+        raise ValueError("attention tensors must be bfloat16")
+    Nq, Hl, d = _attn_dims(q, layout)
+    Nk = _attn_dims(k, layout)[0]
+    o = torch.empty_like(q)
+    lse = torch.empty((Hl, Nq), dtype=torch.float32, device=q.device)
+    _check(load().ulysses_xattn_fwd(_dev(q, "xattn_fwd"), _dev(k, "xattn_fwd"), _dev(v, "xattn_fwd"),
+                                    _dev(o, "xattn_fwd"), _dev(lse, "xattn_fwd"), Nq, Nk, Hl, d, scale, layout,
+                                    _stream()), "ulysses_xattn_fwd")
+    return o, lse
+
+
+def ulysses_xattn_bwd(q, k, v, o, dout, lse, scale: float, layout: int = LAYOUT_SEQ_HEAD):
+    """-> (dq like q, dk, dv like k) bf16."""
+    import torch
+    Nq, Hl, d = _attn_dims(q, layout)
+    Nk = _attn_dims(k, layout)[0]
+    need = int(load().ulysses_xattn_bwd_workspace_bytes(Nq, Nk, Hl, d))
+    workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(k)
+    w = "xattn_bwd"
+    _check(load().ulysses_xattn_bwd(_dev(q, w), _dev(k, w), _dev(v, w), _dev(o, w), _dev(dout, w), _dev(lse, w),
+                                    _dev(dq, w), _dev(dk, w), _dev(dv, w), _dev(workspace, w), workspace.numel(),
+                                    Nq, Nk, Hl, d, scale, layout, _stream()), "ulysses_xattn_bwd")
     return dq, dk, dv

@@ -141,20 +141,33 @@ int ulysses_pack_rev(const void* o, void* send, int64_t n_local, int H, int d, i
     return uly::regroup(o, send, N, Hl, (int64_t)d * elem_bytes, /*to_b=*/false, stream);  // [Hl,N,d] -> [N,Hl,d]
 }
 
-int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int Hl, int d,
-                     float scale, int causal, int layout, void* stream) {
-    uint64_t tb;
-    const int rc = check_attn_common(N, Hl, d, layout, &tb);
+// Shared by self-attention (Nk == N) and cross-attention (causal == 0, Nk keys for N queries).
+static int attn_fwd_checked(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk,
+                            int Hl, int d, float scale, int causal, int layout, void* stream) {
+    uint64_t tb, tbk;
+    int rc = check_attn_common(N, Hl, d, layout, &tb);
+    if (rc == ULY_OK) rc = check_attn_common(Nk, Hl, d, layout, &tbk);
     if (rc != ULY_OK) return rc;
     if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;     // scale must be finite and > 0
     if (N == 0) return ULY_OK;
+    if (Nk == 0) return ULY_ERR_SHAPE;                                             // softmax over no keys
     if (!q || !k || !v || !o || !lse) return ULY_ERR_NULL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse)) return ULY_ERR_ALIGN;
-    const Range in[3] = {{q, tb}, {k, tb}, {v, tb}};
+    const Range in[3] = {{q, tb}, {k, tbk}, {v, tbk}};
     const Range out[2] = {{o, tb}, {lse, (uint64_t)N * Hl * 4u}};
     if (any_alias(in, out)) return ULY_ERR_ALIAS;
-    return uly::attn_fwd_launch(q, k, v, o, lse, N, Hl, d, scale, causal != 0, uly::strides_for(layout, N, Hl, d),
-                                stream);
+    return uly::attn_fwd_launch(q, k, v, o, lse, N, Nk, Hl, d, scale, causal != 0, uly::strides_for(layout, N, Hl, d),
+                                uly::strides_for(layout, Nk, Hl, d), stream);
+}
+
+int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int Hl, int d,
+                     float scale, int causal, int layout, void* stream) {
+    return attn_fwd_checked(q, k, v, o, lse, N, N, Hl, d, scale, causal, layout, stream);
+}
+
+int ulysses_xattn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t Nq, int64_t Nk,
+                      int Hl, int d, float scale, int layout, void* stream) {
+    return attn_fwd_checked(q, k, v, o, lse, Nq, Nk, Hl, d, scale, 0, layout, stream);
 }
 
 size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
@@ -163,15 +176,22 @@ size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
     return (size_t)uly::attn_bwd_workspace_floats(N, Hl) * sizeof(float);
 }
 
+size_t ulysses_xattn_bwd_workspace_bytes(int64_t Nq, int64_t Nk, int Hl, int d) {
+    (void)Nk;
+    return ulysses_attn_bwd_workspace_bytes(Nq, Hl, d);
+}
+
 static int attn_bwd_checked(int stage_mask, const void* q, const void* k, const void* v, const void* o,
                             const void* dout, const float* lse, void* dq, void* dk, void* dv, void* workspace,
-                            size_t workspace_bytes, int64_t N, int Hl, int d, float scale, int causal, int layout,
-                            void* stream) {
-    uint64_t tb;
-    const int rc = check_attn_common(N, Hl, d, layout, &tb);
+                            size_t workspace_bytes, int64_t N, int64_t Nk, int Hl, int d, float scale, int causal,
+                            int layout, void* stream) {
+    uint64_t tb, tbk;
+    int rc = check_attn_common(N, Hl, d, layout, &tb);
+    if (rc == ULY_OK) rc = check_attn_common(Nk, Hl, d, layout, &tbk);
     if (rc != ULY_OK) return rc;
     if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;
-    if (N == 0) return ULY_OK;
+    if (N == 0 && Nk == 0) return ULY_OK;
+    if (N == 0 || Nk == 0) return ULY_ERR_SHAPE;          // gradients of an empty side are not defined here
     if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv) return ULY_ERR_NULL;
     const size_t need = ulysses_attn_bwd_workspace_bytes(N, Hl, d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return ULY_ERR_WORKSPACE;
@@ -179,17 +199,18 @@ static int attn_bwd_checked(int stage_mask, const void* q, const void* k, const 
         misaligned(dq) || misaligned(dk) || misaligned(dv) || misaligned(workspace))
         return ULY_ERR_ALIGN;
     const uint64_t lb = (uint64_t)N * Hl * 4u;
-    const Range in[6] = {{q, tb}, {k, tb}, {v, tb}, {o, tb}, {dout, tb}, {lse, lb}};
-    const Range out[4] = {{dq, tb}, {dk, tb}, {dv, tb}, {workspace, need}};
+    const Range in[6] = {{q, tb}, {k, tbk}, {v, tbk}, {o, tb}, {dout, tb}, {lse, lb}};
+    const Range out[4] = {{dq, tb}, {dk, tbk}, {dv, tbk}, {workspace, need}};
     if (any_alias(in, out)) return ULY_ERR_ALIAS;
-    return uly::attn_bwd_launch(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, N, Hl, d, scale,
-                                causal != 0, uly::strides_for(layout, N, Hl, d), stream);
+    return uly::attn_bwd_launch(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, N, Nk, Hl, d, scale,
+                                causal != 0, uly::strides_for(layout, N, Hl, d), uly::strides_for(layout, Nk, Hl, d),
+                                stream);
 }
 
 int ulysses_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
                      void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int64_t N, int Hl,
                      int d, float scale, int causal, int layout, void* stream) {
-    return attn_bwd_checked(7, q, k, v, o, dout, lse, dq, dk, dv, workspace, workspace_bytes, N, Hl, d, scale,
+    return attn_bwd_checked(7, q, k, v, o, dout, lse, dq, dk, dv, workspace, workspace_bytes, N, N, Hl, d, scale,
                             causal, layout, stream);
 }
 
@@ -198,8 +219,15 @@ int ulysses_attn_bwd_stage(int stage, const void* q, const void* k, const void* 
                            int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream) {
     if (stage != ULY_BWD_STAGE_DELTA && stage != ULY_BWD_STAGE_DKV && stage != ULY_BWD_STAGE_DQ)
         return ULY_ERR_UNSUPPORTED;
-    return attn_bwd_checked(1 << stage, q, k, v, o, dout, lse, dq, dk, dv, workspace, workspace_bytes, N, Hl, d,
+    return attn_bwd_checked(1 << stage, q, k, v, o, dout, lse, dq, dk, dv, workspace, workspace_bytes, N, N, Hl, d,
                             scale, causal, layout, stream);
+}
+
+int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
+                      void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int64_t Nq, int64_t Nk,
+                      int Hl, int d, float scale, int layout, void* stream) {
+    return attn_bwd_checked(7, q, k, v, o, dout, lse, dq, dk, dv, workspace, workspace_bytes, Nq, Nk, Hl, d, scale, 0,
+                            layout, stream);
 }
 
 const char* ulysses_status_string(int status) {

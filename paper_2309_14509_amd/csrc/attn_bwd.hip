@@ -68,7 +68,7 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dO,
     const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, bf16* __restrict__ dQ, int N,
-    int n_qtiles, int64_t row_stride, int64_t head_stride, float scale) {
+    int Nk, int n_qtiles, int64_t row_stride, int64_t head_stride, int64_t kv_head_stride, float scale) {
     constexpr int NT = D / 16, NCB = D / 32;
     constexpr int TILE = kDqBK * D;
     constexpr int TB = TILE * 2;
@@ -89,19 +89,20 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     const int head = blockIdx.x / n_pairs;
     const int pr = blockIdx.x - head * n_pairs;
     const int64_t hoff = (int64_t)head * head_stride;
-    const bf16* Kh = K + hoff;
-    const bf16* Vh = V + hoff;
+    // N queries, Nk keys (Nk = N for self-attention); K and V may have their own head stride
+    const bf16* Kh = K + (int64_t)head * kv_head_stride;
+    const bf16* Vh = V + (int64_t)head * kv_head_stride;
 
     // Key blocks are walked in whole groups of four; blocks nblk .. do not exist (all their keys are
     // masked) and re-read the data of the last real block.
-    const int nblk = (N + kDqBK - 1) / kDqBK;
+    const int nblk = (Nk + kDqBK - 1) / kDqBK;
 
     const typename Loader::LaneOffsets ld = Loader::lane_offsets(row_stride, wave, lane);
-    const typename Loader::TailOffsets ld_tail = Loader::tail_offsets(row_stride, wave, lane, N);
+    const typename Loader::TailOffsets ld_tail = Loader::tail_offsets(row_stride, wave, lane, Nk);
     auto load_tile = [&](int slot, int tb) __attribute__((always_inline)) {     // branch-free
         tb = tb < nblk ? tb : nblk - 1;          // blocks past the end re-read the last real one
         const int r0 = tb * kDqBK;
-        const bool is_tail = r0 + kDqBK > N;
+        const bool is_tail = r0 + kDqBK > Nk;
         Loader::issue_sel(smem + slot * TILE, Kh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
         Loader::issue_sel(smem + (kDqRing + slot) * TILE, Vh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
     };
@@ -151,7 +152,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     const float lse2 = LSE2[(int64_t)head * ws_stride + q_row];     // padded: +inf for q_row >= N
     const float delta = DELTA[(int64_t)head * ws_stride + q_row];
     // key offset c_r (inside a block starting at k0) is masked iff c_r > klim - k0
-    const int klim = (CAUSAL ? (q_row < N - 1 ? q_row : N - 1) : N - 1) - 4 * g;
+    const int klim = (CAUSAL ? (q_row < Nk - 1 ? q_row : Nk - 1) : Nk - 1) - 4 * g;
 
 
     f32x16 acc[NCB];
@@ -377,7 +378,8 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dO,
     const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, bf16* __restrict__ dK,
-    bf16* __restrict__ dV, int N, int n_ktiles, int64_t row_stride, int64_t head_stride, float scale) {
+    bf16* __restrict__ dV, int N, int Nk, int n_ktiles, int64_t row_stride, int64_t head_stride,
+    int64_t kv_head_stride, float scale) {
     constexpr int NT = D / 16, NCB = D / 32;
     constexpr int TILE = kDkvBQ * D;            // elements per tile
     constexpr int TB = TILE * 2;                // bytes per tile
@@ -403,6 +405,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     const int64_t hoff = (int64_t)head * head_stride;
     const bf16* Qh = Q + hoff;
     const bf16* dOh = dO + hoff;
+    const int64_t kv_hoff = (int64_t)head * kv_head_stride;   // N queries, Nk keys (Nk = N for self-attention)
     const float* lse_h = LSE2 + (int64_t)head * ws_stride;
     const float* del_h = DELTA + (int64_t)head * ws_stride;
 
@@ -480,12 +483,12 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 
     // ---- this lane's key: K and V rows as B operands
     const int j_col = j0 + wave * 32 + ln;
-    const int j_ld = j_col < N ? j_col : N - 1;
+    const int j_ld = j_col < Nk ? j_col : Nk - 1;
     bf16x8 kreg[NT], vreg[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        kreg[t] = *reinterpret_cast<const bf16x8*>(K + hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
-        vreg[t] = *reinterpret_cast<const bf16x8*>(V + hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
+        kreg[t] = *reinterpret_cast<const bf16x8*>(K + kv_hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
+        vreg[t] = *reinterpret_cast<const bf16x8*>(V + kv_hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
     }
     const int jcol_g = j_col - 4 * g;            // causal test: row offset c_r is masked iff c_r < jcol_g - i0
 
@@ -744,9 +747,9 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     for (int cb = 0; cb < NCB; ++cb) lds_tie(dk_acc[cb], dv_acc[cb]);
     __builtin_amdgcn_sched_barrier(0);
 
-    if (j_col < N) {
-        bf16* krow = dK + hoff + (int64_t)j_col * row_stride;
-        bf16* vrow = dV + hoff + (int64_t)j_col * row_stride;
+    if (j_col < Nk) {
+        bf16* krow = dK + kv_hoff + (int64_t)j_col * row_stride;
+        bf16* vrow = dV + kv_hoff + (int64_t)j_col * row_stride;
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
@@ -770,13 +773,13 @@ inline int64_t stats_stride(int64_t N) { return ((N + 127) / 128) * 128 + 64; }
 
 template <int D>
 static int launch_bwd(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
-                      const float* lse, void* dq, void* dk, void* dv, float* ws, int64_t N, int Hl, float scale,
-                      int causal, TensorStrides st, hipStream_t stream) {
+                      const float* lse, void* dq, void* dk, void* dv, float* ws, int64_t N, int64_t Nk, int Hl,
+                      float scale, int causal, TensorStrides st, TensorStrides kv, hipStream_t stream) {
     const int64_t stride = stats_stride(N);
     float* delta = ws;
     float* lse2 = ws + stride * Hl;
     const int64_t delta_blocks = (stride * Hl * (D / 8) + 255) / 256;
-    const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (N + kDkvBK - 1) / kDkvBK;
+    const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (Nk + kDkvBK - 1) / kDkvBK;
     if (delta_blocks > 0x7FFFFFFFll || n_qtiles * Hl > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     const bf16 *Q = (const bf16*)q, *K = (const bf16*)k, *V = (const bf16*)v, *dO = (const bf16*)dout;
     // causal: a workgroup takes a pair of key tiles (query tiles)
@@ -791,19 +794,21 @@ static int launch_bwd(int stage_mask, const void* q, const void* k, const void* 
     if (stage_mask & 2) {
         if (causal)
             attn_bwd_dkv_kernel<D, true><<<gkv, dim3(kDkvThreads), 0, stream>>>(
-                Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)n_ktiles, st.row, st.head, scale);
+                Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
+                kv.head, scale);
         else
             attn_bwd_dkv_kernel<D, false><<<gkv, dim3(kDkvThreads), 0, stream>>>(
-                Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)n_ktiles, st.row, st.head, scale);
+                Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
+                kv.head, scale);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     if (stage_mask & 4) {
         if (causal)
             attn_bwd_dq_kernel<D, true><<<gq, dim3(kDqThreads), 0, stream>>>(
-                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)n_qtiles, st.row, st.head, scale);
+                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale);
         else
             attn_bwd_dq_kernel<D, false><<<gq, dim3(kDqThreads), 0, stream>>>(
-                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)n_qtiles, st.row, st.head, scale);
+                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     return ULY_OK;
@@ -812,12 +817,12 @@ static int launch_bwd(int stage_mask, const void* q, const void* k, const void* 
 int64_t attn_bwd_workspace_floats(int64_t N, int Hl) { return 2 * stats_stride(N) * Hl; }
 
 int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
-                    const float* lse, void* dq, void* dk, void* dv, float* ws, int64_t N, int Hl, int d,
-                    float scale, int causal, TensorStrides st, void* stream) {
+                    const float* lse, void* dq, void* dk, void* dv, float* ws, int64_t N, int64_t Nk, int Hl, int d,
+                    float scale, int causal, TensorStrides st, TensorStrides kv, void* stream) {
     if (d == 128)
-        return launch_bwd<128>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Hl, scale, causal, st,
+        return launch_bwd<128>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Nk, Hl, scale, causal, st, kv,
                                (hipStream_t)stream);
-    return launch_bwd<64>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Hl, scale, causal, st,
+    return launch_bwd<64>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Nk, Hl, scale, causal, st, kv,
                           (hipStream_t)stream);
 }
 

@@ -32,8 +32,8 @@ constexpr bool kFwdPair = false;
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                                    const bf16* __restrict__ V, bf16* __restrict__ O,
-                                                                   float* __restrict__ LSE, int N, int n_qtiles,
-                                                                   int64_t row_stride, int64_t head_stride,
+                                                                   float* __restrict__ LSE, int N, int Nk, int n_qtiles,
+                                                                   int64_t row_stride, int64_t head_stride, int64_t kv_head_stride,
                                                                    float scale) {
     constexpr int NT = D / 16;              // contraction steps over the head dim
     constexpr int NCB = D / 32;             // 32-channel blocks of the output
@@ -66,19 +66,20 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
     const int pr = blockIdx.x - head * n_pairs;
     const int64_t hoff = (int64_t)head * head_stride;
     const bf16* Qh = Q + hoff;
-    const bf16* Kh = K + hoff;
-    const bf16* Vh = V + hoff;
+    // N queries attend to Nk keys (Nk = N for self-attention); K and V may have their own head stride
+    const bf16* Kh = K + (int64_t)head * kv_head_stride;
+    const bf16* Vh = V + (int64_t)head * kv_head_stride;
 
     const typename KLoader::LaneOffsets k_ld = KLoader::lane_offsets(row_stride, wave, lane);
     const typename VLoader::LaneOffsets v_ld = VLoader::lane_offsets(row_stride, wave, lane);
     auto load_tile = [&](int kbuf, int vbuf, int kt) __attribute__((always_inline)) {     // buffer byte offsets
         const int r0 = kt * kFwdBK;
-        if (r0 + kFwdBK <= N) {
+        if (r0 + kFwdBK <= Nk) {
             KLoader::issue(smem + kbuf / 2, Kh + (int64_t)r0 * row_stride, k_ld, wave);
             VLoader::issue(smem + vbuf / 2, Vh + (int64_t)r0 * row_stride, v_ld, wave);
         } else {
-            KLoader::issue_clamped(smem + kbuf / 2, Kh, row_stride, r0, N, wave, lane);
-            VLoader::issue_clamped(smem + vbuf / 2, Vh, row_stride, r0, N, wave, lane);
+            KLoader::issue_clamped(smem + kbuf / 2, Kh, row_stride, r0, Nk, wave, lane);
+            VLoader::issue_clamped(smem + vbuf / 2, Vh, row_stride, r0, Nk, wave, lane);
         }
     };
     // per-lane LDS byte addresses inside a tile (buffer, block and half-block offsets are immediates)
@@ -104,8 +105,8 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
     const int qt = (CAUSAL && part == 0) ? n_qtiles - 1 - pr : pr;
     const int dir = part == 0 ? 1 : -1;                        // walking direction over the key tiles
     const int q0 = qt * kFwdBQ;
-    int k_end = N;
-    if (CAUSAL) { const int lim = q0 + kFwdBQ; k_end = lim < N ? lim : N; }
+    int k_end = Nk;
+    if (CAUSAL) { const int lim = q0 + kFwdBQ; k_end = lim < Nk ? lim : Nk; }
     const int n_kt = (k_end + kFwdBK - 1) / kFwdBK;
     auto tile_of = [&](int pos) __attribute__((always_inline)) { return dir > 0 ? pos : n_kt - 1 - pos; };
     load_tile(K0, V0, tile_of(0));
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
 
         if (MASKED) {
             // key kb0 + c_r + 4g (c_r = 8*(r/4) + r%4) is visible iff it is <= jmax: one limit per block
-            const int jmax = CAUSAL ? (q_row < N - 1 ? q_row : N - 1) : N - 1;
+            const int jmax = CAUSAL ? (q_row < Nk - 1 ? q_row : Nk - 1) : Nk - 1;
             const int lim = jmax - kb0 - 4 * g;
 #pragma unroll
             for (int r = 0; r < 16; ++r)
@@ -286,7 +287,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
     };
 
     // Blocks entirely below the diagonal for every wave and inside the sequence need no mask.
-    int n_full = N / kFwdBK;
+    int n_full = Nk / kFwdBK;
     if (CAUSAL) { const int lim = q0 / kFwdBK; n_full = lim < n_full ? lim : n_full; }
     using Plain = std::integral_constant<bool, false>;
     using Masked = std::integral_constant<bool, true>;
@@ -350,26 +351,26 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
 }
 
 template <int D>
-static int launch_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int Hl,
-                      float scale, int causal, TensorStrides st, hipStream_t stream) {
+static int launch_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
+                      float scale, int causal, TensorStrides st, TensorStrides kv, hipStream_t stream) {
     const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ;
     const int64_t blocks = ((causal && kFwdPair) ? (n_qtiles + 1) / 2 : n_qtiles) * Hl;    // causal: pairs of query tiles
     if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     dim3 grid((uint32_t)blocks), block(kFwdThreads);
     if (causal)
         attn_fwd_kernel<D, true><<<grid, block, 0, stream>>>((const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o,
-                                                             lse, (int)N, (int)n_qtiles, st.row, st.head, scale);
+                                                             lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale);
     else
         attn_fwd_kernel<D, false><<<grid, block, 0, stream>>>((const bf16*)q, (const bf16*)k, (const bf16*)v,
-                                                              (bf16*)o, lse, (int)N, (int)n_qtiles, st.row, st.head,
-                                                              scale);
+                                                              (bf16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
+                                                              kv.head, scale);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 
-int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int Hl, int d,
-                    float scale, int causal, TensorStrides st, void* stream) {
-    if (d == 128) return launch_fwd<128>(q, k, v, o, lse, N, Hl, scale, causal, st, (hipStream_t)stream);
-    return launch_fwd<64>(q, k, v, o, lse, N, Hl, scale, causal, st, (hipStream_t)stream);
+int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
+                    int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream) {
+    if (d == 128) return launch_fwd<128>(q, k, v, o, lse, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
+    return launch_fwd<64>(q, k, v, o, lse, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
 }
 
 }  // namespace uly

@@ -29,16 +29,18 @@ inline TensorStrides strides_for(int layout, int64_t N, int Hl, int d) {
     return s;
 }
 
-int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int Hl, int d,
-                    float scale, int causal, TensorStrides st, void* stream);
+// N queries attend to Nk keys/values (Nk = N for self-attention; causal requires Nk = N).  `st` are the
+// strides of the query-side tensors (q, o, dout, dq), `kv` those of k, v, dk, dv.
+int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
+                    int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
 
-// floats of scratch the backward kernels need (padded row statistics: delta and lse*log2e)
+// floats of scratch the backward kernels need (padded row statistics: delta and lse*log2e); N = queries
 int64_t attn_bwd_workspace_floats(int64_t N, int Hl);
 
 // stage_mask: bit 0 delta, bit 1 dK/dV, bit 2 dQ (kernels run in that order)
 int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
-                    const float* lse, void* dq, void* dk, void* dv, float* delta, int64_t N, int Hl, int d,
-                    float scale, int causal, TensorStrides st, void* stream);
+                    const float* lse, void* dq, void* dk, void* dv, float* delta, int64_t N, int64_t Nk, int Hl, int d,
+                    float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
 
 }  // namespace uly
 #endif

@@ -126,3 +126,25 @@ def test_build_scratch_report_parser():
     )
     assert build.scratch_bytes(text) == {"_Zk1": 0, "_Zk2": 120}
     assert build.scratch_bytes("no remarks here") == {}
+
+
+def test_cross_attention_validation(lib):
+    f = lambda **kw: lib.ulysses_xattn_fwd(*[{**dict(q=A, k=B, v=C_, o=D_, lse=0x7000000, Nq=128, Nk=96, Hl=2, d=64,
+                                                      scale=0.125, layout=0), **kw}[n]
+                                             for n in ("q", "k", "v", "o", "lse", "Nq", "Nk", "Hl", "d", "scale", "layout")],
+                                           None)
+    assert f(q=None) == 1 and f(k=None) == 1
+    assert f(Nq=-1) == 2 and f(Nk=-3) == 2 and f(Nk=0) == 2       # no keys: softmax undefined
+    assert f(Nq=0, Nk=0) == 0 and f(Nq=0) == 0
+    assert f(d=96) == 3 and f(scale=0.0) == 3 and f(layout=5) == 3
+    assert f(v=C_ + 4) == 4
+    assert f(o=B + 96 * 2 * 64 * 2 - 32) == 5                      # o overlaps the end of k (sized by Nk)
+    assert lib.ulysses_xattn_bwd_workspace_bytes(128, 96, 2, 64) == lib.ulysses_attn_bwd_workspace_bytes(128, 2, 64)
+    g = lambda **kw: lib.ulysses_xattn_bwd(*[{**dict(q=A, k=B, v=C_, o=D_, do=0x70000000, lse=0x7800000, dq=0x80000000,
+                                                      dk=0x90000000, dv=0xA0000000, ws=0xB0000000, wsb=1 << 20, Nq=128,
+                                                      Nk=96, Hl=2, d=64, scale=0.125, layout=0), **kw}[n]
+                                             for n in ("q", "k", "v", "o", "do", "lse", "dq", "dk", "dv", "ws", "wsb",
+                                                       "Nq", "Nk", "Hl", "d", "scale", "layout")], None)
+    assert g(dk=None) == 1 and g(Nk=0) == 2 and g(Nq=0) == 2 and g(Nq=0, Nk=0) == 0
+    assert g(wsb=16) == 6 and g(ws=None) == 6
+    assert g(dv=B + 64) == 5
