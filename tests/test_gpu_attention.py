@@ -105,6 +105,40 @@ def test_shape_sweep(gpu_lib, N, d, causal, layout, Hl):
     _full_parity(gpu_lib, N, Hl, d, causal=causal, layout=layout, seed=N)
 
 
+def _parity_on(gpu_lib, q, k, v, do, scale, causal=True):
+    o, lse, dq, dk, dv = _run_gpu(gpu_lib, q, k, v, do, scale, causal, 0)
+    fq, fk, fv, fdo = (oracle.bf16_to_f64(a) for a in (q, k, v, do))
+    o_ref, lse_ref = oracle.attn_fwd(fq, fk, fv, scale, causal)
+    o_abs, _ = oracle.attn_fwd(fq, fk, np.abs(fv), scale, causal)
+    ok, worst, n_bad = o_within_tolerance(f64_of(o), o_ref, o_abs, TOL_O)
+    assert ok, (worst, n_bad)
+    assert max_abs(f64_of(lse), lse_ref) <= TOL_LSE
+    for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), oracle.attn_bwd(fq, fk, fv, fdo, scale, causal)):
+        denom = np.sqrt((ref ** 2).sum())
+        if denom < 1e-6:                      # an exactly-zero gradient (e.g. dQ for constant K)
+            assert np.abs(f64_of(got)).max() <= 2e-2, name
+        else:
+            assert rel_l2(f64_of(got), ref) <= TOL_G, name
+
+
+@pytest.mark.parametrize("case", ["constant_k", "zero_q", "one_hot", "huge_logits"])
+def test_degenerate_inputs(gpu_lib, case):
+    """The degenerate cases of softmax: uniform rows (constant K, zero Q), one-hot rows, saturating logits."""
+    N, Hl, d = 1500, 2, 128
+    q, k, v, do = synth.attention_inputs(N, Hl, d, 77)
+    scale = 1.0 / np.sqrt(d)
+    if case == "constant_k":
+        k = np.broadcast_to(k[:1], k.shape).copy()
+    elif case == "zero_q":
+        q = np.zeros_like(q)
+    elif case == "one_hot":
+        scale = 4.0                                   # logit sigma about 45: one key takes all the weight
+    elif case == "huge_logits":
+        q, k, _, _ = synth.attention_inputs(N, Hl, d, 78, 8.0)   # |logit| up to several thousand before scaling
+        scale = 1.0
+    _parity_on(gpu_lib, q, k, v, do, scale)
+
+
 def test_backward_is_deterministic(gpu_lib):
     q, k, v, do = synth.attention_inputs(777, 2, 128, 3)
     a = _run_gpu(gpu_lib, q, k, v, do, 0.088, True, 0)
