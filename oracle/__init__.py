@@ -46,8 +46,10 @@ def _load():
         lib.oracle_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, dbl, ci, ci]
         lib.oracle_xattn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, ci, ci, dbl, ci]
         lib.oracle_xattn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, ci, ci, dbl, ci]
+        lib.oracle_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, ci, ci, dbl, ci]
+        lib.oracle_sparse_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, ci, ci, dbl, ci]
         for f in (lib.oracle_attn_fwd, lib.oracle_attn_fwd_rows, lib.oracle_attn_bwd_rows, lib.oracle_attn_bwd,
-                  lib.oracle_xattn_fwd, lib.oracle_xattn_bwd):
+                  lib.oracle_xattn_fwd, lib.oracle_xattn_bwd, lib.oracle_sparse_attn_fwd, lib.oracle_sparse_attn_bwd):
             f.restype = ci
         lib.oracle_num_threads.restype = ci
         _lib = lib
@@ -196,6 +198,44 @@ def xattn_bwd(q, k, v, dout, scale: float, layout: int = LAYOUT_SEQ_HEAD):
                                   dq.ctypes.data, dk.ctypes.data, dv.ctypes.data, Nq, Nk, Hl, d, scale, layout)
     if rc:
         raise MemoryError("oracle_xattn_bwd")
+    return dq, dk, dv
+
+
+def _block_mask(mask, N, B):
+    nb = (N + B - 1) // B
+    m = np.ascontiguousarray(np.asarray(mask) != 0, dtype=np.uint8)
+    if m.shape != (nb, nb):
+        raise ValueError(f"block mask must be {nb} x {nb}")
+    return m
+
+
+def sparse_attn_fwd(q, k, v, mask, B: int, scale: float, layout: int = LAYOUT_SEQ_HEAD):
+    """Causal attention restricted to the blocks set in ``mask`` [ceil(N/B), ceil(N/B)] (diagonal required)."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    N, Hl, d = _dims(q, layout)
+    m = _block_mask(mask, N, B)
+    o = np.empty_like(q); lse = np.empty((Hl, N), np.float64)
+    rc = _load().oracle_sparse_attn_fwd(q.ctypes.data, k.ctypes.data, v.ctypes.data, o.ctypes.data, lse.ctypes.data,
+                                        m.ctypes.data, B, N, Hl, d, scale, layout)
+    if rc == 3:
+        raise ValueError("every diagonal block must be set")
+    if rc:
+        raise MemoryError("oracle_sparse_attn_fwd")
+    return o, lse
+
+
+def sparse_attn_bwd(q, k, v, dout, mask, B: int, scale: float, layout: int = LAYOUT_SEQ_HEAD):
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    N, Hl, d = _dims(q, layout)
+    m = _block_mask(mask, N, B)
+    dq, dk, dv = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    rc = _load().oracle_sparse_attn_bwd(q.ctypes.data, k.ctypes.data, v.ctypes.data, dout.ctypes.data,
+                                        dq.ctypes.data, dk.ctypes.data, dv.ctypes.data, m.ctypes.data, B, N, Hl, d,
+                                        scale, layout)
+    if rc == 3:
+        raise ValueError("every diagonal block must be set")
+    if rc:
+        raise MemoryError("oracle_sparse_attn_bwd")
     return dq, dk, dv
 
 

@@ -401,6 +401,107 @@ int oracle_xattn_bwd(const double* q, const double* k, const double* v, const do
     return 0;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Block-sparse causal attention (the paper names "blocked sparse attention"   */
+/* in Section 3.4 and evaluates it in Section 4.3 without fixing a pattern).   */
+/* Reading used here: key j is visible to query i iff j <= i and the block     */
+/* (i / B, j / B) is set in a caller-given nb x nb byte mask, nb = ceil(N/B);  */
+/* all heads share the mask; every diagonal block must be set.  Equation 1 is  */
+/* then evaluated over the visible keys only.  Written on its own.             */
+/* ------------------------------------------------------------------------- */
+static inline int sparse_visible(const uint8_t* mask, int64_t nb, int64_t B, int64_t i, int64_t j) {
+    return j <= i && mask[(i / B) * nb + (j / B)] != 0;
+}
+
+/* returns 3 if a diagonal block is missing */
+static int sparse_mask_ok(const uint8_t* mask, int64_t nb) {
+    for (int64_t r = 0; r < nb; ++r)
+        if (!mask[r * nb + r]) return 0;
+    return 1;
+}
+
+int oracle_sparse_attn_fwd(const double* q, const double* k, const double* v, double* o, double* lse,
+                           const uint8_t* mask, int64_t B, int64_t N, int Hl, int d, double scale, int layout) {
+    const int64_t nb = (N + B - 1) / B;
+    if (!sparse_mask_ok(mask, nb)) return 3;
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (int h = 0; h < Hl; ++h)
+        for (int64_t i = 0; i < N; ++i) {
+            const double* qi = q + row_off(i, h, N, Hl, d, layout);
+            double* oi = o + row_off(i, h, N, Hl, d, layout);
+            double m = -INFINITY, l = 0.0;
+            for (int64_t j = 0; j <= i; ++j)
+                if (sparse_visible(mask, nb, B, i, j)) {
+                    const double sij = scale * dot(qi, k + row_off(j, h, N, Hl, d, layout), d);
+                    if (sij > m) m = sij;
+                }
+            for (int64_t j = 0; j <= i; ++j)
+                if (sparse_visible(mask, nb, B, i, j))
+                    l += exp(scale * dot(qi, k + row_off(j, h, N, Hl, d, layout), d) - m);
+            const double L = m + log(l);
+            for (int c = 0; c < d; ++c) oi[c] = 0.0;
+            for (int64_t j = 0; j <= i; ++j)
+                if (sparse_visible(mask, nb, B, i, j)) {
+                    const double p = exp(scale * dot(qi, k + row_off(j, h, N, Hl, d, layout), d) - L);
+                    const double* vj = v + row_off(j, h, N, Hl, d, layout);
+                    for (int c = 0; c < d; ++c) oi[c] += p * vj[c];
+                }
+            lse[(int64_t)h * N + i] = L;
+        }
+    return 0;
+}
+
+int oracle_sparse_attn_bwd(const double* q, const double* k, const double* v, const double* dout,
+                           double* dq, double* dk, double* dv,
+                           const uint8_t* mask, int64_t B, int64_t N, int Hl, int d, double scale, int layout) {
+    const int64_t nb = (N + B - 1) / B;
+    if (!sparse_mask_ok(mask, nb)) return 3;
+    double* o = (double*)malloc(sizeof(double) * (size_t)(N * Hl * d + 1));
+    double* lse = (double*)malloc(sizeof(double) * (size_t)(N * Hl + 1));
+    double* D = (double*)malloc(sizeof(double) * (size_t)(N * Hl + 1));
+    if (!o || !lse || !D || oracle_sparse_attn_fwd(q, k, v, o, lse, mask, B, N, Hl, d, scale, layout)) {
+        free(o); free(lse); free(D);
+        return 1;
+    }
+    for (int h = 0; h < Hl; ++h)
+        for (int64_t i = 0; i < N; ++i)
+            D[(int64_t)h * N + i] = dot(dout + row_off(i, h, N, Hl, d, layout), o + row_off(i, h, N, Hl, d, layout), d);
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (int h = 0; h < Hl; ++h)
+        for (int64_t i = 0; i < N; ++i) {
+            const double* qi = q + row_off(i, h, N, Hl, d, layout);
+            const double* doi = dout + row_off(i, h, N, Hl, d, layout);
+            double* dqi = dq + row_off(i, h, N, Hl, d, layout);
+            for (int c = 0; c < d; ++c) dqi[c] = 0.0;
+            for (int64_t j = 0; j <= i; ++j)
+                if (sparse_visible(mask, nb, B, i, j)) {
+                    const double* kj = k + row_off(j, h, N, Hl, d, layout);
+                    const double p = exp(scale * dot(qi, kj, d) - lse[(int64_t)h * N + i]);
+                    const double ds = p * (dot(doi, v + row_off(j, h, N, Hl, d, layout), d) - D[(int64_t)h * N + i]);
+                    for (int c = 0; c < d; ++c) dqi[c] += scale * ds * kj[c];
+                }
+        }
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (int h = 0; h < Hl; ++h)
+        for (int64_t j = 0; j < N; ++j) {
+            const double* kj = k + row_off(j, h, N, Hl, d, layout);
+            const double* vj = v + row_off(j, h, N, Hl, d, layout);
+            double* dkj = dk + row_off(j, h, N, Hl, d, layout);
+            double* dvj = dv + row_off(j, h, N, Hl, d, layout);
+            for (int c = 0; c < d; ++c) { dkj[c] = 0.0; dvj[c] = 0.0; }
+            for (int64_t i = j; i < N; ++i)
+                if (sparse_visible(mask, nb, B, i, j)) {
+                    const double* qi = q + row_off(i, h, N, Hl, d, layout);
+                    const double* doi = dout + row_off(i, h, N, Hl, d, layout);
+                    const double p = exp(scale * dot(qi, kj, d) - lse[(int64_t)h * N + i]);
+                    const double ds = p * (dot(doi, vj, d) - D[(int64_t)h * N + i]);
+                    for (int c = 0; c < d; ++c) { dvj[c] += p * doi[c]; dkj[c] += scale * ds * qi[c]; }
+                }
+        }
+    free(o); free(lse); free(D);
+    return 0;
+}
+
 int oracle_num_threads(void) {
     int n = 1;
 #ifdef _OPENMP
