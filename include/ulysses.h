@@ -147,6 +147,36 @@ int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o
                       void* workspace, size_t workspace_bytes,
                       int64_t Nq, int64_t Nk, int Hl, int d, float scale, int layout, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Block-sparse causal attention.  The paper names blocked sparse attention among the supported
+ * forms (Section 3.4) and evaluates it (Section 4.3) without fixing a pattern; here the caller gives
+ * one: key j is visible to query i iff j <= i AND block (i / 256, j / 256) belongs to the pattern.
+ * Equation 1 is evaluated over the visible keys; all local heads share the pattern.
+ *
+ * The pattern is a set of blocks of ULY_SPARSE_BLOCK x ULY_SPARSE_BLOCK tokens, nb = ceil(N / 256)
+ * block rows and columns, given in compressed form as DEVICE arrays of int32:
+ *   row_ptr [nb + 1], col_idx [nnz]: block row r sees block columns col_idx[row_ptr[r] .. row_ptr[r+1]),
+ *       strictly ascending, every one <= r, and the last one == r (each diagonal block is required:
+ *       a query always sees itself);
+ *   col_ptr [nb + 1], row_idx [nnz]: the same set by columns (backward only): block column c is seen
+ *       by block rows row_idx[col_ptr[c] .. col_ptr[c+1]), strictly ascending, the first one == c.
+ * The arrays live in device memory, so the library cannot check their contents: a pattern that
+ * breaks these rules is undefined behaviour (the Python binding builds and checks them on the host).
+ * Other arguments, precision, workspace and status codes are those of ulysses_attn_fwd / _bwd with
+ * causal = 1; the pattern arrays must be non-NULL and 4-byte aligned.
+ * ------------------------------------------------------------------------------------------- */
+#define ULY_SPARSE_BLOCK 256
+int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                            const int32_t* row_ptr, const int32_t* col_idx,
+                            int64_t N, int Hl, int d, float scale, int layout, void* stream);
+size_t ulysses_sparse_attn_bwd_workspace_bytes(int64_t N, int Hl, int d);
+int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                            const float* lse, void* dq, void* dk, void* dv,
+                            const int32_t* row_ptr, const int32_t* col_idx,
+                            const int32_t* col_ptr, const int32_t* row_idx,
+                            void* workspace, size_t workspace_bytes,
+                            int64_t N, int Hl, int d, float scale, int layout, void* stream);
+
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* ulysses_status_string(int status);
 

@@ -19,6 +19,7 @@ LAYOUT_HEAD_SEQ = 1   # [Hl, N, d]
 EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
            "ulysses_pack_qkv", "ulysses_unpack_qkv",
            "ulysses_xattn_fwd", "ulysses_xattn_bwd_workspace_bytes", "ulysses_xattn_bwd",
+           "ulysses_sparse_attn_fwd", "ulysses_sparse_attn_bwd_workspace_bytes", "ulysses_sparse_attn_bwd",
            "ulysses_attn_fwd", "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd", "ulysses_attn_bwd_stage",
            "ulysses_status_string", "ulysses_abi_version")
 
@@ -58,11 +59,15 @@ def load(path: str | None = None):
     lib.ulysses_xattn_bwd_workspace_bytes.argtypes = [i64, i64, ci, ci]
     lib.ulysses_xattn_bwd_workspace_bytes.restype = sz
     lib.ulysses_xattn_bwd.argtypes = [vp] * 10 + [sz, i64, i64, ci, ci, cf, ci, vp]
+    lib.ulysses_sparse_attn_fwd.argtypes = [vp] * 7 + [i64, ci, ci, cf, ci, vp]
+    lib.ulysses_sparse_attn_bwd_workspace_bytes.argtypes = [i64, ci, ci]
+    lib.ulysses_sparse_attn_bwd_workspace_bytes.restype = sz
+    lib.ulysses_sparse_attn_bwd.argtypes = [vp] * 14 + [sz, i64, ci, ci, cf, ci, vp]
     lib.ulysses_status_string.argtypes = [ci]
     lib.ulysses_status_string.restype = ctypes.c_char_p
     for name in ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
                  "ulysses_pack_qkv", "ulysses_unpack_qkv", "ulysses_xattn_fwd", "ulysses_xattn_bwd",
-                 "ulysses_attn_fwd", "ulysses_attn_bwd", "ulysses_attn_bwd_stage", "ulysses_abi_version"):
+                 "ulysses_sparse_attn_fwd", "ulysses_sparse_attn_bwd", "ulysses_attn_fwd", "ulysses_attn_bwd", "ulysses_attn_bwd_stage", "ulysses_abi_version"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -244,4 +249,73 @@ def ulysses_xattn_bwd(q, k, v, o, dout, lse, scale: float, layout: int = LAYOUT_
     _check(load().ulysses_xattn_bwd(_dev(q, w), _dev(k, w), _dev(v, w), _dev(o, w), _dev(dout, w), _dev(lse, w),
                                     _dev(dq, w), _dev(dk, w), _dev(dv, w), _dev(workspace, w), workspace.numel(),
                                     Nq, Nk, Hl, d, scale, layout, _stream()), "ulysses_xattn_bwd")
+    return dq, dk, dv
+
+
+SPARSE_BLOCK = 256
+
+
+class SparsePattern:
+    """A block-sparse causal pattern in the compressed form the library takes (device int32 arrays).
+    ``mask`` is a [nb, nb] boolean array over 256-token blocks; only its lower triangle is used and every
+    diagonal block must be set.  Built and checked on the host."""
+
+    def __init__(self, mask, device="cuda"):
+        import numpy as np
+        import torch
+        m = np.asarray(mask).astype(bool)
+        if m.ndim != 2 or m.shape[0] != m.shape[1]:
+            raise ValueError("block mask must be square")
+        m = np.tril(m)
+        if not m.diagonal().all():
+            raise ValueError("every diagonal block must be set")
+        self.nb = m.shape[0]
+        rows, cols = np.nonzero(m)                      # row-major order: ascending columns inside a row
+        self.row_ptr = np.concatenate([[0], np.cumsum(m.sum(1))]).astype(np.int32)
+        self.col_idx = cols.astype(np.int32)
+        cols_t, rows_t = np.nonzero(m.T)                # column-major: ascending rows inside a column
+        self.col_ptr = np.concatenate([[0], np.cumsum(m.sum(0))]).astype(np.int32)
+        self.row_idx = rows_t.astype(np.int32)
+        self.nnz = int(m.sum())
+        self.dev = {n: torch.from_numpy(getattr(self, n)).to(device)
+                    for n in ("row_ptr", "col_idx", "col_ptr", "row_idx")}
+
+
+def _pattern_for(pattern, N):
+    if pattern.nb != (N + SPARSE_BLOCK - 1) // SPARSE_BLOCK:
+        raise ValueError("pattern does not match the sequence length")
+    return pattern.dev
+
+
+def ulysses_sparse_attn_fwd(q, k, v, pattern: SparsePattern, scale: float, layout: int = LAYOUT_SEQ_HEAD):
+    """Causal attention restricted to the blocks of ``pattern`` -> (o, lse)."""
+    import torch
+    if q.dtype != torch.bfloat16:
+        raise ValueError("attention tensors must be bfloat16")
+    N, Hl, d = _attn_dims(q, layout)
+    p = _pattern_for(pattern, N)
+    o = torch.empty_like(q)
+    lse = torch.empty((Hl, N), dtype=torch.float32, device=q.device)
+    w = "sparse_attn_fwd"
+    _check(load().ulysses_sparse_attn_fwd(_dev(q, w), _dev(k, w), _dev(v, w), _dev(o, w), _dev(lse, w),
+                                          _dev(p["row_ptr"], w), _dev(p["col_idx"], w), N, Hl, d, scale, layout,
+                                          _stream()), "ulysses_sparse_attn_fwd")
+    return o, lse
+
+
+def ulysses_sparse_attn_bwd(q, k, v, o, dout, lse, pattern: SparsePattern, scale: float,
+                            layout: int = LAYOUT_SEQ_HEAD):
+    """-> (dq, dk, dv) bf16 in ``layout``."""
+    import torch
+    N, Hl, d = _attn_dims(q, layout)
+    p = _pattern_for(pattern, N)
+    need = int(load().ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d))
+    workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    w = "sparse_attn_bwd"
+    _check(load().ulysses_sparse_attn_bwd(_dev(q, w), _dev(k, w), _dev(v, w), _dev(o, w), _dev(dout, w), _dev(lse, w),
+                                          _dev(dq, w), _dev(dk, w), _dev(dv, w), _dev(p["row_ptr"], w),
+                                          _dev(p["col_idx"], w), _dev(p["col_ptr"], w), _dev(p["row_idx"], w),
+                                          _dev(workspace, w), workspace.numel(), N, Hl, d, scale, layout, _stream()),
+           "ulysses_sparse_attn_bwd")
     return dq, dk, dv

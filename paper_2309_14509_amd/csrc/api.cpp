@@ -230,6 +230,52 @@ int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o
                             layout, stream);
 }
 
+int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* row_ptr,
+                            const int32_t* col_idx, int64_t N, int Hl, int d, float scale, int layout, void* stream) {
+    uint64_t tb;
+    const int rc = check_attn_common(N, Hl, d, layout, &tb);
+    if (rc != ULY_OK) return rc;
+    if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;
+    if (N == 0) return ULY_OK;
+    if (!q || !k || !v || !o || !lse || !row_ptr || !col_idx) return ULY_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse)) return ULY_ERR_ALIGN;
+    if (((uintptr_t)row_ptr | (uintptr_t)col_idx) & 3u) return ULY_ERR_ALIGN;
+    const Range in[3] = {{q, tb}, {k, tb}, {v, tb}};
+    const Range out[2] = {{o, tb}, {lse, (uint64_t)N * Hl * 4u}};
+    if (any_alias(in, out)) return ULY_ERR_ALIAS;
+    return uly::attn_fwd_sparse_launch(q, k, v, o, lse, row_ptr, col_idx, N, Hl, d, scale,
+                                       uly::strides_for(layout, N, Hl, d), stream);
+}
+
+size_t ulysses_sparse_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
+    return ulysses_attn_bwd_workspace_bytes(N, Hl, d);
+}
+
+int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                            const float* lse, void* dq, void* dk, void* dv, const int32_t* row_ptr,
+                            const int32_t* col_idx, const int32_t* col_ptr, const int32_t* row_idx, void* workspace,
+                            size_t workspace_bytes, int64_t N, int Hl, int d, float scale, int layout, void* stream) {
+    uint64_t tb;
+    const int rc = check_attn_common(N, Hl, d, layout, &tb);
+    if (rc != ULY_OK) return rc;
+    if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;
+    if (N == 0) return ULY_OK;
+    if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv || !row_ptr || !col_idx || !col_ptr || !row_idx)
+        return ULY_ERR_NULL;
+    const size_t need = ulysses_attn_bwd_workspace_bytes(N, Hl, d);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return ULY_ERR_WORKSPACE;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(dout) || misaligned(lse) ||
+        misaligned(dq) || misaligned(dk) || misaligned(dv) || misaligned(workspace))
+        return ULY_ERR_ALIGN;
+    if (((uintptr_t)row_ptr | (uintptr_t)col_idx | (uintptr_t)col_ptr | (uintptr_t)row_idx) & 3u) return ULY_ERR_ALIGN;
+    const uint64_t lb = (uint64_t)N * Hl * 4u;
+    const Range in[6] = {{q, tb}, {k, tb}, {v, tb}, {o, tb}, {dout, tb}, {lse, lb}};
+    const Range out[4] = {{dq, tb}, {dk, tb}, {dv, tb}, {workspace, need}};
+    if (any_alias(in, out)) return ULY_ERR_ALIAS;
+    return uly::attn_bwd_sparse_launch(q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, row_ptr, col_idx, col_ptr,
+                                       row_idx, N, Hl, d, scale, uly::strides_for(layout, N, Hl, d), stream);
+}
+
 const char* ulysses_status_string(int status) {
     switch (status) {
         case ULY_OK: return "ok";

@@ -64,11 +64,19 @@ constexpr int kDqBQ = 128;    // queries per workgroup
 constexpr int kDqBK = 32;     // keys per LDS tile
 constexpr int kDqRing = 4;
 
-template <int D, bool CAUSAL>
+// SPARSE (causal only) in both backward kernels: the (query, key) pairs are further restricted to the
+// blocks of a CSR pattern over 256 x 256 token blocks (see the forward kernel).  The dQ kernel walks the
+// block columns listed for its block row (row_ptr, col_idx: ascending, diagonal last); the dK/dV kernel
+// the block rows listed for its block column (col_ptr, row_idx: ascending, diagonal first).
+constexpr int kSparseBlockBwd = 256;
+
+template <int D, bool CAUSAL, bool SPARSE = false>
 __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dO,
     const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, bf16* __restrict__ dQ, int N,
-    int Nk, int n_qtiles, int64_t row_stride, int64_t head_stride, int64_t kv_head_stride, float scale) {
+    int Nk, int n_qtiles, int64_t row_stride, int64_t head_stride, int64_t kv_head_stride, float scale,
+    const int* __restrict__ row_ptr, const int* __restrict__ col_idx) {
+    static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
     constexpr int NT = D / 16, NCB = D / 32;
     constexpr int TILE = kDqBK * D;
     constexpr int TB = TILE * 2;
@@ -85,7 +93,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     // upwards from the start of the sequence and those of the second downwards from its diagonal: at
     // any moment all workgroups that started together read one of only two key blocks, which keeps
     // the K/V stream in the L2 caches instead of re-fetching it per workgroup.
-    const int n_pairs = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;
+    const int n_pairs = (CAUSAL && !SPARSE) ? (n_qtiles + 1) / 2 : n_qtiles;
     const int head = blockIdx.x / n_pairs;
     const int pr = blockIdx.x - head * n_pairs;
     const int64_t hoff = (int64_t)head * head_stride;
@@ -123,18 +131,30 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
                                              4 * (i & 1));
     }
 
-    const int n_parts = (CAUSAL && n_qtiles - 1 - pr != pr) ? 2 : 1;
+    const int n_parts = (CAUSAL && !SPARSE && n_qtiles - 1 - pr != pr) ? 2 : 1;
 #pragma unroll 1
     for (int part = 0; part < n_parts; ++part) {
-    const int qt = (CAUSAL && part == 0) ? n_qtiles - 1 - pr : pr;
+    const int qt = (CAUSAL && !SPARSE && part == 0) ? n_qtiles - 1 - pr : pr;
     const int dir = part == 0 ? 1 : -1;                        // walking direction over the key blocks
     const int q0 = qt * kDqBQ;
     // blocks to process (a multiple of 4); the last four in sequence order carry the mask (diagonal
     // and/or end of the sequence), all others are entirely visible
-    const int cnt = CAUSAL ? (q0 + kDqBQ) / kDqBK : (nblk + 3) & ~3;
+    int cnt = CAUSAL ? (q0 + kDqBQ) / kDqBK : (nblk + 3) & ~3;
+    // SPARSE: BPS key blocks for every listed block column but the last (the diagonal one), which
+    // contributes the key blocks from its start up to this tile's own diagonal
+    constexpr int BPS = kSparseBlockBwd / kDqBK;
+    int sp0 = 0, n_off = 0, diag0 = 0;
+    if (SPARSE) {
+        const int brow = q0 / kSparseBlockBwd;
+        sp0 = row_ptr[brow];
+        n_off = BPS * (row_ptr[brow + 1] - sp0 - 1);
+        diag0 = brow * BPS;
+        cnt = n_off + (q0 + kDqBQ) / kDqBK - diag0;
+    }
     // block at walk position p; positions past the end re-read the last one (their tiles are never used)
     auto blk = [&](int p) __attribute__((always_inline)) {
         p = p < cnt ? p : cnt - 1;
+        if (SPARSE) return p < n_off ? BPS * col_idx[sp0 + p / BPS] + p % BPS : diag0 + (p - n_off);
         return dir > 0 ? p : cnt - 1 - p;
     };
 #pragma unroll
@@ -374,12 +394,13 @@ constexpr int kDkvBK = 128;   // keys per workgroup
 constexpr int kDkvBQ = 32;    // queries per LDS tile
 constexpr int kDkvRing = 4;   // LDS tiles per tensor
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool SPARSE = false>
 __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dO,
     const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, bf16* __restrict__ dK,
     bf16* __restrict__ dV, int N, int Nk, int n_ktiles, int64_t row_stride, int64_t head_stride,
-    int64_t kv_head_stride, float scale) {
+    int64_t kv_head_stride, float scale, const int* __restrict__ col_ptr, const int* __restrict__ row_idx) {
+    static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
     constexpr int NT = D / 16, NCB = D / 32;
     constexpr int TILE = kDkvBQ * D;            // elements per tile
     constexpr int TB = TILE * 2;                // bytes per tile
@@ -399,7 +420,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     // the first tile downwards from the end of the sequence and those of the second upwards from its
     // diagonal: at any moment all workgroups that started together read one of only two query
     // blocks, which keeps the Q/dO stream in the L2 caches instead of re-fetching it per workgroup.
-    const int n_pairs = CAUSAL ? (n_ktiles + 1) / 2 : n_ktiles;
+    const int n_pairs = (CAUSAL && !SPARSE) ? (n_ktiles + 1) / 2 : n_ktiles;
     const int head = blockIdx.x / n_pairs;
     const int pr = blockIdx.x - head * n_pairs;
     const int64_t hoff = (int64_t)head * head_stride;
@@ -465,17 +486,28 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     }
     const uint32_t st_adr = lds_addr(stat) + 16 * g;    // rows 8q+4g .. +3 of a slot: immediate 32q (+256: delta)
 
-    const int n_parts = (CAUSAL && n_ktiles - 1 - pr != pr) ? 2 : 1;
+    const int n_parts = (CAUSAL && !SPARSE && n_ktiles - 1 - pr != pr) ? 2 : 1;
 #pragma unroll 1
     for (int part = 0; part < n_parts; ++part) {
     const int ktile = part == 0 ? pr : n_ktiles - 1 - pr;
-    const int dir = (CAUSAL && part == 0) ? -1 : 1;           // walking direction over the query blocks
+    const int dir = (CAUSAL && !SPARSE && part == 0) ? -1 : 1;   // walking direction over the query blocks
     const int j0 = ktile * kDkvBK;
     const int b0 = CAUSAL ? j0 / kDkvBQ : 0;                  // first block that sees a key of this tile
-    const int cnt = nblk4 - b0;                               // blocks to process (a multiple of 4)
+    int cnt = nblk4 - b0;                                     // blocks to process (a multiple of 4)
+    // SPARSE: the diagonal block row (listed first) contributes the query blocks from this tile's
+    // diagonal to its end, every further listed block row BPS query blocks
+    constexpr int BPS = kSparseBlockBwd / kDkvBQ;
+    int sp0 = 0, n_diag = 0;
+    if (SPARSE) {
+        const int bcol = j0 / kSparseBlockBwd;
+        sp0 = col_ptr[bcol];
+        n_diag = (bcol + 1) * BPS - b0;
+        cnt = n_diag + BPS * (col_ptr[bcol + 1] - sp0 - 1);
+    }
     // block at walk position p; positions past the end re-read the last one (their tiles are never used)
     auto blk = [&](int p) __attribute__((always_inline)) {
         p = p < cnt ? p : cnt - 1;
+        if (SPARSE) return p < n_diag ? b0 + p : BPS * row_idx[sp0 + 1 + (p - n_diag) / BPS] + (p - n_diag) % BPS;
         return dir > 0 ? b0 + p : nblk4 - 1 - p;
     };
 #pragma unroll
@@ -769,7 +801,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 }
 
 // padded row stride of the statistics arrays in the workspace
-inline int64_t stats_stride(int64_t N) { return ((N + 127) / 128) * 128 + 64; }
+inline int64_t stats_stride(int64_t N) { return ((N + 255) / 256) * 256 + 64; }   // covers whole sparse blocks
 
 template <int D>
 static int launch_bwd(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
@@ -795,23 +827,62 @@ static int launch_bwd(int stage_mask, const void* q, const void* k, const void* 
         if (causal)
             attn_bwd_dkv_kernel<D, true><<<gkv, dim3(kDkvThreads), 0, stream>>>(
                 Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
-                kv.head, scale);
+                kv.head, scale, nullptr, nullptr);
         else
             attn_bwd_dkv_kernel<D, false><<<gkv, dim3(kDkvThreads), 0, stream>>>(
                 Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
-                kv.head, scale);
+                kv.head, scale, nullptr, nullptr);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     if (stage_mask & 4) {
         if (causal)
             attn_bwd_dq_kernel<D, true><<<gq, dim3(kDqThreads), 0, stream>>>(
-                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale);
+                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
+                nullptr, nullptr);
         else
             attn_bwd_dq_kernel<D, false><<<gq, dim3(kDqThreads), 0, stream>>>(
-                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale);
+                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
+                nullptr, nullptr);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     return ULY_OK;
+}
+
+// Block-sparse causal backward (all three stages): one key tile / query tile per workgroup.
+template <int D>
+static int launch_bwd_sparse(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                             const float* lse, void* dq, void* dk, void* dv, float* ws, const int* row_ptr,
+                             const int* col_idx, const int* col_ptr, const int* row_idx, int64_t N, int Hl, float scale,
+                             TensorStrides st, hipStream_t stream) {
+    const int64_t stride = stats_stride(N);
+    float* delta = ws;
+    float* lse2 = ws + stride * Hl;
+    const int64_t delta_blocks = (stride * Hl * (D / 8) + 255) / 256;
+    const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (N + kDkvBK - 1) / kDkvBK;
+    if (delta_blocks > 0x7FFFFFFFll || n_qtiles * Hl > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
+    const bf16 *Q = (const bf16*)q, *K = (const bf16*)k, *V = (const bf16*)v, *dO = (const bf16*)dout;
+    attn_bwd_delta_kernel<D><<<dim3((uint32_t)delta_blocks), dim3(256), 0, stream>>>(
+        (const bf16*)o, dO, lse, delta, lse2, (int)N, Hl, stride, st.row, st.head);
+    if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+    attn_bwd_dkv_kernel<D, true, true><<<dim3((uint32_t)(n_ktiles * Hl)), dim3(kDkvThreads), 0, stream>>>(
+        Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)N, (int)n_ktiles, st.row, st.head, st.head,
+        scale, col_ptr, row_idx);
+    if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+    attn_bwd_dq_kernel<D, true, true><<<dim3((uint32_t)(n_qtiles * Hl)), dim3(kDqThreads), 0, stream>>>(
+        Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)N, (int)n_qtiles, st.row, st.head, st.head, scale,
+        row_ptr, col_idx);
+    return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
+}
+
+int attn_bwd_sparse_launch(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                           const float* lse, void* dq, void* dk, void* dv, float* ws, const int* row_ptr,
+                           const int* col_idx, const int* col_ptr, const int* row_idx, int64_t N, int Hl, int d,
+                           float scale, TensorStrides st, void* stream) {
+    if (d == 128)
+        return launch_bwd_sparse<128>(q, k, v, o, dout, lse, dq, dk, dv, ws, row_ptr, col_idx, col_ptr, row_idx, N, Hl,
+                                      scale, st, (hipStream_t)stream);
+    return launch_bwd_sparse<64>(q, k, v, o, dout, lse, dq, dk, dv, ws, row_ptr, col_idx, col_ptr, row_idx, N, Hl, scale,
+                                 st, (hipStream_t)stream);
 }
 
 int64_t attn_bwd_workspace_floats(int64_t N, int Hl) { return 2 * stats_stride(N) * Hl; }

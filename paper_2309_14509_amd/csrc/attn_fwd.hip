@@ -29,12 +29,20 @@ constexpr int kFwdBK = 64;    // keys per LDS tile
 // workgroups share a CU, and when all of them walk in step their softmax and MFMA phases collide.
 constexpr bool kFwdPair = false;
 
-template <int D, bool CAUSAL>
+// SPARSE (causal only): the keys a query tile sees are further restricted to the 256-key blocks listed for
+// its block row in a CSR pattern (row_ptr, col_idx: ascending block columns, the diagonal one last); a
+// query tile is exactly one block row.  Dense kernels ignore the two pointers.
+constexpr int kSparseBlock = 256;
+static_assert(kFwdBQ == kSparseBlock && kSparseBlock % kFwdBK == 0, "a query tile must be one sparse block row");
+
+template <int D, bool CAUSAL, bool SPARSE = false>
 __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                                    const bf16* __restrict__ V, bf16* __restrict__ O,
                                                                    float* __restrict__ LSE, int N, int Nk, int n_qtiles,
                                                                    int64_t row_stride, int64_t head_stride, int64_t kv_head_stride,
-                                                                   float scale) {
+                                                                   float scale, const int* __restrict__ row_ptr,
+                                                                   const int* __restrict__ col_idx) {
+    static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
     constexpr int NT = D / 16;              // contraction steps over the head dim
     constexpr int NCB = D / 32;             // 32-channel blocks of the output
     constexpr int TILE = kFwdBK * D;        // elements per LDS tile
@@ -61,7 +69,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
     // upwards from the start of the sequence and those of the second downwards from its diagonal: at
     // any moment all workgroups that started together read one of only two key tiles, which keeps
     // the K/V stream in the L2 caches instead of re-fetching it per workgroup.
-    const int n_pairs = (CAUSAL && kFwdPair) ? (n_qtiles + 1) / 2 : n_qtiles;
+    const int n_pairs = (CAUSAL && kFwdPair && !SPARSE) ? (n_qtiles + 1) / 2 : n_qtiles;
     const int head = blockIdx.x / n_pairs;
     const int pr = blockIdx.x - head * n_pairs;
     const int64_t hoff = (int64_t)head * head_stride;
@@ -99,7 +107,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
 
     const float sl2 = scale * kLog2e;
 
-    const int n_parts = (CAUSAL && kFwdPair && n_qtiles - 1 - pr != pr) ? 2 : 1;
+    const int n_parts = (CAUSAL && kFwdPair && !SPARSE && n_qtiles - 1 - pr != pr) ? 2 : 1;
 #pragma unroll 1
     for (int part = 0; part < n_parts; ++part) {
     const int qt = (CAUSAL && part == 0) ? n_qtiles - 1 - pr : pr;
@@ -107,8 +115,18 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
     const int q0 = qt * kFwdBQ;
     int k_end = Nk;
     if (CAUSAL) { const int lim = q0 + kFwdBQ; k_end = lim < Nk ? lim : Nk; }
-    const int n_kt = (k_end + kFwdBK - 1) / kFwdBK;
-    auto tile_of = [&](int pos) __attribute__((always_inline)) { return dir > 0 ? pos : n_kt - 1 - pos; };
+    constexpr int TPB = kSparseBlock / kFwdBK;                 // key tiles per sparse block
+    int n_kt = (k_end + kFwdBK - 1) / kFwdBK;
+    int sp0 = 0;                                               // first entry of this block row in col_idx
+    if (SPARSE) {
+        sp0 = row_ptr[qt];
+        // every listed block but the last (the diagonal one) is entirely visible: TPB tiles each
+        n_kt = TPB * (row_ptr[qt + 1] - sp0 - 1) + (k_end - q0 + kFwdBK - 1) / kFwdBK;
+    }
+    auto tile_of = [&](int pos) __attribute__((always_inline)) {
+        if (SPARSE) return TPB * col_idx[sp0 + pos / TPB] + pos % TPB;
+        return dir > 0 ? pos : n_kt - 1 - pos;
+    };
     load_tile(K0, V0, tile_of(0));
     if (n_kt > 1) load_tile(K1, V1, tile_of(1));
 
@@ -359,11 +377,30 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
     dim3 grid((uint32_t)blocks), block(kFwdThreads);
     if (causal)
         attn_fwd_kernel<D, true><<<grid, block, 0, stream>>>((const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o,
-                                                             lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale);
+                                                             lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
+                                                             nullptr, nullptr);
     else
         attn_fwd_kernel<D, false><<<grid, block, 0, stream>>>((const bf16*)q, (const bf16*)k, (const bf16*)v,
                                                               (bf16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
-                                                              kv.head, scale);
+                                                              kv.head, scale, nullptr, nullptr);
+    return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
+}
+
+int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, const int* row_ptr,
+                           const int* col_idx, int64_t N, int Hl, int d, float scale, TensorStrides st, void* stream) {
+    const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ;
+    const int64_t blocks = n_qtiles * Hl;
+    if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
+    dim3 grid((uint32_t)blocks), block(kFwdThreads);
+    hipStream_t s = (hipStream_t)stream;
+    if (d == 128)
+        attn_fwd_kernel<128, true, true><<<grid, block, 0, s>>>((const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o,
+                                                                lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head,
+                                                                st.head, scale, row_ptr, col_idx);
+    else
+        attn_fwd_kernel<64, true, true><<<grid, block, 0, s>>>((const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o,
+                                                               lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head,
+                                                               st.head, scale, row_ptr, col_idx);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 

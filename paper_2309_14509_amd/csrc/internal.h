@@ -34,6 +34,10 @@ inline TensorStrides strides_for(int layout, int64_t N, int Hl, int d) {
 int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
                     int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
 
+// Block-sparse causal forward: keys restricted to the 256-key blocks of a CSR pattern (device arrays).
+int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, const int* row_ptr,
+                           const int* col_idx, int64_t N, int Hl, int d, float scale, TensorStrides st, void* stream);
+
 // floats of scratch the backward kernels need (padded row statistics: delta and lse*log2e); N = queries
 int64_t attn_bwd_workspace_floats(int64_t N, int Hl);
 
@@ -41,6 +45,13 @@ int64_t attn_bwd_workspace_floats(int64_t N, int Hl);
 int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
                     const float* lse, void* dq, void* dk, void* dv, float* delta, int64_t N, int64_t Nk, int Hl, int d,
                     float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
+
+// Block-sparse causal backward; row_ptr/col_idx list the block columns of each block row, col_ptr/row_idx
+// the block rows of each block column (device arrays).
+int attn_bwd_sparse_launch(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                           const float* lse, void* dq, void* dk, void* dv, float* delta, const int* row_ptr,
+                           const int* col_idx, const int* col_ptr, const int* row_idx, int64_t N, int Hl, int d,
+                           float scale, TensorStrides st, void* stream);
 
 }  // namespace uly
 #endif

@@ -148,3 +148,24 @@ def test_cross_attention_validation(lib):
     assert g(dk=None) == 1 and g(Nk=0) == 2 and g(Nq=0) == 2 and g(Nq=0, Nk=0) == 0
     assert g(wsb=16) == 6 and g(ws=None) == 6
     assert g(dv=B + 64) == 5
+
+
+def test_sparse_attention_validation(lib):
+    RP, CI, CP, RI = 0xC0000000, 0xC1000000, 0xC2000000, 0xC3000000
+    f = lambda **kw: lib.ulysses_sparse_attn_fwd(*[{**dict(q=A, k=B, v=C_, o=D_, lse=0x7000000, rp=RP, ci=CI, N=600, Hl=2,
+                                                            d=64, scale=0.125, layout=0), **kw}[n]
+                                                   for n in ("q", "k", "v", "o", "lse", "rp", "ci", "N", "Hl", "d", "scale",
+                                                             "layout")], None)
+    assert f(rp=None) == 1 and f(ci=None) == 1 and f(v=None) == 1
+    assert f(N=-1) == 2 and f(d=100) == 3 and f(scale=-1.0) == 3
+    assert f(rp=RP + 2) == 4 and f(q=A + 8) == 4
+    assert f(o=A) == 5 and f(N=0, rp=None, ci=None) == 0
+    assert lib.ulysses_sparse_attn_bwd_workspace_bytes(600, 2, 64) == lib.ulysses_attn_bwd_workspace_bytes(600, 2, 64)
+    g = lambda **kw: lib.ulysses_sparse_attn_bwd(*[{**dict(q=A, k=B, v=C_, o=D_, do=0x70000000, lse=0x7800000,
+                                                            dq=0x80000000, dk=0x90000000, dv=0xA0000000, rp=RP, ci=CI,
+                                                            cp=CP, ri=RI, ws=0xB0000000, wsb=1 << 20, N=600, Hl=2, d=64,
+                                                            scale=0.125, layout=0), **kw}[n]
+                                                   for n in ("q", "k", "v", "o", "do", "lse", "dq", "dk", "dv", "rp", "ci",
+                                                             "cp", "ri", "ws", "wsb", "N", "Hl", "d", "scale", "layout")],
+                                                 None)
+    assert g(cp=None) == 1 and g(ri=None) == 1 and g(wsb=8) == 6 and g(ri=RI + 1) == 4 and g(dq=A) == 5

@@ -1,0 +1,91 @@
+"""GPU parity of block-sparse causal attention (256-token blocks, caller-given pattern) against the fp64
+oracle, through the C ABI.  Same tolerances as dense attention (see test_gpu_attention.py)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as synth
+from _util import f64_of, max_abs, o_within_tolerance, rel_l2, to_gpu_bf16
+
+pytestmark = pytest.mark.gpu
+
+TOL_O, TOL_G, TOL_LSE = 1e-2, 2e-2, 2e-3
+B = 256
+
+
+def _mask(nb, kind, seed):
+    rng = np.random.default_rng(seed)
+    if kind == "full":
+        m = np.ones((nb, nb), bool)
+    elif kind == "diagonal":
+        m = np.eye(nb, dtype=bool)
+    elif kind == "window_global":          # local window of 2 blocks plus the first block column
+        i, j = np.indices((nb, nb))
+        m = (i - j < 2) | (j == 0)
+    else:
+        m = rng.random((nb, nb)) < 0.4
+    m = np.tril(m)
+    np.fill_diagonal(m, True)
+    return m
+
+
+def _check(gpu_lib, N, Hl, d, kind, layout=0, seed=0):
+    scale = 1.0 / np.sqrt(d)
+    q, k, v, do = synth.attention_inputs(N, Hl, d, 500 + N + seed)
+    if layout == 1:
+        q, k, v, do = (np.ascontiguousarray(a.transpose(1, 0, 2)) for a in (q, k, v, do))
+    mask = _mask((N + B - 1) // B, kind, N + seed)
+    pat = gpu_lib.SparsePattern(mask)
+    tq, tk, tv, tdo = (to_gpu_bf16(a) for a in (q, k, v, do))
+    o, lse = gpu_lib.ulysses_sparse_attn_fwd(tq, tk, tv, pat, scale, layout)
+    dq, dk, dv = gpu_lib.ulysses_sparse_attn_bwd(tq, tk, tv, o, tdo, lse, pat, scale, layout)
+    torch.cuda.synchronize()
+    fq, fk, fv, fdo = (oracle.bf16_to_f64(a) for a in (q, k, v, do))
+    o_ref, lse_ref = oracle.sparse_attn_fwd(fq, fk, fv, mask, B, scale, layout)
+    o_abs, _ = oracle.sparse_attn_fwd(fq, fk, np.abs(fv), mask, B, scale, layout)
+    ok, worst, n_bad = o_within_tolerance(f64_of(o), o_ref, o_abs, TOL_O)
+    assert ok, (worst, n_bad)
+    assert max_abs(f64_of(lse), lse_ref) <= TOL_LSE
+    refs = oracle.sparse_attn_bwd(fq, fk, fv, fdo, mask, B, scale, layout)
+    for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
+        err = rel_l2(f64_of(got), ref)
+        assert err <= TOL_G, (name, err)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("N", [1, 200, 256, 257, 700, 1024, 1300, 2300])
+@pytest.mark.parametrize("kind", ["random", "window_global"])
+def test_sparse_parity(gpu_lib, N, d, kind):
+    _check(gpu_lib, N, 2, d, kind)
+
+
+@pytest.mark.parametrize("kind", ["full", "diagonal"])
+def test_extreme_patterns(gpu_lib, kind):
+    """Every lower-triangular block (= dense causal attention) and diagonal blocks only (= block-local)."""
+    _check(gpu_lib, 1500, 2, 128, kind)
+
+
+def test_head_major_and_odd_heads(gpu_lib):
+    _check(gpu_lib, 1100, 3, 128, "random", layout=1, seed=3)
+
+
+def test_full_pattern_agrees_with_the_dense_kernels(gpu_lib):
+    N, Hl, d = 1280, 2, 128
+    q, k, v, do = synth.attention_inputs(N, Hl, d, 9)
+    tq, tk, tv, tdo = (to_gpu_bf16(a) for a in (q, k, v, do))
+    pat = gpu_lib.SparsePattern(np.ones((5, 5), bool))
+    o, lse = gpu_lib.ulysses_sparse_attn_fwd(tq, tk, tv, pat, 0.09)
+    o2, lse2 = gpu_lib.ulysses_attn_fwd(tq, tk, tv, 0.09, True)
+    assert torch.equal(o, o2) and torch.equal(lse, lse2)          # same tiles in the same order
+    for a, b in zip(gpu_lib.ulysses_sparse_attn_bwd(tq, tk, tv, o, tdo, lse, pat, 0.09),
+                    gpu_lib.ulysses_attn_bwd(tq, tk, tv, o, tdo, lse, 0.09, True)):
+        assert rel_l2(f64_of(a), f64_of(b)) <= 5e-3               # same terms, summed in another order
+
+
+def test_pattern_is_checked_on_the_host(gpu_lib):
+    with pytest.raises(ValueError):
+        gpu_lib.SparsePattern(np.array([[1, 0], [1, 0]]))
+    z = torch.zeros((300, 1, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(ValueError):
+        gpu_lib.ulysses_sparse_attn_fwd(z, z.clone(), z.clone(), gpu_lib.SparsePattern(np.eye(3)), 0.1)
