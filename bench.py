@@ -39,6 +39,9 @@ def main() -> int:
     ap.add_argument("--config", default="gpt7b", help="workload name from synth_inputs.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-rows", type=int, default=640, help="query rows the CPU oracle is timed on")
+    ap.add_argument("--sparse-window", type=int, default=0,
+                    help="also time block-sparse attention: local window of this many 256-token blocks plus the "
+                         "first block column (0 = off; extra 'sparse' object in the output)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU's share only (no collectives, no second GPU); "
@@ -166,6 +169,37 @@ def main() -> int:
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dkv_tflops / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": DKV_TRAFFIC_BYTES.get(args.config)},
     }
+
+    # ---- optional: block-sparse causal attention on the same tensors ---------------------------
+    if args.sparse_window > 0:
+        nb = (N + uly.SPARSE_BLOCK - 1) // uly.SPARSE_BLOCK
+        bi, bj = np.indices((nb, nb))
+        pat = uly.SparsePattern((bi - bj < args.sparse_window) | (bj == 0))
+        pd = pat.dev
+
+        def sparse_step():
+            uly._check(lib.ulysses_sparse_attn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse),
+                                                   ptr(pd["row_ptr"]), ptr(pd["col_idx"]), N, Hl, d, scale,
+                                                   uly.LAYOUT_SEQ_HEAD, sp), "sparse_attn_fwd")
+            uly._check(lib.ulysses_sparse_attn_bwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(dout), ptr(lse),
+                                                   ptr(grads[0]), ptr(grads[1]), ptr(grads[2]), ptr(pd["row_ptr"]),
+                                                   ptr(pd["col_idx"]), ptr(pd["col_ptr"]), ptr(pd["row_idx"]), ptr(ws),
+                                                   ws.numel(), N, Hl, d, scale, uly.LAYOUT_SEQ_HEAD, sp),
+                       "sparse_attn_bwd")
+        sparse_step()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            sparse_step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        sp_ms = e0.elapsed_time(e1) / args.steps
+        # visible (query, key) pairs: full blocks count 256*256, diagonal blocks 256*257/2 (N a multiple of 256 here)
+        Bk = uly.SPARSE_BLOCK
+        pairs = (pat.nnz - nb) * Bk * Bk + nb * Bk * (Bk + 1) // 2
+        result["sparse"] = {"pattern": f"window of {args.sparse_window} blocks of {Bk} tokens + first block column",
+                            "blocks": pat.nnz, "of_lower_triangle": pat.nnz / (nb * (nb + 1) / 2),
+                            "ms_fwd_bwd": sp_ms, "tflops": 14.0 * pairs * d * Hl / (sp_ms * 1e-3) / 1e12}
 
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
     if not args.no_cpu_baseline:
