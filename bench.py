@@ -26,9 +26,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 # HBM-side bytes per launch of the dK/dV kernel, from the committed rocprofv3 counter runs of this
-# same command (profiles/bench_gpt7b_kernels.md): FETCH_SIZE 1.029e7 KiB x 2.0 + WRITE_SIZE 2.622e5 KiB.
+# same command (profiles/bench_gpt7b_kernels.md): FETCH_SIZE 2.755e6 KiB x 2.0 + WRITE_SIZE 2.63e5 KiB
+# (the fetch figure varies between runs, 5 - 20 GiB: it depends on how well the workgroups stay in step).
 # Counters cannot be read from inside this script, so the figure is only reported for that workload.
-DKV_TRAFFIC_BYTES = {"gpt7b": (1.029e7 * 2.0 + 2.622e5) * 1024}
+DKV_TRAFFIC_BYTES = {"gpt7b": (2.755e6 * 2.0 + 2.63e5) * 1024}
 
 
 def main() -> int:
