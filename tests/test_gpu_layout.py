@@ -71,6 +71,38 @@ def test_other_element_sizes(gpu_lib, elem):
     assert torch.equal(gpu_lib.ulysses_unpack_rev(got.cuda()).cpu(), x)
 
 
+# nl, H, d, P: shapes whose contiguous run is one element of 2 / 4 / 8 bytes (bf16-sized payloads), which go
+# through the LDS-staged transpose; several row tiles, ragged ends, more than 64 groups
+SHORT_RUNS = [(5000, 8, 1, 8), (333, 130, 1, 130), (4097, 6, 2, 6), (1300, 12, 4, 12), (70, 2, 1, 2), (9000, 70, 1, 70)]
+
+
+@pytest.mark.parametrize("nl,H,d,P", SHORT_RUNS)
+def test_short_runs_bit_exact(gpu_lib, nl, H, d, P):
+    x = synth.bits_u16((nl, H, d), 5, synth.TID_X)
+    ref = oracle.pack(x, P)
+    got = gpu_lib.ulysses_pack(to_gpu_u16(x), P)
+    assert np.array_equal(bits_of(got), ref)
+    assert np.array_equal(bits_of(gpu_lib.ulysses_unpack_rev(got)), x)
+
+
+@pytest.mark.parametrize("N,Hl,d", [(3000, 5, 1), (1025, 80, 2), (513, 3, 4), (100, 2, 1)])
+def test_head_major_short_runs_bit_exact(gpu_lib, N, Hl, d):
+    """[N, Hl, d] <-> [Hl, N, d] with d of 1, 2 or 4 elements: runs of 2 to 8 bytes."""
+    r = synth.bits_u16((1, N, Hl, d), 6, synth.TID_R)
+    ref = oracle.unpack(r, 1)
+    got = gpu_lib.ulysses_unpack(to_gpu_u16(r), 1)
+    assert np.array_equal(bits_of(got), ref)
+    assert np.array_equal(bits_of(gpu_lib.ulysses_pack_rev(got, 1, 1)), r)
+
+
+def test_single_byte_runs(gpu_lib):
+    g = torch.Generator().manual_seed(9)
+    x = torch.randint(0, 255, (7001, 9, 1), generator=g, dtype=torch.int32).to(torch.uint8)
+    got = gpu_lib.ulysses_pack(x.cuda(), 9).cpu()
+    assert torch.equal(got, x.reshape(7001, 9, 1, 1).permute(1, 0, 2, 3))
+    assert torch.equal(gpu_lib.ulysses_unpack_rev(got.cuda()).cpu(), x)
+
+
 def test_empty_input_is_a_no_op(gpu_lib):
     x = torch.empty((0, 8, 64), dtype=torch.int16, device="cuda")
     assert gpu_lib.ulysses_pack(x, 4).shape == (4, 0, 2, 64)
