@@ -171,6 +171,23 @@ def main() -> int:
                      "traffic": DKV_TRAFFIC_BYTES.get(args.config)},
     }
 
+    # ---- the matrix rate the device sustains with nothing but MFMAs on the same kind of data -----
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    probe_iters = 20000
+    sink = torch.empty(n_cu * 256, dtype=torch.float32, device="cuda")
+    probe_args = (ptr(qkv[0]), 65536, ptr(sink), sink.numel() * 4, n_cu, probe_iters, sp)
+    uly._check(lib.ulysses_probe_mfma(*probe_args), "probe_mfma")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(3):
+        uly._check(lib.ulysses_probe_mfma(*probe_args), "probe_mfma")
+    e1.record(stream)
+    torch.cuda.synchronize()
+    probe_tflops = 3 * n_cu * 4 * probe_iters * 8 * 2.0 * 32 * 32 * 16 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    result["mfma_only_tflops"] = probe_tflops
+    result["roofline"]["frac_of_mfma_only_loop"] = dkv_tflops / probe_tflops
+    result["attn_frac_of_mfma_only_loop"] = result["attn_fwd_bwd_tflops"] / probe_tflops
+
     # ---- optional: block-sparse causal attention on the same tensors ---------------------------
     if args.sparse_window > 0:
         nb = (N + uly.SPARSE_BLOCK - 1) // uly.SPARSE_BLOCK

@@ -177,6 +177,16 @@ int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const v
                             void* workspace, size_t workspace_bytes,
                             int64_t N, int Hl, int d, float scale, int layout, void* stream);
 
+/* Measurement aid for benchmarks (no paper counterpart): launches `blocks` workgroups (one per CU is
+ * the intended use: blocks = number of CUs) of 4 waves that issue iters x 8 bf16 32x32x16 MFMAs each
+ * and nothing else; 2 * 32*32*16 FLOP per MFMA.  Timed by the caller, it gives the matrix rate the
+ * device sustains under its power limit on the data in `data`.
+ *   data: device buffer of at least 65536 bytes, read as bf16 operands (fill it like real data);
+ *   sink: device buffer of at least blocks * 256 floats (written only in a practically impossible case).
+ * ULY_ERR_WORKSPACE if a buffer is too small. */
+int ulysses_probe_mfma(const void* data, size_t data_bytes, float* sink, size_t sink_bytes,
+                       int blocks, int iters, void* stream);
+
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* ulysses_status_string(int status);
 

@@ -20,6 +20,7 @@ EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack
            "ulysses_pack_qkv", "ulysses_unpack_qkv",
            "ulysses_xattn_fwd", "ulysses_xattn_bwd_workspace_bytes", "ulysses_xattn_bwd",
            "ulysses_sparse_attn_fwd", "ulysses_sparse_attn_bwd_workspace_bytes", "ulysses_sparse_attn_bwd",
+           "ulysses_probe_mfma",
            "ulysses_attn_fwd", "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd", "ulysses_attn_bwd_stage",
            "ulysses_status_string", "ulysses_abi_version")
 
@@ -63,6 +64,8 @@ def load(path: str | None = None):
     lib.ulysses_sparse_attn_bwd_workspace_bytes.argtypes = [i64, ci, ci]
     lib.ulysses_sparse_attn_bwd_workspace_bytes.restype = sz
     lib.ulysses_sparse_attn_bwd.argtypes = [vp] * 14 + [sz, i64, ci, ci, cf, ci, vp]
+    lib.ulysses_probe_mfma.argtypes = [vp, sz, vp, sz, ci, ci, vp]
+    lib.ulysses_probe_mfma.restype = ci
     lib.ulysses_status_string.argtypes = [ci]
     lib.ulysses_status_string.restype = ctypes.c_char_p
     for name in ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",

@@ -276,6 +276,15 @@ int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const v
                                        row_idx, N, Hl, d, scale, uly::strides_for(layout, N, Hl, d), stream);
 }
 
+int ulysses_probe_mfma(const void* data, size_t data_bytes, float* sink, size_t sink_bytes, int blocks, int iters,
+                       void* stream) {
+    if (blocks <= 0 || iters <= 0 || blocks > 65536) return ULY_ERR_SHAPE;
+    if (!data || !sink) return ULY_ERR_NULL;
+    if (misaligned(data) || misaligned(sink)) return ULY_ERR_ALIGN;
+    if (data_bytes < uly::kProbeBytes || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return ULY_ERR_WORKSPACE;
+    return uly::mfma_probe_launch(data, sink, blocks, iters, stream);
+}
+
 const char* ulysses_status_string(int status) {
     switch (status) {
         case ULY_OK: return "ok";

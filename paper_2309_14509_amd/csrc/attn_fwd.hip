@@ -386,6 +386,43 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 
+// ------------------------------------------------------------------------------------------
+// Measurement aid: nothing but bf16 MFMAs (four independent accumulation chains per wave, one wave
+// per SIMD, operands taken from a caller-filled buffer so that they toggle like real data).  What
+// this sustains is the matrix rate the part actually allows under its power limit; the attention
+// kernels are quoted against it next to the published peak.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 1) void mfma_probe_kernel(const bf16* __restrict__ data, float* __restrict__ sink,
+                                                            int iters) {
+    __shared__ float pad[24 * 1024];                 // 96 KiB: one workgroup per CU
+    if (iters < 0) pad[threadIdx.x] = 0.f;
+    bf16x8 a[8], b[8];
+    const bf16x8* src = reinterpret_cast<const bf16x8*>(data);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) { a[t] = src[threadIdx.x + 512 * t]; b[t] = src[threadIdx.x + 512 * t + 256]; }
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t & 3] = mfma32(a[t], b[t], acc[t & 3]);
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tot += acc[i][r];
+    if (tot == 12345.678f) sink[blockIdx.x * 256 + threadIdx.x] = tot + pad[0];   // keeps the loop alive; practically never true
+}
+
+// data: at least kProbeBytes of device memory filled by the caller; sink: at least blocks*256 floats
+int mfma_probe_launch(const void* data, float* sink, int blocks, int iters, void* stream) {
+    mfma_probe_kernel<<<dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream>>>((const bf16*)data, sink, iters);
+    return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
+}
+
 int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, const int* row_ptr,
                            const int* col_idx, int64_t N, int Hl, int d, float scale, TensorStrides st, void* stream) {
     const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ;

@@ -34,6 +34,10 @@ inline TensorStrides strides_for(int layout, int64_t N, int Hl, int d) {
 int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
                     int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
 
+// MFMA-only probe (measurement aid): `blocks` workgroups of 256 lanes, `iters` x 8 MFMAs per wave.
+constexpr size_t kProbeBytes = 64 * 1024;        // operand bytes read from `data`
+int mfma_probe_launch(const void* data, float* sink, int blocks, int iters, void* stream);
+
 // Block-sparse causal forward: keys restricted to the 256-key blocks of a CSR pattern (device arrays).
 int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, const int* row_ptr,
                            const int* col_idx, int64_t N, int Hl, int d, float scale, TensorStrides st, void* stream);

@@ -169,3 +169,12 @@ def test_sparse_attention_validation(lib):
                                                              "cp", "ri", "ws", "wsb", "N", "Hl", "d", "scale", "layout")],
                                                  None)
     assert g(cp=None) == 1 and g(ri=None) == 1 and g(wsb=8) == 6 and g(ri=RI + 1) == 4 and g(dq=A) == 5
+
+
+def test_probe_validation(lib):
+    ok = dict(data=A, db=65536, sink=B, sb=256 * 256 * 4, blocks=256, iters=10)
+    f = lambda **kw: lib.ulysses_probe_mfma(*[{**ok, **kw}[n] for n in ("data", "db", "sink", "sb", "blocks", "iters")], None)
+    assert f(data=None) == 1 and f(sink=None) == 1
+    assert f(blocks=0) == 2 and f(iters=0) == 2 and f(blocks=1 << 20) == 2
+    assert f(data=A + 4) == 4
+    assert f(db=1000) == 6 and f(sb=1024) == 6
