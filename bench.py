@@ -194,16 +194,21 @@ def main() -> int:
         bi, bj = np.indices((nb, nb))
         pat = uly.SparsePattern((bi - bj < args.sparse_window) | (bj == 0))
         pd = pat.dev
+        sws = torch.empty(int(lib.ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d)), dtype=torch.uint8, device="cuda")
+        sp_ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
         def sparse_step():
+            sp_ev[0].record(stream)
             uly._check(lib.ulysses_sparse_attn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse),
                                                    ptr(pd["row_ptr"]), ptr(pd["col_idx"]), N, Hl, d, scale,
                                                    uly.LAYOUT_SEQ_HEAD, sp), "sparse_attn_fwd")
+            sp_ev[1].record(stream)
             uly._check(lib.ulysses_sparse_attn_bwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(dout), ptr(lse),
                                                    ptr(grads[0]), ptr(grads[1]), ptr(grads[2]), ptr(pd["row_ptr"]),
-                                                   ptr(pd["col_idx"]), ptr(pd["col_ptr"]), ptr(pd["row_idx"]), ptr(ws),
-                                                   ws.numel(), N, Hl, d, scale, uly.LAYOUT_SEQ_HEAD, sp),
+                                                   ptr(pd["col_idx"]), ptr(pd["col_ptr"]), ptr(pd["row_idx"]), ptr(sws),
+                                                   sws.numel(), N, Hl, d, scale, uly.LAYOUT_SEQ_HEAD, sp),
                        "sparse_attn_bwd")
+            sp_ev[2].record(stream)
         sparse_step()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
@@ -217,7 +222,8 @@ def main() -> int:
         pairs = (pat.nnz - nb) * Bk * Bk + nb * Bk * (Bk + 1) // 2
         result["sparse"] = {"pattern": f"window of {args.sparse_window} blocks of {Bk} tokens + first block column",
                             "blocks": pat.nnz, "of_lower_triangle": pat.nnz / (nb * (nb + 1) / 2),
-                            "ms_fwd_bwd": sp_ms, "tflops": 14.0 * pairs * d * Hl / (sp_ms * 1e-3) / 1e12}
+                            "ms_fwd_bwd": sp_ms, "ms_fwd_last_step": sp_ev[0].elapsed_time(sp_ev[1]),
+                            "ms_bwd_last_step": sp_ev[1].elapsed_time(sp_ev[2]), "tflops": 14.0 * pairs * d * Hl / (sp_ms * 1e-3) / 1e12}
 
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
     if not args.no_cpu_baseline:

@@ -162,8 +162,13 @@ int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o
  *       by block rows row_idx[col_ptr[c] .. col_ptr[c+1]), strictly ascending, the first one == c.
  * The arrays live in device memory, so the library cannot check their contents: a pattern that
  * breaks these rules is undefined behaviour (the Python binding builds and checks them on the host).
- * Other arguments, precision, workspace and status codes are those of ulysses_attn_fwd / _bwd with
- * causal = 1; the pattern arrays must be non-NULL and 4-byte aligned.
+ * Other arguments, precision and status codes are those of ulysses_attn_fwd / _bwd with causal = 1;
+ * the pattern arrays must be non-NULL and 4-byte aligned.
+ * Workspace of the backward (caller-owned device memory, ulysses_sparse_attn_bwd_workspace_bytes;
+ * 0 for a shape the library rejects): the row statistics of the dense backward, a work plan the
+ * library derives from col_ptr on the device, and fp32 partial sums for block columns so long that
+ * several workgroups share one (at most 2048 slots of 128 keys x d x 2 tensors: 256 MiB at d = 128,
+ * whatever N is).  The sums are added in a fixed order: results are deterministic.
  * ------------------------------------------------------------------------------------------- */
 #define ULY_SPARSE_BLOCK 256
 int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,

@@ -248,7 +248,9 @@ int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o
 }
 
 size_t ulysses_sparse_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
-    return ulysses_attn_bwd_workspace_bytes(N, Hl, d);
+    uint64_t tb;
+    if (check_attn_common(N, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK || N == 0) return 0;
+    return (size_t)uly::attn_bwd_sparse_workspace_floats(N, Hl, d) * sizeof(float);
 }
 
 int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
@@ -262,7 +264,7 @@ int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const v
     if (N == 0) return ULY_OK;
     if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv || !row_ptr || !col_idx || !col_ptr || !row_idx)
         return ULY_ERR_NULL;
-    const size_t need = ulysses_attn_bwd_workspace_bytes(N, Hl, d);
+    const size_t need = ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return ULY_ERR_WORKSPACE;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(dout) || misaligned(lse) ||
         misaligned(dq) || misaligned(dk) || misaligned(dv) || misaligned(workspace))

@@ -399,7 +399,8 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dO,
     const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, bf16* __restrict__ dK,
     bf16* __restrict__ dV, int N, int Nk, int n_ktiles, int64_t row_stride, int64_t head_stride,
-    int64_t kv_head_stride, float scale, const int* __restrict__ col_ptr, const int* __restrict__ row_idx) {
+    int64_t kv_head_stride, float scale, const int* __restrict__ col_ptr, const int* __restrict__ row_idx,
+    const int4* __restrict__ plan, float* __restrict__ partial, int slots_per_head) {
     static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
     constexpr int NT = D / 16, NCB = D / 32;
     constexpr int TILE = kDkvBQ * D;            // elements per tile
@@ -420,9 +421,21 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     // the first tile downwards from the end of the sequence and those of the second upwards from its
     // diagonal: at any moment all workgroups that started together read one of only two query
     // blocks, which keeps the Q/dO stream in the L2 caches instead of re-fetching it per workgroup.
+    // SPARSE: grid (heads, work items); an item of the plan is a key tile and a range of walk
+    // positions of its block column (long columns are cut into several items, see the plan kernel).
     const int n_pairs = (CAUSAL && !SPARSE) ? (n_ktiles + 1) / 2 : n_ktiles;
-    const int head = blockIdx.x / n_pairs;
-    const int pr = blockIdx.x - head * n_pairs;
+    const int head = SPARSE ? blockIdx.x : blockIdx.x / n_pairs;
+    int pr = blockIdx.x - head * n_pairs;
+    int p_off = 0, p_end = 0, slot = -1;
+    if (SPARSE) {
+        const int4 hdr = plan[0];                 // {items, items that write partial sums, ..}
+        if ((int)blockIdx.y >= hdr.x) return;     // the grid is an upper bound on the number of items
+        const int4 it = plan[1 + blockIdx.y];     // {key tile, first walk position, end, -}
+        pr = it.x;
+        p_off = it.y;
+        p_end = it.z;
+        slot = (int)blockIdx.y < hdr.y ? (int)blockIdx.y : -1;
+    }
     const int64_t hoff = (int64_t)head * head_stride;
     const bf16* Qh = Q + hoff;
     const bf16* dOh = dO + hoff;
@@ -506,10 +519,12 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     }
     // block at walk position p; positions past the end re-read the last one (their tiles are never used)
     auto blk = [&](int p) __attribute__((always_inline)) {
+        if (SPARSE) p += p_off;
         p = p < cnt ? p : cnt - 1;
         if (SPARSE) return p < n_diag ? b0 + p : BPS * row_idx[sp0 + 1 + (p - n_diag) / BPS] + (p - n_diag) % BPS;
         return dir > 0 ? b0 + p : nblk4 - 1 - p;
     };
+    const int walk = SPARSE ? p_end - p_off : cnt;            // positions this workgroup processes
 #pragma unroll
     for (int i = 0; i < kDkvRing; ++i) load_tile(i, blk(i));
 
@@ -757,7 +772,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         iteration(Masked{}, S3{}, S0{}, S1{}, 3); settle();
         p = 4;
     }
-    const int plain_end = (CAUSAL && dir < 0) ? cnt - 4 : cnt;
+    const int plain_end = (CAUSAL && dir < 0) ? walk - 4 : walk;
     for (; p < plain_end; p += 4) {
         iteration(Plain{}, S0{}, S1{}, S2{}, p);
         iteration(Plain{}, S1{}, S2{}, S3{}, p + 1);
@@ -779,7 +794,23 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     for (int cb = 0; cb < NCB; ++cb) lds_tie(dk_acc[cb], dv_acc[cb]);
     __builtin_amdgcn_sched_barrier(0);
 
-    if (j_col < Nk) {
+    if (SPARSE && slot >= 0) {
+        // one of several items of this key tile: fp32 partial sums [slot][dK, dV][key][channel]
+        float* prow = partial + ((int64_t)head * slots_per_head + slot) * (2 * kDkvBK * D) + (wave * 32 + ln) * D;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                f32x4 wk, wv;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    wk[e] = dk_acc[cb][4 * rq + e] * scale;
+                    wv[e] = dv_acc[cb][4 * rq + e];
+                }
+                *reinterpret_cast<f32x4*>(prow + 32 * cb + 8 * rq + 4 * g) = wk;
+                *reinterpret_cast<f32x4*>(prow + kDkvBK * D + 32 * cb + 8 * rq + 4 * g) = wv;
+            }
+    } else if (j_col < Nk) {
         bf16* krow = dK + kv_hoff + (int64_t)j_col * row_stride;
         bf16* vrow = dV + kv_hoff + (int64_t)j_col * row_stride;
 #pragma unroll
@@ -800,8 +831,161 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     }   // key tiles of this workgroup
 }
 
+// ------------------------------------------------------------------------------------------
+// Work plan of the block-sparse dK/dV kernel.  A key tile's walk has cnt query blocks (a multiple
+// of 4), anything from 4 to the whole sequence: one workgroup per key tile would leave the launch
+// waiting for the few longest block columns.  Columns longer than L blocks are therefore cut into
+// items of at most L blocks (a multiple of 4); the workgroups of a cut column write fp32 partial
+// sums, which the reduce kernel adds in a fixed order.  L = max(kPlanMinLen, total work / kPlanTarget)
+// so that no item exceeds a small part of one CU's share, and the number of partial-sum slots is
+// bounded independently of N:  sum over cut columns of ceil(cnt / L) <= 2 * total / L <= 2 * kPlanTarget / Hl.
+//   plan[0] = {items, cut items, L, 0};  plan[1 + s] = {key tile, first position, end position, 0};
+//   cut items come first (s = slot of their partial sums);  red[ktile] = {first slot, items} (items 1: not cut).
+// One workgroup; every thread scans a contiguous range of key tiles.
+// ------------------------------------------------------------------------------------------
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanTarget = 1024;   // items the cut columns are aimed at, over all heads
+constexpr int kPlanMinLen = 32;     // query blocks; below this the per-item overhead would show
+
+inline int plan_slots_per_head(int64_t n_ktiles, int64_t nblk4, int Hl) {
+    const int64_t by_target = 2 * ((kPlanTarget + Hl - 1) / Hl);
+    const int64_t by_size = 2 * (n_ktiles * nblk4 / kPlanMinLen) + 1;      // total <= n_ktiles * nblk4
+    return (int)(by_target < by_size ? by_target : by_size);
+}
+inline int64_t plan_items_bound(int64_t n_ktiles, int Hl) { return n_ktiles + (kPlanTarget + Hl - 1) / Hl + 1; }
+
+__device__ __forceinline__ int block_scan_exclusive(int v, int* sh, int* total) {
+    const int tid = threadIdx.x;
+    sh[tid] = v;
+    __syncthreads();
+    for (int off = 1; off < kPlanThreads; off <<= 1) {
+        const int add = tid >= off ? sh[tid - off] : 0;
+        __syncthreads();
+        sh[tid] += add;
+        __syncthreads();
+    }
+    const int incl = sh[tid];
+    *total = sh[kPlanThreads - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void sparse_dkv_plan_kernel(const int* __restrict__ col_ptr, int n_ktiles,
+                                                                       int Hl, int slots_per_head,
+                                                                       int4* __restrict__ plan, int2* __restrict__ red) {
+    __shared__ int sh[kPlanThreads];
+    __shared__ unsigned long long sh_total;
+    constexpr int BPS = kSparseBlockBwd / kDkvBQ, TPB = kSparseBlockBwd / kDkvBK;
+    const int tid = threadIdx.x;
+    const int chunk = (n_ktiles + kPlanThreads - 1) / kPlanThreads;
+    const int k0 = tid * chunk < n_ktiles ? tid * chunk : n_ktiles;
+    const int k1 = k0 + chunk < n_ktiles ? k0 + chunk : n_ktiles;
+    auto count = [&](int kt) {
+        const int bcol = kt / TPB;
+        return (bcol + 1) * BPS - kt * (kDkvBK / kDkvBQ) + BPS * (col_ptr[bcol + 1] - col_ptr[bcol] - 1);
+    };
+    if (tid == 0) sh_total = 0;
+    __syncthreads();
+    unsigned long long mine = 0;
+    for (int kt = k0; kt < k1; ++kt) mine += (unsigned long long)count(kt);
+    atomicAdd(&sh_total, mine);
+    __syncthreads();
+    const unsigned long long want = (sh_total * (unsigned long long)Hl + kPlanTarget - 1) / kPlanTarget;
+    int L = want > 0x3FFFFFFFull ? 0x3FFFFFFF : (int)want;
+    L = (L + 3) & ~3;
+    L = L < kPlanMinLen ? kPlanMinLen : L;
+    // items of a column of cnt blocks: pieces of len blocks
+    auto piece_len = [&](int cnt) {
+        const int n = (cnt + L - 1) / L;
+        return (((cnt + n - 1) / n) + 3) & ~3;
+    };
+    int n_cut = 0, n_whole = 0, cut_total = 0, whole_total = 0, cut_at = 0, whole_at = 0;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        n_cut = n_whole = 0;
+        for (int kt = k0; kt < k1; ++kt) {
+            const int cnt = count(kt);
+            if (cnt > L) n_cut += (cnt + piece_len(cnt) - 1) / piece_len(cnt);
+            else ++n_whole;
+        }
+        cut_at = block_scan_exclusive(n_cut, sh, &cut_total);
+        whole_at = block_scan_exclusive(n_whole, sh, &whole_total);
+        if (cut_total <= slots_per_head) break;
+        L = 0x3FFFFFFC;                         // cannot happen by the bound above; then nothing is cut
+    }
+    if (tid == 0) plan[0] = make_int4(cut_total + whole_total, cut_total, L, 0);
+    int cs = cut_at, ws = cut_total + whole_at;
+    for (int kt = k0; kt < k1; ++kt) {
+        const int cnt = count(kt);
+        if (cnt > L) {
+            const int len = piece_len(cnt), n = (cnt + len - 1) / len;
+            red[kt] = make_int2(cs, n);
+            for (int i = 0; i < n; ++i, ++cs)
+                plan[1 + cs] = make_int4(kt, i * len, (i + 1) * len < cnt ? (i + 1) * len : cnt, 0);
+        } else {
+            red[kt] = make_int2(-1, 1);
+            plan[1 + ws] = make_int4(kt, 0, cnt, 0);
+            ++ws;
+        }
+    }
+}
+
+// Adds the partial sums of the cut block columns (fixed order: deterministic) and writes dK, dV.
+// Grid (any, heads): the workgroups of a head share out (cut item, 1024-float chunk) tasks; the task of
+// a column's first item does the column, the others are skipped.
+constexpr int kReduceBlocks = 256;
+template <int D>
+__global__ __launch_bounds__(256) void sparse_dkv_reduce_kernel(const int4* __restrict__ plan,
+                                                                const int2* __restrict__ red,
+                                                                const float* __restrict__ partial, int slots_per_head,
+                                                                bf16* __restrict__ dK, bf16* __restrict__ dV, int Nk,
+                                                                int64_t row_stride, int64_t kv_head_stride) {
+    constexpr int PER = kDkvBK * D;                       // floats per tensor and slot
+    constexpr int CH = 2 * PER / 1024;                    // chunks per slot
+    const int head = blockIdx.y;
+    const int n_cut = plan[0].y;
+    for (int t = blockIdx.x; t < n_cut * CH; t += gridDim.x) {
+        const int s = t / CH, e = (t % CH) * 1024 + threadIdx.x * 4;
+        const int4 it = plan[1 + s];
+        if (it.y != 0) continue;                          // not the first item of its column
+        const int kt = it.x, n = red[kt].y;
+        const float* base = partial + ((int64_t)head * slots_per_head + s) * (2 * PER) + e;
+        f32x4 acc = *reinterpret_cast<const f32x4*>(base);
+#pragma unroll 4
+        for (int i = 1; i < n; ++i) acc += *reinterpret_cast<const f32x4*>(base + (int64_t)i * (2 * PER));
+        const int which = e / PER, key = (e % PER) / D, ch = e % D;
+        const int j = kt * kDkvBK + key;
+        if (j >= Nk) continue;
+        bf16x4 w;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) w[c] = (bf16)acc[c];
+        bf16* dst = (which ? dV : dK) + (int64_t)head * kv_head_stride + (int64_t)j * row_stride + ch;
+        *reinterpret_cast<bf16x4*>(dst) = w;
+    }
+}
+
 // padded row stride of the statistics arrays in the workspace
 inline int64_t stats_stride(int64_t N) { return ((N + 255) / 256) * 256 + 64; }   // covers whole sparse blocks
+
+// Workspace of the block-sparse backward, in floats from its start: the two statistics arrays, the
+// dK/dV work plan, the per-key-tile reduce table, the partial sums (each section 256-byte aligned).
+struct SparseWorkspace {
+    int64_t plan_at, red_at, partial_at, total;
+    int64_t items_bound;
+    int slots_per_head;
+};
+inline SparseWorkspace sparse_workspace(int64_t N, int Hl, int d) {
+    const int64_t n_ktiles = (N + kDkvBK - 1) / kDkvBK;
+    const int64_t nblk4 = (((N + kDkvBQ - 1) / kDkvBQ) + 3) & ~(int64_t)3;
+    auto up = [](int64_t x) { return (x + 63) & ~(int64_t)63; };
+    SparseWorkspace w;
+    w.items_bound = plan_items_bound(n_ktiles, Hl);
+    w.slots_per_head = plan_slots_per_head(n_ktiles, nblk4, Hl);
+    w.plan_at = up(2 * stats_stride(N) * Hl);
+    w.red_at = up(w.plan_at + 4 * (1 + w.items_bound));
+    w.partial_at = up(w.red_at + 2 * n_ktiles);
+    w.total = w.partial_at + (int64_t)w.slots_per_head * Hl * 2 * kDkvBK * d;
+    return w;
+}
 
 template <int D>
 static int launch_bwd(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
@@ -827,11 +1011,11 @@ static int launch_bwd(int stage_mask, const void* q, const void* k, const void* 
         if (causal)
             attn_bwd_dkv_kernel<D, true><<<gkv, dim3(kDkvThreads), 0, stream>>>(
                 Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
-                kv.head, scale, nullptr, nullptr);
+                kv.head, scale, nullptr, nullptr, nullptr, nullptr, 0);
         else
             attn_bwd_dkv_kernel<D, false><<<gkv, dim3(kDkvThreads), 0, stream>>>(
                 Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
-                kv.head, scale, nullptr, nullptr);
+                kv.head, scale, nullptr, nullptr, nullptr, nullptr, 0);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     if (stage_mask & 4) {
@@ -864,9 +1048,21 @@ static int launch_bwd_sparse(const void* q, const void* k, const void* v, const 
     attn_bwd_delta_kernel<D><<<dim3((uint32_t)delta_blocks), dim3(256), 0, stream>>>(
         (const bf16*)o, dO, lse, delta, lse2, (int)N, Hl, stride, st.row, st.head);
     if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
-    attn_bwd_dkv_kernel<D, true, true><<<dim3((uint32_t)(n_ktiles * Hl)), dim3(kDkvThreads), 0, stream>>>(
+    // work plan, then the items, then the sums of the cut columns
+    const SparseWorkspace w = sparse_workspace(N, Hl, D);
+    if (w.items_bound > 65535 || Hl > 65535) return ULY_ERR_SHAPE;      // grid y dimensions
+    int4* plan = reinterpret_cast<int4*>(ws + w.plan_at);
+    int2* red = reinterpret_cast<int2*>(ws + w.red_at);
+    float* partial = ws + w.partial_at;
+    sparse_dkv_plan_kernel<<<dim3(1), dim3(kPlanThreads), 0, stream>>>(col_ptr, (int)n_ktiles, Hl, w.slots_per_head, plan,
+                                                                      red);
+    if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+    attn_bwd_dkv_kernel<D, true, true><<<dim3((uint32_t)Hl, (uint32_t)w.items_bound), dim3(kDkvThreads), 0, stream>>>(
         Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)N, (int)n_ktiles, st.row, st.head, st.head,
-        scale, col_ptr, row_idx);
+        scale, col_ptr, row_idx, plan, partial, w.slots_per_head);
+    if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+    sparse_dkv_reduce_kernel<D><<<dim3(kReduceBlocks, (uint32_t)Hl), dim3(256), 0, stream>>>(
+        plan, red, partial, w.slots_per_head, (bf16*)dk, (bf16*)dv, (int)N, st.row, st.head);
     if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     attn_bwd_dq_kernel<D, true, true><<<dim3((uint32_t)(n_qtiles * Hl)), dim3(kDqThreads), 0, stream>>>(
         Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)N, (int)n_qtiles, st.row, st.head, st.head, scale,
@@ -886,6 +1082,7 @@ int attn_bwd_sparse_launch(const void* q, const void* k, const void* v, const vo
 }
 
 int64_t attn_bwd_workspace_floats(int64_t N, int Hl) { return 2 * stats_stride(N) * Hl; }
+int64_t attn_bwd_sparse_workspace_floats(int64_t N, int Hl, int d) { return sparse_workspace(N, Hl, d).total; }
 
 int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
                     const float* lse, void* dq, void* dk, void* dv, float* ws, int64_t N, int64_t Nk, int Hl, int d,

@@ -50,6 +50,10 @@ int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v,
                     const float* lse, void* dq, void* dk, void* dv, float* delta, int64_t N, int64_t Nk, int Hl, int d,
                     float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
 
+// floats of scratch of the block-sparse backward: the statistics, the dK/dV work plan and the fp32
+// partial sums of block columns that are cut into several work items
+int64_t attn_bwd_sparse_workspace_floats(int64_t N, int Hl, int d);
+
 // Block-sparse causal backward; row_ptr/col_idx list the block columns of each block row, col_ptr/row_idx
 // the block rows of each block column (device arrays).
 int attn_bwd_sparse_launch(const void* q, const void* k, const void* v, const void* o, const void* dout,

@@ -160,7 +160,12 @@ def test_sparse_attention_validation(lib):
     assert f(N=-1) == 2 and f(d=100) == 3 and f(scale=-1.0) == 3
     assert f(rp=RP + 2) == 4 and f(q=A + 8) == 4
     assert f(o=A) == 5 and f(N=0, rp=None, ci=None) == 0
-    assert lib.ulysses_sparse_attn_bwd_workspace_bytes(600, 2, 64) == lib.ulysses_attn_bwd_workspace_bytes(600, 2, 64)
+    # statistics as for the dense backward, plus a work plan and a bounded number of fp32 partial-sum slots
+    assert lib.ulysses_sparse_attn_bwd_workspace_bytes(600, 2, 64) > lib.ulysses_attn_bwd_workspace_bytes(600, 2, 64)
+    big, slot = lib.ulysses_sparse_attn_bwd_workspace_bytes(1 << 20, 4, 128), 2 * 128 * 128 * 4
+    assert big - lib.ulysses_attn_bwd_workspace_bytes(1 << 20, 4, 128) <= 2048 * slot + (1 << 20)
+    assert lib.ulysses_sparse_attn_bwd_workspace_bytes(0, 4, 128) == 0
+    assert lib.ulysses_sparse_attn_bwd_workspace_bytes(600, 2, 100) == 0
     g = lambda **kw: lib.ulysses_sparse_attn_bwd(*[{**dict(q=A, k=B, v=C_, o=D_, do=0x70000000, lse=0x7800000,
                                                             dq=0x80000000, dk=0x90000000, dv=0xA0000000, rp=RP, ci=CI,
                                                             cp=CP, ri=RI, ws=0xB0000000, wsb=1 << 20, N=600, Hl=2, d=64,

@@ -66,6 +66,14 @@ def test_extreme_patterns(gpu_lib, kind):
     _check(gpu_lib, 1500, 2, 128, kind)
 
 
+@pytest.mark.parametrize("N,Hl,d,kind", [(6000, 3, 128, "window_global"), (5000, 1, 64, "full"),
+                                         (7700, 2, 128, "random")])
+def test_long_block_columns_are_cut_into_several_work_items(gpu_lib, N, Hl, d, kind):
+    """Block columns of 20 to 31 visible blocks: the dK/dV kernel cuts them into several work items whose
+    fp32 partial sums a second kernel adds; every (query block, key tile) pair must be counted once."""
+    _check(gpu_lib, N, Hl, d, kind, seed=11)
+
+
 def test_head_major_and_odd_heads(gpu_lib):
     _check(gpu_lib, 1100, 3, 128, "random", layout=1, seed=3)
 
