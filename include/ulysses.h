@@ -47,6 +47,14 @@ enum {
     ULY_LAYOUT_HEAD_SEQ = 1  /* [Hl, N, d]  head-major             */
 };
 
+/* Element type of the attention entry points: OR this flag into their `layout` argument when
+ * q, k, v, o, dout, dq, dk, dv hold IEEE fp16 instead of bf16 (lse and the workspace do not
+ * change).  The layout transforms ignore element types (they take elem_bytes) and reject the flag. */
+enum {
+    ULY_ELEM_BF16 = 0,
+    ULY_ELEM_F16 = 0x100
+};
+
 /* ---------------------------------------------------------------------------------------------
  * Layout transforms around the two all-to-alls (Section 3.1; message sizes in Section 3.2).
  * Pure data movement of `elem_bytes`-sized elements (1, 2 or 4); results are bit-exact.
@@ -92,8 +100,10 @@ int ulysses_unpack_rev(const void* recv, void* y, int64_t n_local, int H, int d,
 /* ---------------------------------------------------------------------------------------------
  * Exact softmax attention per local head, Equation 1:  O = Softmax(Q K^T * scale) V,
  * softmax over keys.  causal != 0 restricts query i to keys j <= i (global token positions,
- * diagonal included).  q, k, v, o, dout, dq, dk, dv are bf16 in `layout`; arithmetic is bf16
- * MFMA with fp32 accumulation and fp32 softmax; outputs are rounded to bf16 (nearest even).
+ * diagonal included).  q, k, v, o, dout, dq, dk, dv are bf16 in `layout` (fp16 with
+ * layout | ULY_ELEM_F16; this holds for the cross- and sparse-attention entry points too);
+ * arithmetic is 16-bit MFMA with fp32 accumulation and fp32 softmax; outputs are rounded to the
+ * element type (nearest even).  The paper does not state a precision.
  * N tokens (any N >= 0), Hl local heads, d in {64, 128}.  `scale` is normally 1/sqrt(d) and must
  * be finite and > 0 (anything else is ULY_ERR_UNSUPPORTED).
  * ------------------------------------------------------------------------------------------- */

@@ -183,16 +183,30 @@ def _attn_dims(q, layout):
     return N, Hl, d
 
 
-def ulysses_attn_fwd(q, k, v, scale: float, causal: bool = True, layout: int = LAYOUT_SEQ_HEAD, out=None, lse=None):
-    """bf16 q, k, v in ``layout`` -> (o bf16 in ``layout``, lse fp32 [Hl, N])."""
+ELEM_BF16, ELEM_F16 = 0, 0x100
+
+
+def _elem_flag(*tensors):
+    """The element-type flag the attention entry points take on their layout argument: all tensors
+    bfloat16 -> 0, all float16 -> ELEM_F16."""
     import torch
-    if q.dtype != torch.bfloat16:
-        raise ValueError("attention tensors must be bfloat16")
+    kinds = {t.dtype for t in tensors}
+    if kinds == {torch.bfloat16}:
+        return ELEM_BF16
+    if kinds == {torch.float16}:
+        return ELEM_F16
+    raise ValueError("attention tensors must all be bfloat16 or all be float16")
+
+
+def ulysses_attn_fwd(q, k, v, scale: float, causal: bool = True, layout: int = LAYOUT_SEQ_HEAD, out=None, lse=None):
+    """bf16 (or fp16) q, k, v in ``layout`` -> (o of the same type in ``layout``, lse fp32 [Hl, N])."""
+    import torch
+    elem = _elem_flag(q, k, v)
     N, Hl, d = _attn_dims(q, layout)
     o = torch.empty_like(q) if out is None else out
     lse = torch.empty((Hl, N), dtype=torch.float32, device=q.device) if lse is None else lse
     _check(load().ulysses_attn_fwd(_dev(q, "attn_fwd"), _dev(k, "attn_fwd"), _dev(v, "attn_fwd"), _dev(o, "attn_fwd"),
-                                   _dev(lse, "attn_fwd"), N, Hl, d, scale, int(causal), layout, _stream()),
+                                   _dev(lse, "attn_fwd"), N, Hl, d, scale, int(causal), layout | elem, _stream()),
            "ulysses_attn_fwd")
     return o, lse
 
@@ -209,6 +223,7 @@ def ulysses_attn_bwd(q, k, v, o, dout, lse, scale: float, causal: bool = True, l
     """-> (dq, dk, dv) bf16 in ``layout``.  ``stage`` (one of BWD_STAGE_*) runs a single stage of the
     backward pass through ulysses_attn_bwd_stage; the caller then supplies ``workspace`` and ``out``."""
     import torch
+    elem = _elem_flag(q, k, v, o, dout)
     N, Hl, d = _attn_dims(q, layout)
     need = ulysses_attn_bwd_workspace_bytes(N, Hl, d)
     if workspace is None:
@@ -217,7 +232,7 @@ def ulysses_attn_bwd(q, k, v, o, dout, lse, scale: float, causal: bool = True, l
     args = (_dev(q, "attn_bwd"), _dev(k, "attn_bwd"), _dev(v, "attn_bwd"), _dev(o, "attn_bwd"),
             _dev(dout, "attn_bwd"), _dev(lse, "attn_bwd"), _dev(dq, "attn_bwd"), _dev(dk, "attn_bwd"),
             _dev(dv, "attn_bwd"), _dev(workspace, "attn_bwd"), workspace.numel() * workspace.element_size(),
-            N, Hl, d, scale, int(causal), layout, _stream())
+            N, Hl, d, scale, int(causal), layout | elem, _stream())
     if stage is None:
         _check(load().ulysses_attn_bwd(*args), "ulysses_attn_bwd")
     else:
@@ -228,14 +243,13 @@ def ulysses_attn_bwd(q, k, v, o, dout, lse, scale: float, causal: bool = True, l
 def ulysses_xattn_fwd(q, k, v, scale: float, layout: int = LAYOUT_SEQ_HEAD):
     """Cross-attention, no mask: bf16 q (Nq tokens), k, v (Nk tokens) in ``layout`` -> (o like q, lse fp32 [Hl, Nq])."""
     import torch
-    if q.dtype != torch.bfloat16:
-        raise ValueError("attention tensors must be bfloat16")
+    elem = _elem_flag(q, k, v)
     Nq, Hl, d = _attn_dims(q, layout)
     Nk = _attn_dims(k, layout)[0]
     o = torch.empty_like(q)
     lse = torch.empty((Hl, Nq), dtype=torch.float32, device=q.device)
     _check(load().ulysses_xattn_fwd(_dev(q, "xattn_fwd"), _dev(k, "xattn_fwd"), _dev(v, "xattn_fwd"),
-                                    _dev(o, "xattn_fwd"), _dev(lse, "xattn_fwd"), Nq, Nk, Hl, d, scale, layout,
+                                    _dev(o, "xattn_fwd"), _dev(lse, "xattn_fwd"), Nq, Nk, Hl, d, scale, layout | elem,
                                     _stream()), "ulysses_xattn_fwd")
     return o, lse
 
@@ -243,6 +257,7 @@ def ulysses_xattn_fwd(q, k, v, scale: float, layout: int = LAYOUT_SEQ_HEAD):
 def ulysses_xattn_bwd(q, k, v, o, dout, lse, scale: float, layout: int = LAYOUT_SEQ_HEAD):
     """-> (dq like q, dk, dv like k) bf16."""
     import torch
+    elem = _elem_flag(q, k, v, o, dout)
     Nq, Hl, d = _attn_dims(q, layout)
     Nk = _attn_dims(k, layout)[0]
     need = int(load().ulysses_xattn_bwd_workspace_bytes(Nq, Nk, Hl, d))
@@ -251,7 +266,7 @@ def ulysses_xattn_bwd(q, k, v, o, dout, lse, scale: float, layout: int = LAYOUT_
     w = "xattn_bwd"
     _check(load().ulysses_xattn_bwd(_dev(q, w), _dev(k, w), _dev(v, w), _dev(o, w), _dev(dout, w), _dev(lse, w),
                                     _dev(dq, w), _dev(dk, w), _dev(dv, w), _dev(workspace, w), workspace.numel(),
-                                    Nq, Nk, Hl, d, scale, layout, _stream()), "ulysses_xattn_bwd")
+                                    Nq, Nk, Hl, d, scale, layout | elem, _stream()), "ulysses_xattn_bwd")
     return dq, dk, dv
 
 
@@ -293,15 +308,14 @@ def _pattern_for(pattern, N):
 def ulysses_sparse_attn_fwd(q, k, v, pattern: SparsePattern, scale: float, layout: int = LAYOUT_SEQ_HEAD):
     """Causal attention restricted to the blocks of ``pattern`` -> (o, lse)."""
     import torch
-    if q.dtype != torch.bfloat16:
-        raise ValueError("attention tensors must be bfloat16")
+    elem = _elem_flag(q, k, v)
     N, Hl, d = _attn_dims(q, layout)
     p = _pattern_for(pattern, N)
     o = torch.empty_like(q)
     lse = torch.empty((Hl, N), dtype=torch.float32, device=q.device)
     w = "sparse_attn_fwd"
     _check(load().ulysses_sparse_attn_fwd(_dev(q, w), _dev(k, w), _dev(v, w), _dev(o, w), _dev(lse, w),
-                                          _dev(p["row_ptr"], w), _dev(p["col_idx"], w), N, Hl, d, scale, layout,
+                                          _dev(p["row_ptr"], w), _dev(p["col_idx"], w), N, Hl, d, scale, layout | elem,
                                           _stream()), "ulysses_sparse_attn_fwd")
     return o, lse
 
@@ -310,6 +324,7 @@ def ulysses_sparse_attn_bwd(q, k, v, o, dout, lse, pattern: SparsePattern, scale
                             layout: int = LAYOUT_SEQ_HEAD):
     """-> (dq, dk, dv) bf16 in ``layout``."""
     import torch
+    elem = _elem_flag(q, k, v, o, dout)
     N, Hl, d = _attn_dims(q, layout)
     p = _pattern_for(pattern, N)
     need = int(load().ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d))
@@ -319,6 +334,7 @@ def ulysses_sparse_attn_bwd(q, k, v, o, dout, lse, pattern: SparsePattern, scale
     _check(load().ulysses_sparse_attn_bwd(_dev(q, w), _dev(k, w), _dev(v, w), _dev(o, w), _dev(dout, w), _dev(lse, w),
                                           _dev(dq, w), _dev(dk, w), _dev(dv, w), _dev(p["row_ptr"], w),
                                           _dev(p["col_idx"], w), _dev(p["col_ptr"], w), _dev(p["row_idx"], w),
-                                          _dev(workspace, w), workspace.numel(), N, Hl, d, scale, layout, _stream()),
+                                          _dev(workspace, w), workspace.numel(), N, Hl, d, scale, layout | elem,
+                                          _stream()),
            "ulysses_sparse_attn_bwd")
     return dq, dk, dv

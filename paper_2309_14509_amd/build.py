@@ -10,7 +10,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libulysses.so")
 SOURCES = ["api.cpp", "layout.hip", "attn_fwd.hip", "attn_bwd.hip"]
-HEADERS = ["internal.h", "attn_common.h", os.path.join("..", "..", "include", "ulysses.h")]
+HEADERS = ["internal.h", "attn_launch.h", "attn_common.h", os.path.join("..", "..", "include", "ulysses.h")]
+# (source, object stem, extra flags): the attention sources are compiled once per element type
+UNITS = [("api.cpp", "api", []), ("layout.hip", "layout", []),
+         ("attn_fwd.hip", "attn_fwd", []), ("attn_bwd.hip", "attn_bwd", []),
+         ("attn_fwd.hip", "attn_fwd_f16", ["-DULY_BUILD_F16=1"]), ("attn_bwd.hip", "attn_bwd_f16", ["-DULY_BUILD_F16=1"])]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          # packed-fp32 VALU forms are kept off for every device function of this library
@@ -50,27 +54,28 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
         return LIB
     objs = []
     procs = []
-    for src in SOURCES:
-        obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-        cmd = [HIPCC, *FLAGS, *([RESOURCE_FLAG] if src in NO_SCRATCH else []), "-c", os.path.join(CSRC, src), "-o", obj]
+    for src, stem, extra in UNITS:
+        obj = os.path.join(CSRC, stem + ".o")
+        cmd = [HIPCC, *FLAGS, *extra, *([RESOURCE_FLAG] if src in NO_SCRATCH else []), "-c", os.path.join(CSRC, src),
+               "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
-        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        procs.append((src, stem, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
-    for src, p in procs:
+    for src, stem, p in procs:
         out, _ = p.communicate()
         if p.returncode != 0:
             sys.stderr.write(out)
-            raise RuntimeError(f"hipcc failed on {src}")
+            raise RuntimeError(f"hipcc failed on {src} ({stem})")
         if src in NO_SCRATCH:
             usage = scratch_bytes(out)
             if not usage:
-                raise RuntimeError(f"no kernel resource report for {src}: cannot verify that it uses no scratch")
+                raise RuntimeError(f"no kernel resource report for {stem}: cannot verify that it uses no scratch")
             bad = {k: v for k, v in usage.items() if v != 0}
             if bad:
-                raise RuntimeError(f"{src}: kernels with hand-issued LDS reads must not use scratch memory: {bad}")
+                raise RuntimeError(f"{stem}: kernels with hand-issued LDS reads must not use scratch memory: {bad}")
             if verbose:
-                print(f"{src}: {len(usage)} kernels, no scratch memory", flush=True)
+                print(f"{stem}: {len(usage)} kernels, no scratch memory", flush=True)
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.check_call(cmd)
     return LIB

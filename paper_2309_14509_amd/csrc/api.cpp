@@ -71,6 +71,7 @@ int check_layout_args3(const void* const src[3], void* const dst[3], int64_t n_l
 int check_attn_common(int64_t N, int Hl, int d, int layout, uint64_t* tensor_bytes) {
     if (N < 0 || Hl <= 0 || d <= 0) return ULY_ERR_SHAPE;
     if (d != 64 && d != 128) return ULY_ERR_UNSUPPORTED;
+    layout &= ~ULY_ELEM_F16;                                           // the element type flag rides on the layout word
     if (layout != ULY_LAYOUT_SEQ_HEAD && layout != ULY_LAYOUT_HEAD_SEQ) return ULY_ERR_UNSUPPORTED;
     if (N >= (1ll << 31)) return ULY_ERR_SHAPE;                       // tile counters are 32-bit
     if ((uint64_t)N * (uint64_t)Hl >= (1ull << 40)) return ULY_ERR_SHAPE;
@@ -156,8 +157,10 @@ static int attn_fwd_checked(const void* q, const void* k, const void* v, void* o
     const Range in[3] = {{q, tb}, {k, tbk}, {v, tbk}};
     const Range out[2] = {{o, tb}, {lse, (uint64_t)N * Hl * 4u}};
     if (any_alias(in, out)) return ULY_ERR_ALIAS;
-    return uly::attn_fwd_launch(q, k, v, o, lse, N, Nk, Hl, d, scale, causal != 0, uly::strides_for(layout, N, Hl, d),
-                                uly::strides_for(layout, Nk, Hl, d), stream);
+    const int lay = layout & ~ULY_ELEM_F16;
+    return (layout & ULY_ELEM_F16 ? uly::f16::attn_fwd_launch : uly::bf16::attn_fwd_launch)(
+        q, k, v, o, lse, N, Nk, Hl, d, scale, causal != 0, uly::strides_for(lay, N, Hl, d),
+        uly::strides_for(lay, Nk, Hl, d), stream);
 }
 
 int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int Hl, int d,
@@ -173,7 +176,7 @@ int ulysses_xattn_fwd(const void* q, const void* k, const void* v, void* o, floa
 size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
     (void)d;
     if (N <= 0 || Hl <= 0) return 0;
-    return (size_t)uly::attn_bwd_workspace_floats(N, Hl) * sizeof(float);
+    return (size_t)uly::bf16::attn_bwd_workspace_floats(N, Hl) * sizeof(float);      // the same for both element types
 }
 
 size_t ulysses_xattn_bwd_workspace_bytes(int64_t Nq, int64_t Nk, int Hl, int d) {
@@ -202,9 +205,10 @@ static int attn_bwd_checked(int stage_mask, const void* q, const void* k, const 
     const Range in[6] = {{q, tb}, {k, tbk}, {v, tbk}, {o, tb}, {dout, tb}, {lse, lb}};
     const Range out[4] = {{dq, tb}, {dk, tbk}, {dv, tbk}, {workspace, need}};
     if (any_alias(in, out)) return ULY_ERR_ALIAS;
-    return uly::attn_bwd_launch(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, N, Nk, Hl, d, scale,
-                                causal != 0, uly::strides_for(layout, N, Hl, d), uly::strides_for(layout, Nk, Hl, d),
-                                stream);
+    const int lay = layout & ~ULY_ELEM_F16;
+    return (layout & ULY_ELEM_F16 ? uly::f16::attn_bwd_launch : uly::bf16::attn_bwd_launch)(
+        stage_mask, q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, N, Nk, Hl, d, scale, causal != 0,
+        uly::strides_for(lay, N, Hl, d), uly::strides_for(lay, Nk, Hl, d), stream);
 }
 
 int ulysses_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
@@ -243,14 +247,14 @@ int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o
     const Range in[3] = {{q, tb}, {k, tb}, {v, tb}};
     const Range out[2] = {{o, tb}, {lse, (uint64_t)N * Hl * 4u}};
     if (any_alias(in, out)) return ULY_ERR_ALIAS;
-    return uly::attn_fwd_sparse_launch(q, k, v, o, lse, row_ptr, col_idx, N, Hl, d, scale,
-                                       uly::strides_for(layout, N, Hl, d), stream);
+    return (layout & ULY_ELEM_F16 ? uly::f16::attn_fwd_sparse_launch : uly::bf16::attn_fwd_sparse_launch)(
+        q, k, v, o, lse, row_ptr, col_idx, N, Hl, d, scale, uly::strides_for(layout & ~ULY_ELEM_F16, N, Hl, d), stream);
 }
 
 size_t ulysses_sparse_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
     uint64_t tb;
     if (check_attn_common(N, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK || N == 0) return 0;
-    return (size_t)uly::attn_bwd_sparse_workspace_floats(N, Hl, d) * sizeof(float);
+    return (size_t)uly::bf16::attn_bwd_sparse_workspace_floats(N, Hl, d) * sizeof(float);
 }
 
 int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,
@@ -274,8 +278,9 @@ int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const v
     const Range in[6] = {{q, tb}, {k, tb}, {v, tb}, {o, tb}, {dout, tb}, {lse, lb}};
     const Range out[4] = {{dq, tb}, {dk, tb}, {dv, tb}, {workspace, need}};
     if (any_alias(in, out)) return ULY_ERR_ALIAS;
-    return uly::attn_bwd_sparse_launch(q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, row_ptr, col_idx, col_ptr,
-                                       row_idx, N, Hl, d, scale, uly::strides_for(layout, N, Hl, d), stream);
+    return (layout & ULY_ELEM_F16 ? uly::f16::attn_bwd_sparse_launch : uly::bf16::attn_bwd_sparse_launch)(
+        q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, row_ptr, col_idx, col_ptr, row_idx, N, Hl, d, scale,
+        uly::strides_for(layout & ~ULY_ELEM_F16, N, Hl, d), stream);
 }
 
 int ulysses_probe_mfma(const void* data, size_t data_bytes, float* sink, size_t sink_bytes, int blocks, int iters,

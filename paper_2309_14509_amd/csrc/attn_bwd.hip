@@ -14,6 +14,7 @@
 #include "internal.h"
 
 namespace uly {
+namespace ULY_ELEM_NS {
 
 constexpr int kBwdThreads = 256;
 
@@ -24,7 +25,7 @@ constexpr int kBwdThreads = 256;
 // exp2(s - lse2) is exactly 0 without any test in the consumers.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const bf16* __restrict__ O, const bf16* __restrict__ dO,
+__global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const e16* __restrict__ O, const e16* __restrict__ dO,
                                                              const float* __restrict__ LSE, float* __restrict__ delta,
                                                              float* __restrict__ lse2, int N, int Hl, int64_t stride,
                                                              int64_t row_stride, int64_t head_stride) {
@@ -38,8 +39,8 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const bf16* __restr
     const bool live = in_grid && row < N;
     const int64_t ld_row = live ? row : 0;
     const int64_t off = ld_row * row_stride + head * head_stride + sub * 8;
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(O + off);
-    const bf16x8 b = *reinterpret_cast<const bf16x8*>(dO + off);
+    const e16x8 a = *reinterpret_cast<const e16x8*>(O + off);
+    const e16x8 b = *reinterpret_cast<const e16x8*>(dO + off);
     float acc = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
@@ -72,8 +73,8 @@ constexpr int kSparseBlockBwd = 256;
 
 template <int D, bool CAUSAL, bool SPARSE = false>
 __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
-    const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dO,
-    const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, bf16* __restrict__ dQ, int N,
+    const e16* __restrict__ Q, const e16* __restrict__ K, const e16* __restrict__ V, const e16* __restrict__ dO,
+    const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, e16* __restrict__ dQ, int N,
     int Nk, int n_qtiles, int64_t row_stride, int64_t head_stride, int64_t kv_head_stride, float scale,
     const int* __restrict__ row_ptr, const int* __restrict__ col_idx) {
     static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
@@ -85,7 +86,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     using Loader = DirectTile<D, kDqBK, kDqWaves, SwzBoth>;
     constexpr int LPT = 2 * Loader::kPerWave;   // global loads per wave per tile
 
-    __shared__ __attribute__((aligned(1024))) bf16 smem[2 * kDqRing * TILE];
+    __shared__ __attribute__((aligned(1024))) e16 smem[2 * kDqRing * TILE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ln = lane & 31;
     // Work assignment (causal): a workgroup takes query tile n_qtiles-1-pr and then its mirror image
@@ -98,8 +99,8 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     const int pr = blockIdx.x - head * n_pairs;
     const int64_t hoff = (int64_t)head * head_stride;
     // N queries, Nk keys (Nk = N for self-attention); K and V may have their own head stride
-    const bf16* Kh = K + (int64_t)head * kv_head_stride;
-    const bf16* Vh = V + (int64_t)head * kv_head_stride;
+    const e16* Kh = K + (int64_t)head * kv_head_stride;
+    const e16* Vh = V + (int64_t)head * kv_head_stride;
 
     // Key blocks are walked in whole groups of four; blocks nblk .. do not exist (all their keys are
     // masked) and re-read the data of the last real block.
@@ -163,11 +164,11 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     // ---- this lane's query: Q and dO rows as B operands, its two row statistics
     const int q_row = q0 + wave * 32 + ln;
     const int q_ld = q_row < N ? q_row : N - 1;
-    bf16x8 qreg[NT], doreg[NT];
+    e16x8 qreg[NT], doreg[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        qreg[t] = *reinterpret_cast<const bf16x8*>(Q + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
-        doreg[t] = *reinterpret_cast<const bf16x8*>(dO + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
+        qreg[t] = *reinterpret_cast<const e16x8*>(Q + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
+        doreg[t] = *reinterpret_cast<const e16x8*>(dO + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
     }
     const float lse2 = LSE2[(int64_t)head * ws_stride + q_row];     // padded: +inf for q_row >= N
     const float delta = DELTA[(int64_t)head * ws_stride + q_row];
@@ -182,8 +183,8 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
 
     f32x16 s[2], dp[2];
-    bf16x8 krow[NT], vrow[NT];
-    bf16x4 kt_lo[2][NCB], kt_hi[2][NCB];
+    e16x8 krow[NT], vrow[NT];
+    e16x4 kt_lo[2][NCB], kt_hi[2][NCB];
 
     auto read_krow = [&](auto slot_tag) __attribute__((always_inline)) {
         constexpr int SL = decltype(slot_tag)::value;
@@ -259,7 +260,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         constexpr int PAR = SL & 1;
         const int krel = klim - blk(p) * kDqBK;
         const int b_next = blk(p + kDqRing);           // the tile fetched into this position's slot
-        bf16x8 dsb[2];
+        e16x8 dsb[2];
         auto softmax_half = [&](int u) __attribute__((always_inline)) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -267,7 +268,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
                 float x = __builtin_fmaf(s[PAR][r], sl2, -lse2);
                 if (MASKED) x = (8 * (r >> 2) + (r & 3) > krel) ? -INFINITY : x;
                 const float p = fast_exp2(x);
-                dsb[u][e] = (bf16)(p * (dp[PAR][r] - delta));
+                dsb[u][e] = (e16)(p * (dp[PAR][r] - delta));
             }
         };
         auto interleave = [&]() __attribute__((always_inline)) {
@@ -362,15 +363,15 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     __builtin_amdgcn_sched_barrier(0);
 
     if (q_row < N) {
-        bf16* orow = dQ + hoff + (int64_t)q_row * row_stride;
+        e16* orow = dQ + hoff + (int64_t)q_row * row_stride;
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
-                bf16x4 w;
+                e16x4 w;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = (bf16)(acc[cb][4 * rq + e] * scale);
-                *reinterpret_cast<bf16x4*>(orow + 32 * cb + 8 * rq + 4 * g) = w;
+                for (int e = 0; e < 4; ++e) w[e] = (e16)(acc[cb][4 * rq + e] * scale);
+                *reinterpret_cast<e16x4*>(orow + 32 * cb + 8 * rq + 4 * g) = w;
             }
     }
     barrier_no_drain();          // every wave is done with the ring before the next query tile refills it
@@ -396,9 +397,9 @@ constexpr int kDkvRing = 4;   // LDS tiles per tensor
 
 template <int D, bool CAUSAL, bool SPARSE = false>
 __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
-    const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V, const bf16* __restrict__ dO,
-    const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, bf16* __restrict__ dK,
-    bf16* __restrict__ dV, int N, int Nk, int n_ktiles, int64_t row_stride, int64_t head_stride,
+    const e16* __restrict__ Q, const e16* __restrict__ K, const e16* __restrict__ V, const e16* __restrict__ dO,
+    const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, e16* __restrict__ dK,
+    e16* __restrict__ dV, int N, int Nk, int n_ktiles, int64_t row_stride, int64_t head_stride,
     int64_t kv_head_stride, float scale, const int* __restrict__ col_ptr, const int* __restrict__ row_idx,
     const int4* __restrict__ plan, float* __restrict__ partial, int slots_per_head) {
     static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
@@ -412,7 +413,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     using Loader = DirectTile<D, kDkvBQ, kDkvWaves, SwzBoth>;
     constexpr int LPT = 2 * Loader::kPerWave + 2;   // global loads per wave per tile (Q, dO, lse2, delta)
 
-    __shared__ __attribute__((aligned(1024))) bf16 smem[2 * kDkvRing * TILE];
+    __shared__ __attribute__((aligned(1024))) e16 smem[2 * kDkvRing * TILE];
     __shared__ __attribute__((aligned(256))) float stat[kDkvRing * (STAT / 4)];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ln = lane & 31;
@@ -437,8 +438,8 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         slot = (int)blockIdx.y < hdr.y ? (int)blockIdx.y : -1;
     }
     const int64_t hoff = (int64_t)head * head_stride;
-    const bf16* Qh = Q + hoff;
-    const bf16* dOh = dO + hoff;
+    const e16* Qh = Q + hoff;
+    const e16* dOh = dO + hoff;
     const int64_t kv_hoff = (int64_t)head * kv_head_stride;   // N queries, Nk keys (Nk = N for self-attention)
     const float* lse_h = LSE2 + (int64_t)head * ws_stride;
     const float* del_h = DELTA + (int64_t)head * ws_stride;
@@ -531,11 +532,11 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     // ---- this lane's key: K and V rows as B operands
     const int j_col = j0 + wave * 32 + ln;
     const int j_ld = j_col < Nk ? j_col : Nk - 1;
-    bf16x8 kreg[NT], vreg[NT];
+    e16x8 kreg[NT], vreg[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        kreg[t] = *reinterpret_cast<const bf16x8*>(K + kv_hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
-        vreg[t] = *reinterpret_cast<const bf16x8*>(V + kv_hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
+        kreg[t] = *reinterpret_cast<const e16x8*>(K + kv_hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
+        vreg[t] = *reinterpret_cast<const e16x8*>(V + kv_hoff + (int64_t)j_ld * row_stride + 16 * t + 8 * g);
     }
     const int jcol_g = j_col - 4 * g;            // causal test: row offset c_r is masked iff c_r < jcol_g - i0
 
@@ -547,9 +548,9 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 
     // pipeline registers
     f32x16 s[2], dp[2];                 // [parity]: scores / dP of the current and of the next block
-    bf16x8 rowq[NT], rowdo[NT];         // row operands of the block whose S, dP are computed next
+    e16x8 rowq[NT], rowdo[NT];         // row operands of the block whose S, dP are computed next
     f32x4 lse4[4], del4[4];             // statistics of the block whose P, dS are computed next
-    bf16x4 qt_lo[2][NCB], qt_hi[2][NCB], dot_lo[2][NCB], dot_hi[2][NCB];   // transposed operands of the current block
+    e16x4 qt_lo[2][NCB], qt_hi[2][NCB], dot_lo[2][NCB], dot_hi[2][NCB];   // transposed operands of the current block
 
     auto read_rowq = [&](auto slot_tag) __attribute__((always_inline)) {
         constexpr int SL = decltype(slot_tag)::value;
@@ -643,7 +644,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         const int i0 = blk(p) * kDkvBQ;
         const int jrel = jcol_g - i0;
         const int b_next = blk(p + kDkvRing);          // the tile fetched into this position's slot
-        bf16x8 pb[2], dsb[2];
+        e16x8 pb[2], dsb[2];
         // P and dS of 8 rows of block b (vector pipe)
         auto softmax_half = [&](int u) __attribute__((always_inline)) {
 #pragma unroll
@@ -653,8 +654,8 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
                 if (MASKED && CAUSAL) x = (8 * (r >> 2) + (r & 3) < jrel) ? -INFINITY : x;
                 const float p = fast_exp2(x);
                 const float ds = p * (dp[PAR][r] - del4[r >> 2][r & 3]);
-                pb[u][e] = (bf16)p;
-                dsb[u][e] = (bf16)ds;
+                pb[u][e] = (e16)p;
+                dsb[u][e] = (e16)ds;
             }
         };
         auto interleave = [&]() __attribute__((always_inline)) {     // one MFMA, then a share of the vector work
@@ -700,8 +701,8 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         // free, early enough to have landed when B1 ends.
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
-            const bf16x8 da = __builtin_shufflevector(dot_lo[0][cb], dot_hi[0][cb], 0, 1, 2, 3, 4, 5, 6, 7);
-            const bf16x8 qa = __builtin_shufflevector(qt_lo[0][cb], qt_hi[0][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+            const e16x8 da = __builtin_shufflevector(dot_lo[0][cb], dot_hi[0][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+            const e16x8 qa = __builtin_shufflevector(qt_lo[0][cb], qt_hi[0][cb], 0, 1, 2, 3, 4, 5, 6, 7);
             dv_acc[cb] = mfma32(da, pb[0], dv_acc[cb]);
             __builtin_amdgcn_sched_barrier(0);
             if (2 * cb < NCB) read_transposed(slot_tag, U1{}, 2 * cb);
@@ -722,8 +723,8 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         // statistics of block b+1, and the loads of tile b+4 into the slot of tile b
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
-            const bf16x8 da = __builtin_shufflevector(dot_lo[1][cb], dot_hi[1][cb], 0, 1, 2, 3, 4, 5, 6, 7);
-            const bf16x8 qa = __builtin_shufflevector(qt_lo[1][cb], qt_hi[1][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+            const e16x8 da = __builtin_shufflevector(dot_lo[1][cb], dot_hi[1][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+            const e16x8 qa = __builtin_shufflevector(qt_lo[1][cb], qt_hi[1][cb], 0, 1, 2, 3, 4, 5, 6, 7);
             dv_acc[cb] = mfma32(da, pb[1], dv_acc[cb]);
             __builtin_amdgcn_sched_barrier(0);
             if (NCB == 4) {
@@ -811,20 +812,20 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
                 *reinterpret_cast<f32x4*>(prow + kDkvBK * D + 32 * cb + 8 * rq + 4 * g) = wv;
             }
     } else if (j_col < Nk) {
-        bf16* krow = dK + kv_hoff + (int64_t)j_col * row_stride;
-        bf16* vrow = dV + kv_hoff + (int64_t)j_col * row_stride;
+        e16* krow = dK + kv_hoff + (int64_t)j_col * row_stride;
+        e16* vrow = dV + kv_hoff + (int64_t)j_col * row_stride;
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
-                bf16x4 wk, wv;
+                e16x4 wk, wv;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    wk[e] = (bf16)(dk_acc[cb][4 * rq + e] * scale);
-                    wv[e] = (bf16)dv_acc[cb][4 * rq + e];
+                    wk[e] = (e16)(dk_acc[cb][4 * rq + e] * scale);
+                    wv[e] = (e16)dv_acc[cb][4 * rq + e];
                 }
-                *reinterpret_cast<bf16x4*>(krow + 32 * cb + 8 * rq + 4 * g) = wk;
-                *reinterpret_cast<bf16x4*>(vrow + 32 * cb + 8 * rq + 4 * g) = wv;
+                *reinterpret_cast<e16x4*>(krow + 32 * cb + 8 * rq + 4 * g) = wk;
+                *reinterpret_cast<e16x4*>(vrow + 32 * cb + 8 * rq + 4 * g) = wv;
             }
     }
     barrier_no_drain();          // every wave is done with the ring before the next key tile refills it
@@ -937,7 +938,7 @@ template <int D>
 __global__ __launch_bounds__(256) void sparse_dkv_reduce_kernel(const int4* __restrict__ plan,
                                                                 const int2* __restrict__ red,
                                                                 const float* __restrict__ partial, int slots_per_head,
-                                                                bf16* __restrict__ dK, bf16* __restrict__ dV, int Nk,
+                                                                e16* __restrict__ dK, e16* __restrict__ dV, int Nk,
                                                                 int64_t row_stride, int64_t kv_head_stride) {
     constexpr int PER = kDkvBK * D;                       // floats per tensor and slot
     constexpr int CH = 2 * PER / 1024;                    // chunks per slot
@@ -955,11 +956,11 @@ __global__ __launch_bounds__(256) void sparse_dkv_reduce_kernel(const int4* __re
         const int which = e / PER, key = (e % PER) / D, ch = e % D;
         const int j = kt * kDkvBK + key;
         if (j >= Nk) continue;
-        bf16x4 w;
+        e16x4 w;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) w[c] = (bf16)acc[c];
-        bf16* dst = (which ? dV : dK) + (int64_t)head * kv_head_stride + (int64_t)j * row_stride + ch;
-        *reinterpret_cast<bf16x4*>(dst) = w;
+        for (int c = 0; c < 4; ++c) w[c] = (e16)acc[c];
+        e16* dst = (which ? dV : dK) + (int64_t)head * kv_head_stride + (int64_t)j * row_stride + ch;
+        *reinterpret_cast<e16x4*>(dst) = w;
     }
 }
 
@@ -997,35 +998,35 @@ static int launch_bwd(int stage_mask, const void* q, const void* k, const void* 
     const int64_t delta_blocks = (stride * Hl * (D / 8) + 255) / 256;
     const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (Nk + kDkvBK - 1) / kDkvBK;
     if (delta_blocks > 0x7FFFFFFFll || n_qtiles * Hl > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
-    const bf16 *Q = (const bf16*)q, *K = (const bf16*)k, *V = (const bf16*)v, *dO = (const bf16*)dout;
+    const e16 *Q = (const e16*)q, *K = (const e16*)k, *V = (const e16*)v, *dO = (const e16*)dout;
     // causal: a workgroup takes a pair of key tiles (query tiles)
     const int64_t n_kwg = causal ? (n_ktiles + 1) / 2 : n_ktiles, n_qwg = causal ? (n_qtiles + 1) / 2 : n_qtiles;
     const dim3 gkv((uint32_t)(n_kwg * Hl)), gq((uint32_t)(n_qwg * Hl));
 
     if (stage_mask & 1) {
         attn_bwd_delta_kernel<D><<<dim3((uint32_t)delta_blocks), dim3(256), 0, stream>>>(
-            (const bf16*)o, dO, lse, delta, lse2, (int)N, Hl, stride, st.row, st.head);
+            (const e16*)o, dO, lse, delta, lse2, (int)N, Hl, stride, st.row, st.head);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     if (stage_mask & 2) {
         if (causal)
             attn_bwd_dkv_kernel<D, true><<<gkv, dim3(kDkvThreads), 0, stream>>>(
-                Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
+                Q, K, V, dO, lse2, delta, stride, (e16*)dk, (e16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
                 kv.head, scale, nullptr, nullptr, nullptr, nullptr, 0);
         else
             attn_bwd_dkv_kernel<D, false><<<gkv, dim3(kDkvThreads), 0, stream>>>(
-                Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
+                Q, K, V, dO, lse2, delta, stride, (e16*)dk, (e16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
                 kv.head, scale, nullptr, nullptr, nullptr, nullptr, 0);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     if (stage_mask & 4) {
         if (causal)
             attn_bwd_dq_kernel<D, true><<<gq, dim3(kDqThreads), 0, stream>>>(
-                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
+                Q, K, V, dO, lse2, delta, stride, (e16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
                 nullptr, nullptr);
         else
             attn_bwd_dq_kernel<D, false><<<gq, dim3(kDqThreads), 0, stream>>>(
-                Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
+                Q, K, V, dO, lse2, delta, stride, (e16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
                 nullptr, nullptr);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
@@ -1044,9 +1045,9 @@ static int launch_bwd_sparse(const void* q, const void* k, const void* v, const 
     const int64_t delta_blocks = (stride * Hl * (D / 8) + 255) / 256;
     const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (N + kDkvBK - 1) / kDkvBK;
     if (delta_blocks > 0x7FFFFFFFll || n_qtiles * Hl > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
-    const bf16 *Q = (const bf16*)q, *K = (const bf16*)k, *V = (const bf16*)v, *dO = (const bf16*)dout;
+    const e16 *Q = (const e16*)q, *K = (const e16*)k, *V = (const e16*)v, *dO = (const e16*)dout;
     attn_bwd_delta_kernel<D><<<dim3((uint32_t)delta_blocks), dim3(256), 0, stream>>>(
-        (const bf16*)o, dO, lse, delta, lse2, (int)N, Hl, stride, st.row, st.head);
+        (const e16*)o, dO, lse, delta, lse2, (int)N, Hl, stride, st.row, st.head);
     if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     // work plan, then the items, then the sums of the cut columns
     const SparseWorkspace w = sparse_workspace(N, Hl, D);
@@ -1058,14 +1059,14 @@ static int launch_bwd_sparse(const void* q, const void* k, const void* v, const 
                                                                       red);
     if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     attn_bwd_dkv_kernel<D, true, true><<<dim3((uint32_t)Hl, (uint32_t)w.items_bound), dim3(kDkvThreads), 0, stream>>>(
-        Q, K, V, dO, lse2, delta, stride, (bf16*)dk, (bf16*)dv, (int)N, (int)N, (int)n_ktiles, st.row, st.head, st.head,
+        Q, K, V, dO, lse2, delta, stride, (e16*)dk, (e16*)dv, (int)N, (int)N, (int)n_ktiles, st.row, st.head, st.head,
         scale, col_ptr, row_idx, plan, partial, w.slots_per_head);
     if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     sparse_dkv_reduce_kernel<D><<<dim3(kReduceBlocks, (uint32_t)Hl), dim3(256), 0, stream>>>(
-        plan, red, partial, w.slots_per_head, (bf16*)dk, (bf16*)dv, (int)N, st.row, st.head);
+        plan, red, partial, w.slots_per_head, (e16*)dk, (e16*)dv, (int)N, st.row, st.head);
     if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     attn_bwd_dq_kernel<D, true, true><<<dim3((uint32_t)(n_qtiles * Hl)), dim3(kDqThreads), 0, stream>>>(
-        Q, K, V, dO, lse2, delta, stride, (bf16*)dq, (int)N, (int)N, (int)n_qtiles, st.row, st.head, st.head, scale,
+        Q, K, V, dO, lse2, delta, stride, (e16*)dq, (int)N, (int)N, (int)n_qtiles, st.row, st.head, st.head, scale,
         row_ptr, col_idx);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
@@ -1094,4 +1095,5 @@ int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v,
                           (hipStream_t)stream);
 }
 
+}  // namespace ULY_ELEM_NS
 }  // namespace uly

@@ -13,11 +13,25 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-namespace uly {
+// Element type of Q, K, V, O and the gradients: bf16, or fp16 when the translation unit is compiled
+// with ULY_BUILD_F16 (the build compiles every attention source once per type; everything in them
+// lives in namespace uly::bf16 or uly::f16).  Both types use the same MFMA shape and layouts.
+#if defined(ULY_BUILD_F16)
+#define ULY_ELEM_NS f16
+#else
+#define ULY_ELEM_NS bf16
+#endif
 
-typedef __bf16 bf16;
-typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+namespace uly {
+namespace ULY_ELEM_NS {
+
+#if defined(ULY_BUILD_F16)
+typedef _Float16 e16;
+#else
+typedef __bf16 e16;
+#endif
+typedef e16 e16x8 __attribute__((ext_vector_type(8)));
+typedef e16 e16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -25,18 +39,22 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+__device__ __forceinline__ f32x16 mfma32(e16x8 a, e16x8 b, f32x16 c) {
+#if defined(ULY_BUILD_F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+#else
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+#endif
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Registers 8u..8u+7 of a C/D block, rounded to bf16: a B operand whose contraction index e
 // is C-row 16u + 8*(e/4) + 4g + (e%4).
-__device__ __forceinline__ bf16x8 pack_b_operand(const f32x16& c, int u) {
-    bf16x8 r;
+__device__ __forceinline__ e16x8 pack_b_operand(const f32x16& c, int u) {
+    e16x8 r;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) r[e] = (bf16)c[8 * u + e];
+    for (int e = 0; e < 8; ++e) r[e] = (e16)c[8 * u + e];
     return r;
 }
 
@@ -124,7 +142,7 @@ template <int D, int ROWS, int WAVES, typename S = SwzBoth> struct DirectTile {
         return lo;
     }
     // Issue this wave's loads of a full tile whose first row is at `tile_base` (all rows valid).
-    __device__ static __forceinline__ void issue(bf16* tile, const bf16* tile_base, const LaneOffsets& lo, int wave) {
+    __device__ static __forceinline__ void issue(e16* tile, const e16* tile_base, const LaneOffsets& lo, int wave) {
 #pragma unroll
         for (int i = 0; i < kPerWave; ++i) {
             const char* src = reinterpret_cast<const char*>(tile_base) + i * lo.step_bytes + lo.off0;
@@ -151,7 +169,7 @@ template <int D, int ROWS, int WAVES, typename S = SwzBoth> struct DirectTile {
         }
         return to;
     }
-    __device__ static __forceinline__ void issue_sel(bf16* tile, const bf16* tile_base, const LaneOffsets& lo,
+    __device__ static __forceinline__ void issue_sel(e16* tile, const e16* tile_base, const LaneOffsets& lo,
                                                      const TailOffsets& to, bool is_tail, int wave) {
 #pragma unroll
         for (int i = 0; i < kPerWave; ++i) {
@@ -164,7 +182,7 @@ template <int D, int ROWS, int WAVES, typename S = SwzBoth> struct DirectTile {
     }
     // Same for a tile that may run past the end of the tensor: rows at or beyond n_rows are clamped
     // to the last valid row (callers mask them out).
-    __device__ static __forceinline__ void issue_clamped(bf16* tile, const bf16* base, int64_t row_stride, int row0,
+    __device__ static __forceinline__ void issue_clamped(e16* tile, const e16* base, int64_t row_stride, int row0,
                                                          int n_rows, int wave, int lane) {
         // This path runs at most once per workgroup.  The lane id is made opaque here so that none of
         // its address arithmetic is hoisted out of the caller's loop (where it would pin ~30 VGPRs).
@@ -176,7 +194,7 @@ template <int D, int ROWS, int WAVES, typename S = SwzBoth> struct DirectTile {
             const int r = slab * kRowsPerSlab + lr;
             int gr = row0 + r;
             gr = gr < n_rows ? gr : n_rows - 1;
-            const bf16* src = base + (int64_t)gr * row_stride + ((pc ^ S::template f<D>(r)) << 3);
+            const e16* src = base + (int64_t)gr * row_stride + ((pc ^ S::template f<D>(r)) << 3);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              ULY_LDS(void, tile + slab * kRowsPerSlab * D), 16, 0, 0);
         }
@@ -190,26 +208,26 @@ template <int D, int ROWS, int WAVES, typename S = SwzBoth> struct DirectTile {
 // count these in lgkmcnt, so every consumer is preceded by lds_wait<N>(regs...), which both waits
 // and ties the registers to the wait (nothing that uses them can be scheduled above it).
 // ------------------------------------------------------------------------------------------
-template <int IMM> __device__ __forceinline__ bf16x8 lds_b128(uint32_t addr) {
-    bf16x8 r;
+template <int IMM> __device__ __forceinline__ e16x8 lds_b128(uint32_t addr) {
+    e16x8 r;
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(IMM));
     return r;
 }
-template <int IMM> __device__ __forceinline__ bf16x4 lds_tr_b64(uint32_t addr) {
-    bf16x4 r;
+template <int IMM> __device__ __forceinline__ e16x4 lds_tr_b64(uint32_t addr) {
+    e16x4 r;
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(IMM));
     return r;
 }
-template <int N> __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b, bf16x8& c, bf16x8& d) {
+template <int N> __device__ __forceinline__ void lds_wait(e16x8& a, e16x8& b, e16x8& c, e16x8& d) {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
 }
-template <int N> __device__ __forceinline__ void lds_wait(bf16x4& a, bf16x4& b, bf16x4& c, bf16x4& d) {
+template <int N> __device__ __forceinline__ void lds_wait(e16x4& a, e16x4& b, e16x4& c, e16x4& d) {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
 }
-template <int N> __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b) {
+template <int N> __device__ __forceinline__ void lds_wait(e16x8& a, e16x8& b) {
     asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
 }
-template <int N> __device__ __forceinline__ void lds_wait(bf16x4& a, bf16x4& b) {
+template <int N> __device__ __forceinline__ void lds_wait(e16x4& a, e16x4& b) {
     asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
 }
 // Generic form: wait_lgkm<N>() followed by lds_tie(regs...) orders every later use of `regs` behind
@@ -235,5 +253,6 @@ __device__ __forceinline__ void barrier_no_drain() { asm volatile("s_barrier" ::
 // Wait until every direct-to-LDS load this wave has issued has landed.
 __device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+}  // namespace ULY_ELEM_NS
 }  // namespace uly
 #endif

@@ -18,6 +18,7 @@
 #include "internal.h"
 
 namespace uly {
+namespace ULY_ELEM_NS {
 
 constexpr int kFwdThreads = 512;
 constexpr int kFwdWaves = 8;
@@ -36,8 +37,8 @@ constexpr int kSparseBlock = 256;
 static_assert(kFwdBQ == kSparseBlock && kSparseBlock % kFwdBK == 0, "a query tile must be one sparse block row");
 
 template <int D, bool CAUSAL, bool SPARSE = false>
-__global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
-                                                                   const bf16* __restrict__ V, bf16* __restrict__ O,
+__global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __restrict__ Q, const e16* __restrict__ K,
+                                                                   const e16* __restrict__ V, e16* __restrict__ O,
                                                                    float* __restrict__ LSE, int N, int Nk, int n_qtiles,
                                                                    int64_t row_stride, int64_t head_stride, int64_t kv_head_stride,
                                                                    float scale, const int* __restrict__ row_ptr,
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
     constexpr int NQL = (D == 128) ? 2 : 0;
     constexpr int NQR = NT - NQL;
     constexpr int QROW = NQL * 32 + 16;      // bytes per query row in LDS, padded: conflict-free row reads
-    __shared__ __attribute__((aligned(1024))) bf16 smem[4 * TILE];
+    __shared__ __attribute__((aligned(1024))) e16 smem[4 * TILE];
     __shared__ __attribute__((aligned(16))) char q_lds[NQL ? kFwdBQ * QROW : 16];
 
     const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
@@ -73,10 +74,10 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
     const int head = blockIdx.x / n_pairs;
     const int pr = blockIdx.x - head * n_pairs;
     const int64_t hoff = (int64_t)head * head_stride;
-    const bf16* Qh = Q + hoff;
+    const e16* Qh = Q + hoff;
     // N queries attend to Nk keys (Nk = N for self-attention); K and V may have their own head stride
-    const bf16* Kh = K + (int64_t)head * kv_head_stride;
-    const bf16* Vh = V + (int64_t)head * kv_head_stride;
+    const e16* Kh = K + (int64_t)head * kv_head_stride;
+    const e16* Vh = V + (int64_t)head * kv_head_stride;
 
     const typename KLoader::LaneOffsets k_ld = KLoader::lane_offsets(row_stride, wave, lane);
     const typename VLoader::LaneOffsets v_ld = VLoader::lane_offsets(row_stride, wave, lane);
@@ -137,15 +138,15 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
     const int wave_p = wave, g_p = (tid_p >> 5) & 1, ln_p = tid_p & 31;
     const int q_row = q0 + wave_p * 32 + ln_p;                 // this lane's query
     const int q_ld = q_row < N ? q_row : N - 1;
-    bf16x8 qreg[NQR];
+    e16x8 qreg[NQR];
 #pragma unroll
     for (int t = 0; t < NQR; ++t)
-        qreg[t] = *reinterpret_cast<const bf16x8*>(Qh + (int64_t)q_ld * row_stride + 16 * t + 8 * g_p);
+        qreg[t] = *reinterpret_cast<const e16x8*>(Qh + (int64_t)q_ld * row_stride + 16 * t + 8 * g_p);
     const uint32_t q_adr = lds_addr(q_lds) + (wave_p * 32 + ln_p) * QROW + g_p * 16;
 #pragma unroll
     for (int t = NQR; t < NT; ++t)      // only this wave reads these rows back: no barrier needed
-        *reinterpret_cast<bf16x8*>(q_lds + (wave_p * 32 + ln_p) * QROW + (2 * (t - NQR) + g_p) * 16) =
-            *reinterpret_cast<const bf16x8*>(Qh + (int64_t)q_ld * row_stride + 16 * t + 8 * g_p);
+        *reinterpret_cast<e16x8*>(q_lds + (wave_p * 32 + ln_p) * QROW + (2 * (t - NQR) + g_p) * 16) =
+            *reinterpret_cast<const e16x8*>(Qh + (int64_t)q_ld * row_stride + 16 * t + 8 * g_p);
 
 
     float m_used = -INFINITY;    // reference maximum (raw logits) that the exponentials are taken against
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
     // K operands of one 32-key block.  The first half is read one phase ahead (during the PV MFMAs of
     // the previous block), the second half at the start of the block itself, behind the first half's
     // MFMAs: only half of them are live while the register pressure peaks.
-    bf16x8 ka[NT];
+    e16x8 ka[NT];
     auto read_k = [&](auto off_tag, auto half_tag) __attribute__((always_inline)) {
         constexpr int OFF = decltype(off_tag)::value;
         constexpr int H = decltype(half_tag)::value;
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
 
         wait_k(First{});
         read_k(kb_tag, Second{});
-        bf16x8 ql[NQL ? NQL : 1];
+        e16x8 ql[NQL ? NQL : 1];
         if constexpr (NQL == 2) {
             ql[0] = lds_b128<0>(q_adr);
             ql[1] = lds_b128<32>(q_adr);
@@ -218,7 +219,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
         __builtin_amdgcn_sched_barrier(0);      // the reads below reuse ka: keep them behind the MFMAs
 
         // V operands of the first 16 keys: they arrive during the softmax
-        bf16x4 vlo[NCB], vhi[NCB];
+        e16x4 vlo[NCB], vhi[NCB];
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
             vlo[cb] = lds_tr_b64<VB>(v_adr[cb]);
@@ -264,15 +265,15 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
         // and where bf16 rounding of P would be the dominant error, so diagonal blocks carry P in two
         // bf16 pieces (hi + lo).
         auto pv_half = [&](int u) __attribute__((always_inline)) {
-            const bf16x8 pb = pack_b_operand(s, u);
-            bf16x8 plo;
+            const e16x8 pb = pack_b_operand(s, u);
+            e16x8 plo;
             if (MASKED) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) plo[e] = (bf16)(s[8 * u + e] - (float)pb[e]);
+                for (int e = 0; e < 8; ++e) plo[e] = (e16)(s[8 * u + e] - (float)pb[e]);
             }
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
-                const bf16x8 va = __builtin_shufflevector(vlo[cb], vhi[cb], 0, 1, 2, 3, 4, 5, 6, 7);
+                const e16x8 va = __builtin_shufflevector(vlo[cb], vhi[cb], 0, 1, 2, 3, 4, 5, 6, 7);
                 oacc[cb] = mfma32(va, pb, oacc[cb]);
                 if (MASKED) oacc[cb] = mfma32(va, plo, oacc[cb]);
             }
@@ -352,15 +353,15 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const bf16* __
     const float l_tot = xhalf_sum(l_run);
     const float inv = 1.f / l_tot;
     if (q_row < N) {
-        bf16* orow = O + hoff + (int64_t)q_row * row_stride;
+        e16* orow = O + hoff + (int64_t)q_row * row_stride;
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
-                bf16x4 w;
+                e16x4 w;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = (bf16)(oacc[cb][4 * rq + e] * inv);
-                *reinterpret_cast<bf16x4*>(orow + 32 * cb + 8 * rq + 4 * g) = w;
+                for (int e = 0; e < 4; ++e) w[e] = (e16)(oacc[cb][4 * rq + e] * inv);
+                *reinterpret_cast<e16x4*>(orow + 32 * cb + 8 * rq + 4 * g) = w;
             }
         if (g == 0) LSE[(int64_t)head * N + q_row] = m_used * scale + __logf(l_tot);
     }
@@ -376,15 +377,44 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
     if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     dim3 grid((uint32_t)blocks), block(kFwdThreads);
     if (causal)
-        attn_fwd_kernel<D, true><<<grid, block, 0, stream>>>((const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o,
+        attn_fwd_kernel<D, true><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
                                                              lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
                                                              nullptr, nullptr);
     else
-        attn_fwd_kernel<D, false><<<grid, block, 0, stream>>>((const bf16*)q, (const bf16*)k, (const bf16*)v,
-                                                              (bf16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
+        attn_fwd_kernel<D, false><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v,
+                                                              (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
                                                               kv.head, scale, nullptr, nullptr);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
+
+int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, const int* row_ptr,
+                           const int* col_idx, int64_t N, int Hl, int d, float scale, TensorStrides st, void* stream) {
+    const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ;
+    const int64_t blocks = n_qtiles * Hl;
+    if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
+    dim3 grid((uint32_t)blocks), block(kFwdThreads);
+    hipStream_t s = (hipStream_t)stream;
+    if (d == 128)
+        attn_fwd_kernel<128, true, true><<<grid, block, 0, s>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
+                                                                lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head,
+                                                                st.head, scale, row_ptr, col_idx);
+    else
+        attn_fwd_kernel<64, true, true><<<grid, block, 0, s>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
+                                                               lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head,
+                                                               st.head, scale, row_ptr, col_idx);
+    return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
+}
+
+int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
+                    int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream) {
+    if (d == 128) return launch_fwd<128>(q, k, v, o, lse, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
+    return launch_fwd<64>(q, k, v, o, lse, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
+}
+
+}  // namespace ULY_ELEM_NS
+
+#if !defined(ULY_BUILD_F16)
+using namespace bf16;
 
 // ------------------------------------------------------------------------------------------
 // Measurement aid: nothing but bf16 MFMAs (four independent accumulation chains per wave, one wave
@@ -392,12 +422,12 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
 // this sustains is the matrix rate the part actually allows under its power limit; the attention
 // kernels are quoted against it next to the published peak.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 1) void mfma_probe_kernel(const bf16* __restrict__ data, float* __restrict__ sink,
+__global__ __launch_bounds__(256, 1) void mfma_probe_kernel(const e16* __restrict__ data, float* __restrict__ sink,
                                                             int iters) {
     __shared__ float pad[24 * 1024];                 // 96 KiB: one workgroup per CU
     if (iters < 0) pad[threadIdx.x] = 0.f;
-    bf16x8 a[8], b[8];
-    const bf16x8* src = reinterpret_cast<const bf16x8*>(data);
+    e16x8 a[8], b[8];
+    const e16x8* src = reinterpret_cast<const e16x8*>(data);
 #pragma unroll
     for (int t = 0; t < 8; ++t) { a[t] = src[threadIdx.x + 512 * t]; b[t] = src[threadIdx.x + 512 * t + 256]; }
     f32x16 acc[4];
@@ -419,32 +449,9 @@ __global__ __launch_bounds__(256, 1) void mfma_probe_kernel(const bf16* __restri
 
 // data: at least kProbeBytes of device memory filled by the caller; sink: at least blocks*256 floats
 int mfma_probe_launch(const void* data, float* sink, int blocks, int iters, void* stream) {
-    mfma_probe_kernel<<<dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream>>>((const bf16*)data, sink, iters);
+    mfma_probe_kernel<<<dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream>>>((const e16*)data, sink, iters);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
-
-int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, const int* row_ptr,
-                           const int* col_idx, int64_t N, int Hl, int d, float scale, TensorStrides st, void* stream) {
-    const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ;
-    const int64_t blocks = n_qtiles * Hl;
-    if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
-    dim3 grid((uint32_t)blocks), block(kFwdThreads);
-    hipStream_t s = (hipStream_t)stream;
-    if (d == 128)
-        attn_fwd_kernel<128, true, true><<<grid, block, 0, s>>>((const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o,
-                                                                lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head,
-                                                                st.head, scale, row_ptr, col_idx);
-    else
-        attn_fwd_kernel<64, true, true><<<grid, block, 0, s>>>((const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o,
-                                                               lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head,
-                                                               st.head, scale, row_ptr, col_idx);
-    return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
-}
-
-int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
-                    int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream) {
-    if (d == 128) return launch_fwd<128>(q, k, v, o, lse, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
-    return launch_fwd<64>(q, k, v, o, lse, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
-}
+#endif
 
 }  // namespace uly

@@ -1,0 +1,32 @@
+// Launch functions of the attention kernels.  internal.h includes this file once per element type,
+// inside namespace uly::bf16 and inside namespace uly::f16 (no include guard on purpose); the
+// attention sources are compiled once per element type and define the functions of their namespace.
+// Sizes and strides count 16-bit elements.
+
+// N queries attend to Nk keys/values (Nk = N for self-attention; causal requires Nk = N).  `st` are the
+// strides of the query-side tensors (q, o, dout, dq), `kv` those of k, v, dk, dv.
+int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
+                    int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
+
+// Block-sparse causal forward: keys restricted to the 256-key blocks of a CSR pattern (device arrays).
+int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, const int* row_ptr,
+                           const int* col_idx, int64_t N, int Hl, int d, float scale, TensorStrides st, void* stream);
+
+// floats of scratch the backward kernels need (padded row statistics: delta and lse*log2e); N = queries
+int64_t attn_bwd_workspace_floats(int64_t N, int Hl);
+
+// stage_mask: bit 0 delta, bit 1 dK/dV, bit 2 dQ (kernels run in that order)
+int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
+                    const float* lse, void* dq, void* dk, void* dv, float* delta, int64_t N, int64_t Nk, int Hl, int d,
+                    float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
+
+// floats of scratch of the block-sparse backward: the statistics, the dK/dV work plan and the fp32
+// partial sums of block columns that are cut into several work items
+int64_t attn_bwd_sparse_workspace_floats(int64_t N, int Hl, int d);
+
+// Block-sparse causal backward; row_ptr/col_idx list the block columns of each block row, col_ptr/row_idx
+// the block rows of each block column (device arrays).
+int attn_bwd_sparse_launch(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                           const float* lse, void* dq, void* dk, void* dv, float* delta, const int* row_ptr,
+                           const int* col_idx, const int* col_ptr, const int* row_idx, int64_t N, int Hl, int d,
+                           float scale, TensorStrides st, void* stream);

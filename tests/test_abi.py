@@ -109,6 +109,19 @@ def test_attention_backward_validation(lib):
     assert call(N=0, ws=None, wsb=0) == 0
 
 
+def test_element_type_flag(lib):
+    """ULY_ELEM_F16 rides on the layout word of the attention entry points; validation is the same for both
+    element types, unknown bits stay unsupported, and the layout transforms (elem_bytes) refuse the flag."""
+    F16 = 0x100
+    assert uly.ELEM_F16 == F16
+    for layout in (0 | F16, 1 | F16):
+        assert _fwd(lib, layout=layout, N=0) == 0
+        assert _fwd(lib, layout=layout, q=None) == 1 and _fwd(lib, layout=layout, o=A) == 5
+    assert _fwd(lib, layout=2 | F16) == 3 and _fwd(lib, layout=0x200) == 3
+    assert lib.ulysses_unpack(A, B, 64, 8, 64, 4, 2, F16, None) == 3
+    assert lib.ulysses_pack_rev(A, B, 64, 8, 64, 4, 2, F16, None) == 3
+
+
 def test_binding_refuses_a_missing_library(tmp_path):
     with pytest.raises(FileNotFoundError):
         uly.load(str(tmp_path / "nope.so"))
