@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--sparse-window", type=int, default=0,
                     help="also time block-sparse attention: local window of this many 256-token blocks plus the "
                          "first block column (0 = off; extra 'sparse' object in the output)")
+    ap.add_argument("--elem", choices=["bf16", "fp16"], default="bf16",
+                    help="element type of the tensors (the headline metric is bf16)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU's share only (no collectives, no second GPU); "
@@ -67,8 +69,11 @@ def main() -> int:
     scale = 1.0 / math.sqrt(d)
     seed = synth.config_seed(args.config)
 
-    def dev_bf16(bits):
-        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    etype = torch.float16 if args.elem == "fp16" else torch.bfloat16
+    lay = uly.LAYOUT_SEQ_HEAD | (uly.ELEM_F16 if args.elem == "fp16" else 0)      # attention entry points only
+
+    def dev_bf16(bits):      # bf16 bit patterns -> device tensor of the chosen element type
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16).to(etype)
 
     # ---- synthetic inputs, resident in HBM ---------------------------------------------------
     # sequence-sharded activations this rank would send (3 tensors: q, k, v projections)
@@ -77,11 +82,11 @@ def main() -> int:
     q_bits, k_bits, v_bits, do_bits = synth.attention_inputs(N, Hl, d, seed, c["qk_mult"])
     recvs = [dev_bf16(b.reshape(P, nl, Hl, d)) for b in (q_bits, k_bits, v_bits)]
     dout = dev_bf16(do_bits)
-    sends = [torch.empty((P, nl, Hl, d), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
-    qkv = [torch.empty((N, Hl, d), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
-    o = torch.empty((N, Hl, d), dtype=torch.bfloat16, device="cuda")
+    sends = [torch.empty((P, nl, Hl, d), dtype=etype, device="cuda") for _ in range(3)]
+    qkv = [torch.empty((N, Hl, d), dtype=etype, device="cuda") for _ in range(3)]
+    o = torch.empty((N, Hl, d), dtype=etype, device="cuda")
     lse = torch.empty((Hl, N), dtype=torch.float32, device="cuda")
-    grads = tuple(torch.empty((N, Hl, d), dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    grads = tuple(torch.empty((N, Hl, d), dtype=etype, device="cuda") for _ in range(3))
     ws = torch.empty(max(uly.ulysses_attn_bwd_workspace_bytes(N, Hl, d), 16), dtype=torch.uint8, device="cuda")
 
     lib = uly.load()
@@ -111,12 +116,12 @@ def main() -> int:
         uly._check(lib.ulysses_unpack_qkv(recv_ptrs, qkv_ptrs, nl, H, d, P, 2, uly.LAYOUT_SEQ_HEAD, sp), "unpack_qkv")
         mark()
         uly._check(lib.ulysses_attn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse), N, Hl, d, scale, 1,
-                                        uly.LAYOUT_SEQ_HEAD, sp), "attn_fwd")
+                                        lay, sp), "attn_fwd")
         mark()
         for stage in (uly.BWD_STAGE_DELTA, uly.BWD_STAGE_DKV, uly.BWD_STAGE_DQ):
             uly._check(lib.ulysses_attn_bwd_stage(stage, ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(dout),
                                                   ptr(lse), ptr(grads[0]), ptr(grads[1]), ptr(grads[2]), ptr(ws),
-                                                  ws.numel(), N, Hl, d, scale, 1, uly.LAYOUT_SEQ_HEAD, sp), "attn_bwd")
+                                                  ws.numel(), N, Hl, d, scale, 1, lay, sp), "attn_bwd")
             mark()
 
     for _ in range(args.warmup):
@@ -154,9 +159,9 @@ def main() -> int:
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "f16" if args.elem == "fp16" else "bf16", "data": "synthetic",
         "config": {"workload": f"{args.config}: one GPU's share, N={N} tokens, P={P}, H={H} ({Hl} local heads), "
-                               f"d={d}, batch 1, causal; per step pack and unpack of 3 x [{nl},{H},{d}] bf16 (one launch each) and "
+                               f"d={d}, batch 1, causal; per step pack and unpack of 3 x [{nl},{H},{d}] {args.elem} (one launch each) and "
                                "attention fwd+bwd",
                    "N": N, "P": P, "H": H, "local_heads": Hl, "d": d},
         "attn_fwd_bwd_tflops": (flop_fwd + flop_bwd) / (attn_ms * 1e-3) / 1e12,
@@ -201,12 +206,12 @@ def main() -> int:
             sp_ev[0].record(stream)
             uly._check(lib.ulysses_sparse_attn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse),
                                                    ptr(pd["row_ptr"]), ptr(pd["col_idx"]), N, Hl, d, scale,
-                                                   uly.LAYOUT_SEQ_HEAD, sp), "sparse_attn_fwd")
+                                                   lay, sp), "sparse_attn_fwd")
             sp_ev[1].record(stream)
             uly._check(lib.ulysses_sparse_attn_bwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(dout), ptr(lse),
                                                    ptr(grads[0]), ptr(grads[1]), ptr(grads[2]), ptr(pd["row_ptr"]),
                                                    ptr(pd["col_idx"]), ptr(pd["col_ptr"]), ptr(pd["row_idx"]), ptr(sws),
-                                                   sws.numel(), N, Hl, d, scale, uly.LAYOUT_SEQ_HEAD, sp),
+                                                   sws.numel(), N, Hl, d, scale, lay, sp),
                        "sparse_attn_bwd")
             sp_ev[2].record(stream)
         sparse_step()
