@@ -181,6 +181,7 @@ int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o
  * whatever N is).  The sums are added in a fixed order: results are deterministic.
  * ------------------------------------------------------------------------------------------- */
 #define ULY_SPARSE_BLOCK 256
+#define ULY_SPARSE_BWD_MAX_N 8000000   /* longer sequences: ULY_ERR_SHAPE from ulysses_sparse_attn_bwd */
 int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                             const int32_t* row_ptr, const int32_t* col_idx,
                             int64_t N, int Hl, int d, float scale, int layout, void* stream);

@@ -253,7 +253,7 @@ int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o
 
 size_t ulysses_sparse_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
     uint64_t tb;
-    if (check_attn_common(N, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK || N == 0) return 0;
+    if (check_attn_common(N, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK || N == 0 || N > ULY_SPARSE_BWD_MAX_N) return 0;
     return (size_t)uly::bf16::attn_bwd_sparse_workspace_floats(N, Hl, d) * sizeof(float);
 }
 
@@ -266,6 +266,7 @@ int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const v
     if (rc != ULY_OK) return rc;
     if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;
     if (N == 0) return ULY_OK;
+    if (N > ULY_SPARSE_BWD_MAX_N) return ULY_ERR_SHAPE;          // the work items of dK/dV are a grid dimension
     if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv || !row_ptr || !col_idx || !col_ptr || !row_idx)
         return ULY_ERR_NULL;
     const size_t need = ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d);

@@ -186,6 +186,7 @@ def test_sparse_attention_validation(lib):
                                                    for n in ("q", "k", "v", "o", "do", "lse", "dq", "dk", "dv", "rp", "ci",
                                                              "cp", "ri", "ws", "wsb", "N", "Hl", "d", "scale", "layout")],
                                                  None)
+    assert g(N=8000001) == 2 and lib.ulysses_sparse_attn_bwd_workspace_bytes(8000001, 2, 64) == 0
     assert g(cp=None) == 1 and g(ri=None) == 1 and g(wsb=8) == 6 and g(ri=RI + 1) == 4 and g(dq=A) == 5
 
 

@@ -91,6 +91,19 @@ def test_full_pattern_agrees_with_the_dense_kernels(gpu_lib):
         assert rel_l2(f64_of(a), f64_of(b)) <= 5e-3               # same terms, summed in another order
 
 
+def test_backward_with_cut_columns_is_deterministic(gpu_lib):
+    """Partial sums of a cut block column are added in a fixed order: two runs give the same bits."""
+    N, Hl, d = 6000, 2, 128
+    q, k, v, do = synth.attention_inputs(N, Hl, d, 77)
+    tq, tk, tv, tdo = (to_gpu_bf16(a) for a in (q, k, v, do))
+    pat = gpu_lib.SparsePattern(_mask((N + B - 1) // B, "window_global", 0))
+    o, lse = gpu_lib.ulysses_sparse_attn_fwd(tq, tk, tv, pat, 0.09)
+    first = gpu_lib.ulysses_sparse_attn_bwd(tq, tk, tv, o, tdo, lse, pat, 0.09)
+    again = gpu_lib.ulysses_sparse_attn_bwd(tq, tk, tv, o, tdo, lse, pat, 0.09)
+    for a, b in zip(first, again):
+        assert torch.equal(a, b)
+
+
 def test_pattern_is_checked_on_the_host(gpu_lib):
     with pytest.raises(ValueError):
         gpu_lib.SparsePattern(np.array([[1, 0], [1, 0]]))
