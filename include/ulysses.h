@@ -97,6 +97,16 @@ int ulysses_pack_rev(const void* o, void* send, int64_t n_local, int H, int d, i
 int ulysses_unpack_rev(const void* recv, void* y, int64_t n_local, int H, int d, int P,
                        int elem_bytes, void* stream);
 
+/* The reverse transforms for three tensors of one shape in one launch: the backward pass returns
+ * dQ, dK and dV to sequence-parallel form the way the forward pass brought Q, K and V in (the
+ * gradient of an all-to-all is the opposite all-to-all, Section 3.1).  HOST arrays of three device
+ * pointers, as for ulysses_pack_qkv; tensor t is transformed exactly as by ulysses_pack_rev
+ * (ulysses_unpack_rev). */
+int ulysses_pack_rev_qkv(const void* const g[3], void* const send[3], int64_t n_local, int H, int d, int P,
+                         int elem_bytes, int in_layout, void* stream);
+int ulysses_unpack_rev_qkv(const void* const recv[3], void* const y[3], int64_t n_local, int H, int d, int P,
+                           int elem_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Exact softmax attention per local head, Equation 1:  O = Softmax(Q K^T * scale) V,
  * softmax over keys.  causal != 0 restricts query i to keys j <= i (global token positions,

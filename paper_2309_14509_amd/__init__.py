@@ -17,7 +17,7 @@ LAYOUT_SEQ_HEAD = 0   # [N, Hl, d]
 LAYOUT_HEAD_SEQ = 1   # [Hl, N, d]
 
 EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
-           "ulysses_pack_qkv", "ulysses_unpack_qkv",
+           "ulysses_pack_qkv", "ulysses_unpack_qkv", "ulysses_pack_rev_qkv", "ulysses_unpack_rev_qkv",
            "ulysses_xattn_fwd", "ulysses_xattn_bwd_workspace_bytes", "ulysses_xattn_bwd",
            "ulysses_sparse_attn_fwd", "ulysses_sparse_attn_bwd_workspace_bytes", "ulysses_sparse_attn_bwd",
            "ulysses_probe_mfma",
@@ -51,6 +51,8 @@ def load(path: str | None = None):
     p3 = ctypes.POINTER(ctypes.c_void_p)      # host array of three device pointers
     lib.ulysses_pack_qkv.argtypes = [p3, p3, i64, ci, ci, ci, ci, vp]
     lib.ulysses_unpack_qkv.argtypes = [p3, p3, i64, ci, ci, ci, ci, ci, vp]
+    lib.ulysses_pack_rev_qkv.argtypes = [p3, p3, i64, ci, ci, ci, ci, ci, vp]
+    lib.ulysses_unpack_rev_qkv.argtypes = [p3, p3, i64, ci, ci, ci, ci, vp]
     lib.ulysses_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, cf, ci, ci, vp]
     lib.ulysses_attn_bwd_workspace_bytes.argtypes = [i64, ci, ci]
     lib.ulysses_attn_bwd_workspace_bytes.restype = sz
@@ -172,6 +174,35 @@ def ulysses_unpack_rev(recv):
     _check(load().ulysses_unpack_rev(_dev(recv, "unpack_rev"), _dev(y, "unpack_rev"), nl, Hl * P, d, P,
                                      recv.element_size(), _stream()), "ulysses_unpack_rev")
     return y
+
+
+def ulysses_pack_rev_qkv(gs, P: int, in_layout: int = LAYOUT_SEQ_HEAD):
+    """Three tensors [N, Hl, d] (or [Hl, N, d]) of one shape and dtype -> three send buffers [P, N/P, Hl, d]."""
+    import torch
+    if any(g.shape != gs[0].shape or g.dtype != gs[0].dtype for g in gs):
+        raise ValueError("ulysses_pack_rev_qkv: the three tensors must share shape and dtype")
+    if in_layout == LAYOUT_HEAD_SEQ:
+        Hl, N, d = gs[0].shape
+    else:
+        N, Hl, d = gs[0].shape
+    if P <= 0 or N % P:
+        raise ValueError("N must be a multiple of P")
+    sends = [torch.empty((P, N // P, Hl, d), dtype=g.dtype, device=g.device) for g in gs]
+    _check(load().ulysses_pack_rev_qkv(_ptr3(gs, "pack_rev_qkv"), _ptr3(sends, "pack_rev_qkv"), N // P, Hl * P, d, P,
+                                       gs[0].element_size(), in_layout, _stream()), "ulysses_pack_rev_qkv")
+    return sends
+
+
+def ulysses_unpack_rev_qkv(recvs):
+    """Three receive buffers [P, n_local, Hl, d] -> three tensors [n_local, P*Hl, d], in one launch."""
+    import torch
+    P, nl, Hl, d = recvs[0].shape
+    if any(r.shape != recvs[0].shape or r.dtype != recvs[0].dtype for r in recvs):
+        raise ValueError("ulysses_unpack_rev_qkv: the three tensors must share shape and dtype")
+    ys = [torch.empty((nl, P * Hl, d), dtype=r.dtype, device=r.device) for r in recvs]
+    _check(load().ulysses_unpack_rev_qkv(_ptr3(recvs, "unpack_rev_qkv"), _ptr3(ys, "unpack_rev_qkv"), nl, Hl * P, d, P,
+                                         recvs[0].element_size(), _stream()), "ulysses_unpack_rev_qkv")
+    return ys
 
 
 # ---- attention ----------------------------------------------------------------------------------

@@ -142,6 +142,26 @@ int ulysses_pack_rev(const void* o, void* send, int64_t n_local, int H, int d, i
     return uly::regroup(o, send, N, Hl, (int64_t)d * elem_bytes, /*to_b=*/false, stream);  // [Hl,N,d] -> [N,Hl,d]
 }
 
+int ulysses_pack_rev_qkv(const void* const g[3], void* const send[3], int64_t n_local, int H, int d, int P,
+                         int elem_bytes, int in_layout, void* stream) {
+    uint64_t bytes = 0;
+    const int rc = check_layout_args3(g, send, n_local, H, d, P, elem_bytes, in_layout, &bytes);
+    if (rc != ULY_OK || bytes == 0) return rc;
+    const int64_t N = n_local * P;
+    const int Hl = H / P;
+    if (in_layout == ULY_LAYOUT_SEQ_HEAD || Hl == 1)
+        return uly::regroup_multi(g, send, 3, N, 1, (int64_t)Hl * d * elem_bytes, true, stream);
+    return uly::regroup_multi(g, send, 3, N, Hl, (int64_t)d * elem_bytes, /*to_b=*/false, stream);
+}
+
+int ulysses_unpack_rev_qkv(const void* const recv[3], void* const y[3], int64_t n_local, int H, int d, int P,
+                           int elem_bytes, void* stream) {
+    uint64_t bytes = 0;
+    const int rc = check_layout_args3(recv, y, n_local, H, d, P, elem_bytes, ULY_LAYOUT_SEQ_HEAD, &bytes);
+    if (rc != ULY_OK || bytes == 0) return rc;
+    return uly::regroup_multi(recv, y, 3, n_local, P, (int64_t)(H / P) * d * elem_bytes, /*to_b=*/false, stream);
+}
+
 // Shared by self-attention (Nk == N) and cross-attention (causal == 0, Nk keys for N queries).
 static int attn_fwd_checked(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk,
                             int Hl, int d, float scale, int causal, int layout, void* stream) {

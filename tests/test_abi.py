@@ -72,6 +72,13 @@ def test_qkv_transform_validation(lib):
     # empty tensors: nothing to do, pointers inside the arrays are not looked at
     assert lib.ulysses_pack_qkv(arr(None, None, None), arr(None, None, None), 0, 8, 64, 4, 2, None) == 0
     assert lib.ulysses_unpack_qkv(arr(None, None, None), arr(None, None, None), 0, 8, 64, 4, 2, 0, None) == 0
+    # the reverse direction (dQ, dK, dV): same checks
+    assert lib.ulysses_pack_rev_qkv(ins, None, 16, 8, 64, 4, 2, 0, None) == 1
+    assert lib.ulysses_pack_rev_qkv(ins, outs, 16, 8, 64, 4, 2, 7, None) == 3
+    assert lib.ulysses_pack_rev_qkv(ins, arr(B, B + size - 16, B + 2 * size), 16, 8, 64, 4, 2, 1, None) == 5
+    assert lib.ulysses_unpack_rev_qkv(arr(A, A + size, None), outs, 16, 8, 64, 4, 2, None) == 1
+    assert lib.ulysses_unpack_rev_qkv(ins, outs, 16, 8, 64, 3, 2, None) == 2
+    assert lib.ulysses_unpack_rev_qkv(arr(None, None, None), arr(None, None, None), 0, 8, 64, 4, 2, None) == 0
 
 
 def _fwd(lib, q=A, k=B, v=C_, o=D_, lse=0x7000000, N=128, Hl=2, d=64, scale=0.125, causal=1, layout=0):

@@ -60,6 +60,22 @@ def test_qkv_in_one_launch_bit_exact(gpu_lib, nl, H, d, P, layout):
         assert np.array_equal(bits_of(y), oracle.unpack(r, layout))
 
 
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("nl,H,d,P", SMALL[:5])
+def test_reverse_transforms_of_three_tensors_in_one_launch(gpu_lib, nl, H, d, P, layout):
+    """dQ, dK, dV back to sequence-parallel form: each tensor equals the oracle's reverse transform."""
+    Hl, N = H // P, nl * P
+    shape = (Hl, N, d) if layout == 1 else (N, Hl, d)
+    gs = [synth.bits_u16(shape, 8, synth.TID_X + 10 * t) for t in range(3)]
+    sends = gpu_lib.ulysses_pack_rev_qkv([to_gpu_u16(g) for g in gs], P, layout)
+    for g, s_ in zip(gs, sends):
+        assert np.array_equal(bits_of(s_), oracle.pack_rev(g, P, layout))
+    rs = [synth.bits_u16((P, nl, Hl, d), 8, synth.TID_R + 10 * t) for t in range(3)]
+    ys = gpu_lib.ulysses_unpack_rev_qkv([to_gpu_u16(r) for r in rs])
+    for r, y in zip(rs, ys):
+        assert np.array_equal(bits_of(y), oracle.unpack_rev(r))
+
+
 @pytest.mark.parametrize("elem", [torch.uint8, torch.int32])
 def test_other_element_sizes(gpu_lib, elem):
     nl, H, d, P = 37, 6, 24, 3
