@@ -75,6 +75,7 @@ int check_attn_common(int64_t N, int Hl, int d, int layout, uint64_t* tensor_byt
     if (layout != ULY_LAYOUT_SEQ_HEAD && layout != ULY_LAYOUT_HEAD_SEQ) return ULY_ERR_UNSUPPORTED;
     if (N >= (1ll << 31)) return ULY_ERR_SHAPE;                       // tile counters are 32-bit
     if ((uint64_t)N * (uint64_t)Hl >= (1ull << 40)) return ULY_ERR_SHAPE;
+    if ((uint64_t)Hl * (uint64_t)d > (1ull << 22)) return ULY_ERR_SHAPE;    // in-tile byte offsets are 32-bit
     *tensor_bytes = (uint64_t)N * (uint64_t)Hl * (uint64_t)d * 2u;
     return ULY_OK;
 }

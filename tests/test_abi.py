@@ -88,6 +88,7 @@ def _fwd(lib, q=A, k=B, v=C_, o=D_, lse=0x7000000, N=128, Hl=2, d=64, scale=0.12
 def test_attention_forward_validation(lib):
     assert _fwd(lib, q=None) == 1 and _fwd(lib, lse=None) == 1
     assert _fwd(lib, N=-5) == 2 and _fwd(lib, Hl=0) == 2 and _fwd(lib, N=1 << 31) == 2
+    assert _fwd(lib, Hl=(1 << 16) + 1, N=8) == 2                              # a token row of more than 2^22 elements
     assert _fwd(lib, d=96) == 3 and _fwd(lib, layout=2) == 3
     assert _fwd(lib, scale=0.0) == 3 and _fwd(lib, scale=-1.0) == 3
     assert _fwd(lib, scale=float("nan")) == 3 and _fwd(lib, scale=float("inf")) == 3

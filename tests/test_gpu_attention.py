@@ -205,3 +205,66 @@ def test_full_size_configs_sampled_rows(gpu_lib, name):
     # invariants over all rows (bf16 output rounding: N independent errors of relative size 2^-9)
     assert rel_l2(sum_dv, sum_do) <= 1e-2
     assert np.abs(sum_dk).max() <= 0.05 * dk_rms * np.sqrt(N)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_tensors_beyond_four_gib(gpu_lib, layout):
+    """520 heads of 32768 tokens: every tensor is 4.36 GB, so element offsets pass 2^31 and byte offsets 2^32.
+    Three heads (first, middle, last) carry data and are checked on sampled rows as in the full-size test; the
+    other heads are zero and must give exactly zero O and gradients (nothing leaks between heads)."""
+    N, Hl, d, sel = 32768, 520, 128, [0, 259, 519]
+    scale = 1.0 / np.sqrt(d)
+    q, k, v, do = synth.attention_inputs(N, len(sel), d, 4321)
+    rows = sample_rows(N, 48, 1, 4321)
+    shape = (Hl, N, d) if layout == 1 else (N, Hl, d)
+
+    def place(bits):
+        big = torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
+        small = to_gpu_bf16(bits)
+        if layout == 1:
+            big[sel] = small.permute(1, 0, 2)
+        else:
+            big[:, sel] = small
+        return big
+
+    def take(t):                     # -> [N, 3, d]
+        return t[sel].permute(1, 0, 2) if layout == 1 else t[:, sel]
+
+    tq, tk, tv, tdo = (place(a) for a in (q, k, v, do))
+    assert tq.numel() * 2 > (1 << 32)
+    print("[>4GiB] forward", flush=True)
+    o, lse = gpu_lib.ulysses_attn_fwd(tq, tk, tv, scale, True, layout)
+    print("[>4GiB] backward (dense dO)", flush=True)
+    dq, dk, dv = gpu_lib.ulysses_attn_bwd(tq, tk, tv, o, tdo, lse, scale, True, layout)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(rows).cuda()
+    o_s, dq_s = f64_of(take(o)[idx]), f64_of(take(dq)[idx])
+    lse_s = f64_of(lse[sel][:, idx])
+    others = [h for h in range(Hl) if h not in sel]
+    for t in (o, dq, dk, dv):
+        rest = t[others] if layout == 1 else t[:, others]
+        assert not bool(rest.any())
+    tdo_m = torch.zeros_like(tdo)
+    if layout == 1:
+        tdo_m[:, idx] = tdo[:, idx]
+    else:
+        tdo_m[idx] = tdo[idx]
+    del dq, dk, dv
+    print("[>4GiB] backward (masked dO)", flush=True)
+    _, dk_m, dv_m = gpu_lib.ulysses_attn_bwd(tq, tk, tv, o, tdo_m, lse, scale, True, layout)
+    torch.cuda.synchronize()
+    dk_m, dv_m = f64_of(take(dk_m)), f64_of(take(dv_m))
+    del tq, tk, tv, tdo, tdo_m, o, lse
+    torch.cuda.empty_cache()
+
+    print(f"[>4GiB] oracle on {rows.size} rows", flush=True)
+    fq, fk, fv, fdo = (oracle.bf16_to_f64(a) for a in (q, k, v, do))
+    o_ref, lse_ref = oracle.attn_fwd_rows(fq, fk, fv, rows, scale, True)
+    o_abs, _ = oracle.attn_fwd_rows(fq, fk, np.abs(fv), rows, scale, True)
+    dq_ref, dk_ref, dv_ref = oracle.attn_bwd_rows(fq, fk, fv, fdo, rows, scale, True)
+    ok, worst, n_bad = o_within_tolerance(o_s, o_ref, o_abs, TOL_O)
+    assert ok, (worst, n_bad)
+    assert max_abs(lse_s, lse_ref) <= TOL_LSE
+    assert rel_l2(dq_s, dq_ref) <= TOL_G
+    assert rel_l2(dk_m, dk_ref) <= TOL_G
+    assert rel_l2(dv_m, dv_ref) <= TOL_G

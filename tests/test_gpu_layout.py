@@ -138,3 +138,32 @@ def test_full_size_configs_bit_exact(gpu_lib, name):
         got = gpu_lib.ulysses_unpack(to_gpu_u16(r), layout)
         assert np.array_equal(bits_of(got), oracle.unpack(r, layout))
         del got
+
+
+def test_tensors_beyond_four_gib(gpu_lib):
+    """4.9 GB per tensor (2.46e9 elements): element offsets pass 2^31 and byte offsets 2^32 on both sides of every
+    transform.  The oracle's index loops run on sampled row ranges (start, both places where an offset crosses
+    2^31 elements, end): for a set R of local rows, pack(x[R]) = pack(x)[:, R], and likewise for the others."""
+    nl, H, d, P = 1200003, 32, 64, 8
+    Hl = H // P
+    g = torch.Generator(device="cuda").manual_seed(2309)
+    x = torch.randint(-32768, 32767, (nl, H, d), generator=g, dtype=torch.int16, device="cuda")
+    assert x.numel() > (1 << 31)
+    src_cross = (1 << 31) // (H * d)                       # row of x where the element offset passes 2^31
+    dst_cross = ((1 << 31) // (Hl * d)) % nl               # local row where the offset inside send passes 2^31
+    R = np.unique(np.concatenate([np.arange(0, 300), np.arange(src_cross - 300, src_cross + 300),
+                                  np.arange(dst_cross - 300, dst_cross + 300), np.arange(nl - 300, nl)]))
+    Rt = torch.from_numpy(R).cuda()
+
+    send = gpu_lib.ulysses_pack(x, P)                       # [P, nl, Hl, d]
+    assert np.array_equal(bits_of(send[:, Rt]), oracle.pack(bits_of(x[Rt]), P))
+    back = gpu_lib.ulysses_unpack_rev(send)                 # [nl, H, d]
+    assert np.array_equal(bits_of(back[Rt]), oracle.unpack_rev(bits_of(send[:, Rt])))
+    assert torch.equal(back, x)
+    del back
+    y = gpu_lib.ulysses_unpack(send, 1)                     # [Hl, P*nl, d]
+    ref = oracle.unpack(bits_of(send[:, Rt]), 1)            # [Hl, P*|R|, d]
+    assert np.array_equal(bits_of(y.view(Hl, P, nl, d)[:, :, Rt]), ref.reshape(Hl, P, R.size, d))
+    again = gpu_lib.ulysses_pack_rev(y, P, 1)               # [P, nl, Hl, d]
+    assert np.array_equal(bits_of(again[:, Rt]), oracle.pack_rev(ref, P, 1))
+    assert torch.equal(again, send)
