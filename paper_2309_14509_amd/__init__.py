@@ -336,14 +336,15 @@ def _pattern_for(pattern, N):
     return pattern.dev
 
 
-def ulysses_sparse_attn_fwd(q, k, v, pattern: SparsePattern, scale: float, layout: int = LAYOUT_SEQ_HEAD):
+def ulysses_sparse_attn_fwd(q, k, v, pattern: SparsePattern, scale: float, layout: int = LAYOUT_SEQ_HEAD,
+                            out=None, lse=None):
     """Causal attention restricted to the blocks of ``pattern`` -> (o, lse)."""
     import torch
     elem = _elem_flag(q, k, v)
     N, Hl, d = _attn_dims(q, layout)
     p = _pattern_for(pattern, N)
-    o = torch.empty_like(q)
-    lse = torch.empty((Hl, N), dtype=torch.float32, device=q.device)
+    o = torch.empty_like(q) if out is None else out
+    lse = torch.empty((Hl, N), dtype=torch.float32, device=q.device) if lse is None else lse
     w = "sparse_attn_fwd"
     _check(load().ulysses_sparse_attn_fwd(_dev(q, w), _dev(k, w), _dev(v, w), _dev(o, w), _dev(lse, w),
                                           _dev(p["row_ptr"], w), _dev(p["col_idx"], w), N, Hl, d, scale, layout | elem,
@@ -351,16 +352,22 @@ def ulysses_sparse_attn_fwd(q, k, v, pattern: SparsePattern, scale: float, layou
     return o, lse
 
 
+def ulysses_sparse_attn_bwd_workspace_bytes(N: int, Hl: int, d: int) -> int:
+    return int(load().ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d))
+
+
 def ulysses_sparse_attn_bwd(q, k, v, o, dout, lse, pattern: SparsePattern, scale: float,
-                            layout: int = LAYOUT_SEQ_HEAD):
-    """-> (dq, dk, dv) bf16 in ``layout``."""
+                            layout: int = LAYOUT_SEQ_HEAD, workspace=None, out=None):
+    """-> (dq, dk, dv) in ``layout``.  ``workspace`` (uint8, ulysses_sparse_attn_bwd_workspace_bytes) and ``out``
+    are allocated here unless the caller brings them."""
     import torch
     elem = _elem_flag(q, k, v, o, dout)
     N, Hl, d = _attn_dims(q, layout)
     p = _pattern_for(pattern, N)
-    need = int(load().ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d))
-    workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    if workspace is None:
+        workspace = torch.empty(max(ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d), 16), dtype=torch.uint8,
+                                device=q.device)
+    dq, dk, dv = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)) if out is None else out
     w = "sparse_attn_bwd"
     _check(load().ulysses_sparse_attn_bwd(_dev(q, w), _dev(k, w), _dev(v, w), _dev(o, w), _dev(dout, w), _dev(lse, w),
                                           _dev(dq, w), _dev(dk, w), _dev(dv, w), _dev(p["row_ptr"], w),
