@@ -1,7 +1,7 @@
 // Device-side building blocks shared by the attention kernels (gfx950 / CDNA4, wave64).
 //
 // MFMA operand conventions used throughout (v_mfma_f32_32x32x16_bf16, lane l, g = l / 32):
-//   A (32 x 16): lane holds row  l % 32, contraction indices 8g .. 8g+7   (8 bf16 = one 16-byte load)
+//   A (32 x 16): lane holds row  l % 32, contraction indices 8g .. 8g+7   (8 elements = one 16-byte load)
 //   B (16 x 32): lane holds col  l % 32, contraction indices 8g .. 8g+7
 //   C/D (32 x 32): register r of lane l is row 8*(r/4) + 4g + (r%4), column l % 32
 // Every kernel keeps the "long" reduction axis of its softmax in the rows of C, so that a lane
@@ -49,7 +49,7 @@ __device__ __forceinline__ f32x16 mfma32(e16x8 a, e16x8 b, f32x16 c) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Registers 8u..8u+7 of a C/D block, rounded to bf16: a B operand whose contraction index e
+// Registers 8u..8u+7 of a C/D block, rounded to the element type: a B operand whose contraction index e
 // is C-row 16u + 8*(e/4) + 4g + (e%4).
 __device__ __forceinline__ e16x8 pack_b_operand(const f32x16& c, int u) {
     e16x8 r;
@@ -85,7 +85,7 @@ __device__ __forceinline__ float xhalf_sum(float x) {
 // ------------------------------------------------------------------------------------------
 // LDS tiles filled straight from global memory (global_load_lds_dwordx4: no VGPR staging).
 //
-// A tile is ROWS x D bf16, rows unpadded (D*2 bytes); the 16-byte chunk c of row r is stored at
+// A tile is ROWS x D 16-bit elements, rows unpadded (D*2 bytes); the 16-byte chunk c of row r is stored at
 // chunk position c ^ swz(r).  One wave-wide load writes 1 KiB of consecutive LDS (lane L -> byte
 // 16*L), so the swizzle is applied by choosing which global chunk each lane fetches.  swz is
 // chosen so that both access patterns are bank-conflict free:

@@ -1,5 +1,5 @@
 // Forward pass of exact softmax attention (paper Equation 1, causal variant of Section 3.4)
-// for the local heads of one GPU: tiled online softmax, bf16 MFMA, fp32 accumulation.
+// for the local heads of one GPU: tiled online softmax, 16-bit (bf16 or fp16) MFMA, fp32 accumulation.
 //
 // Work decomposition: one workgroup (8 waves) owns 256 consecutive queries of one head; each wave
 // owns 32 of them as the COLUMNS of its MFMA tiles:
@@ -262,8 +262,8 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
         l_run += rs0 + rs1;
 
         // O^T += V^T P^T, 16 keys at a time.  MASKED: rows with few visible keys are where |O| is largest
-        // and where bf16 rounding of P would be the dominant error, so diagonal blocks carry P in two
-        // bf16 pieces (hi + lo).
+        // and where rounding P to 16 bits would be the dominant error, so diagonal blocks carry P in two
+        // 16-bit pieces (hi + lo).
         auto pv_half = [&](int u) __attribute__((always_inline)) {
             const e16x8 pb = pack_b_operand(s, u);
             e16x8 plo;
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
         }
     }
 
-    // ---- epilogue: normalise, store O (bf16) and LSE (natural log)
+    // ---- epilogue: normalise, store O (element type) and LSE (natural log)
     const float l_tot = xhalf_sum(l_run);
     const float inv = 1.f / l_tot;
     if (q_row < N) {
