@@ -43,6 +43,9 @@ def main() -> int:
     ap.add_argument("--sparse-window", type=int, default=0,
                     help="also time block-sparse attention: local window of this many 256-token blocks plus the "
                          "first block column (0 = off; extra 'sparse' object in the output)")
+    ap.add_argument("--xattn", default="",
+                    help="also time attention without a mask for these (queries, keys) counts, e.g. "
+                         "'131072x131072,16384x131072': rows of the same tensors (extra 'xattn' list in the output)")
     ap.add_argument("--elem", choices=["bf16", "fp16"], default="bf16",
                     help="element type of the tensors (the headline metric is bf16)")
     args = ap.parse_args()
@@ -192,6 +195,41 @@ def main() -> int:
     result["mfma_only_tflops"] = probe_tflops
     result["roofline"]["frac_of_mfma_only_loop"] = dkv_tflops / probe_tflops
     result["attn_frac_of_mfma_only_loop"] = result["attn_fwd_bwd_tflops"] / probe_tflops
+
+    # ---- optional: unmasked attention of Nq queries over Nk keys (cross-attention shapes) --------
+    if args.xattn:
+        result["xattn"] = []
+        for spec in args.xattn.split(","):
+            Nq, Nk = (int(x) for x in spec.lower().split("x"))
+            if not (0 < Nq <= N and 0 < Nk <= N):
+                print(f"bench.py: --xattn sizes must be between 1 and N = {N}", file=sys.stderr)
+                return 2
+            xws = torch.empty(int(lib.ulysses_xattn_bwd_workspace_bytes(Nq, Nk, Hl, d)), dtype=torch.uint8, device="cuda")
+            xev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+            def xattn_step():
+                # the first Nq (Nk) token rows of the token-major tensors are tensors of that many tokens
+                xev[0].record(stream)
+                uly._check(lib.ulysses_xattn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse), Nq, Nk, Hl, d,
+                                                 scale, lay, sp), "xattn_fwd")
+                xev[1].record(stream)
+                uly._check(lib.ulysses_xattn_bwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(dout), ptr(lse),
+                                                 ptr(grads[0]), ptr(grads[1]), ptr(grads[2]), ptr(xws), xws.numel(),
+                                                 Nq, Nk, Hl, d, scale, lay, sp), "xattn_bwd")
+                xev[2].record(stream)
+            xattn_step()
+            torch.cuda.synchronize()
+            fwd_ms = bwd_ms = 0.0
+            for _ in range(args.steps):
+                xattn_step()
+                torch.cuda.synchronize()
+                fwd_ms += xev[0].elapsed_time(xev[1]) / args.steps
+                bwd_ms += xev[1].elapsed_time(xev[2]) / args.steps
+            pairs = float(Nq) * Nk * d * Hl
+            result["xattn"].append({"queries": Nq, "keys": Nk, "ms_fwd": fwd_ms, "ms_bwd": bwd_ms,
+                                    "fwd_tflops": 4 * pairs / (fwd_ms * 1e-3) / 1e12,
+                                    "bwd_tflops": 10 * pairs / (bwd_ms * 1e-3) / 1e12,
+                                    "tflops": 14 * pairs / ((fwd_ms + bwd_ms) * 1e-3) / 1e12})
 
     # ---- optional: block-sparse causal attention on the same tensors ---------------------------
     if args.sparse_window > 0:
