@@ -43,6 +43,9 @@ def main() -> int:
     ap.add_argument("--sparse-window", type=int, default=0,
                     help="also time block-sparse attention: local window of this many 256-token blocks plus the "
                          "first block column (0 = off; extra 'sparse' object in the output)")
+    ap.add_argument("--layouts", action="store_true",
+                    help="also time every layout transform (forward and reverse direction, both layouts, one and "
+                         "three tensors per launch) at this workload's shapes (extra 'layout_transforms' object)")
     ap.add_argument("--xattn", default="",
                     help="also time attention without a mask for these (queries, keys) counts, e.g. "
                          "'131072x131072,16384x131072': rows of the same tensors (extra 'xattn' list in the output)")
@@ -195,6 +198,46 @@ def main() -> int:
     result["mfma_only_tflops"] = probe_tflops
     result["roofline"]["frac_of_mfma_only_loop"] = dkv_tflops / probe_tflops
     result["attn_frac_of_mfma_only_loop"] = result["attn_fwd_bwd_tflops"] / probe_tflops
+
+    # ---- optional: every layout transform at this workload's shapes --------------------------------
+    if args.layouts:
+        tb = float(nl) * H * d * 2                                   # bytes of one tensor
+        hm = [torch.empty((Hl, N, d), dtype=etype, device="cuda") for _ in range(3)]       # head-major tensors
+        ys = [torch.empty((nl, H, d), dtype=etype, device="cuda") for _ in range(3)]
+        hm_ptrs, ys_ptrs = ptr3(hm), ptr3(ys)
+        SH, HS = uly.LAYOUT_SEQ_HEAD, uly.LAYOUT_HEAD_SEQ
+        cases = {
+            "pack": (1, lambda: lib.ulysses_pack(ptr(xs[0]), ptr(sends[0]), nl, H, d, P, 2, sp)),
+            "unpack_token_major": (1, lambda: lib.ulysses_unpack(ptr(recvs[0]), ptr(qkv[0]), nl, H, d, P, 2, SH, sp)),
+            "unpack_head_major": (1, lambda: lib.ulysses_unpack(ptr(recvs[0]), ptr(hm[0]), nl, H, d, P, 2, HS, sp)),
+            "pack_rev_token_major": (1, lambda: lib.ulysses_pack_rev(ptr(qkv[0]), ptr(sends[0]), nl, H, d, P, 2, SH, sp)),
+            "pack_rev_head_major": (1, lambda: lib.ulysses_pack_rev(ptr(hm[0]), ptr(sends[0]), nl, H, d, P, 2, HS, sp)),
+            "unpack_rev": (1, lambda: lib.ulysses_unpack_rev(ptr(recvs[0]), ptr(ys[0]), nl, H, d, P, 2, sp)),
+            "pack_qkv": (3, lambda: lib.ulysses_pack_qkv(x_ptrs, send_ptrs, nl, H, d, P, 2, sp)),
+            "unpack_qkv_token_major": (3, lambda: lib.ulysses_unpack_qkv(recv_ptrs, qkv_ptrs, nl, H, d, P, 2, SH, sp)),
+            "unpack_qkv_head_major": (3, lambda: lib.ulysses_unpack_qkv(recv_ptrs, hm_ptrs, nl, H, d, P, 2, HS, sp)),
+            "pack_rev_qkv_token_major": (3, lambda: lib.ulysses_pack_rev_qkv(qkv_ptrs, send_ptrs, nl, H, d, P, 2, SH, sp)),
+            "pack_rev_qkv_head_major": (3, lambda: lib.ulysses_pack_rev_qkv(hm_ptrs, send_ptrs, nl, H, d, P, 2, HS, sp)),
+            "unpack_rev_qkv": (3, lambda: lib.ulysses_unpack_rev_qkv(recv_ptrs, ys_ptrs, nl, H, d, P, 2, sp)),
+        }
+        # Every launch is timed on its own, after copies of other tensors (512 MiB of traffic) have pushed its
+        # input out of the 256 MB last-level cache: back-to-back repeats would partly read from that cache.
+        reps = 10
+        result["layout_transforms"] = {"unit": "GB/s (bytes read + written)", "tensor_bytes": tb, "launches_timed": reps}
+        for name, (count, call) in cases.items():
+            uly._check(call(), name)
+            pairs = []
+            for _ in range(reps):
+                grads[0].copy_(o)
+                grads[1].copy_(dout)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                uly._check(call(), name)
+                e1.record(stream)
+                pairs.append((e0, e1))
+            torch.cuda.synchronize()
+            ms = sum(a.elapsed_time(b) for a, b in pairs) / reps
+            result["layout_transforms"][name] = 2 * count * tb / (ms * 1e-3) / 1e9
 
     # ---- optional: unmasked attention of Nq queries over Nk keys (cross-attention shapes) --------
     if args.xattn:
