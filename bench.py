@@ -248,13 +248,15 @@ def main() -> int:
                 print(f"bench.py: --xattn sizes must be between 1 and N = {N}", file=sys.stderr)
                 return 2
             xws = torch.empty(int(lib.ulysses_xattn_bwd_workspace_bytes(Nq, Nk, Hl, d)), dtype=torch.uint8, device="cuda")
+            xfw = torch.empty(max(int(lib.ulysses_xattn_fwd_workspace_bytes(Nq, Nk, Hl, d)), 16), dtype=torch.uint8,
+                              device="cuda")
             xev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
             def xattn_step():
                 # the first Nq (Nk) token rows of the token-major tensors are tensors of that many tokens
                 xev[0].record(stream)
-                uly._check(lib.ulysses_xattn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse), Nq, Nk, Hl, d,
-                                                 scale, lay, sp), "xattn_fwd")
+                uly._check(lib.ulysses_xattn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse), ptr(xfw),
+                                                 xfw.numel(), Nq, Nk, Hl, d, scale, lay, sp), "xattn_fwd")
                 xev[1].record(stream)
                 uly._check(lib.ulysses_xattn_bwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(dout), ptr(lse),
                                                  ptr(grads[0]), ptr(grads[1]), ptr(grads[2]), ptr(xws), xws.numel(),

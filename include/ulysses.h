@@ -157,10 +157,18 @@ int ulysses_attn_bwd_stage(int stage,
  * queries attending to Nk keys/values of the same local heads, no mask.
  *   q, o, dout, dq: Nq tokens;  k, v, dk, dv: Nk tokens;  all bf16 in `layout` (each tensor with its
  *   own token count: [Nq, Hl, d] / [Nk, Hl, d], or head-major);  lse [Hl, Nq] fp32.
- * Same arithmetic, precision, checks and workspace rules as the self-attention entry points.
+ * Same arithmetic, precision and checks as the self-attention entry points.
  * Nq == 0 does nothing; Nk == 0 with Nq > 0 is ULY_ERR_SHAPE (a softmax over no keys).
+ * Workspaces (caller-owned device memory, 16-byte aligned; ULY_ERR_WORKSPACE if too small): when
+ * one side has too few tokens to occupy the device with one workgroup per tile, the other side of
+ * each tile is cut into several work items whose fp32 partial results a second kernel merges in a
+ * fixed order (deterministic).  ulysses_xattn_fwd_workspace_bytes is 0 for shapes that are not cut
+ * (workspace may then be NULL); ulysses_xattn_bwd_workspace_bytes always covers the row statistics.
+ * Both stay below about 600 MiB whatever the sizes.
  * ------------------------------------------------------------------------------------------- */
+size_t ulysses_xattn_fwd_workspace_bytes(int64_t Nq, int64_t Nk, int Hl, int d);
 int ulysses_xattn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                      void* workspace, size_t workspace_bytes,
                       int64_t Nq, int64_t Nk, int Hl, int d, float scale, int layout, void* stream);
 size_t ulysses_xattn_bwd_workspace_bytes(int64_t Nq, int64_t Nk, int Hl, int d);
 int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,

@@ -18,7 +18,8 @@ LAYOUT_HEAD_SEQ = 1   # [Hl, N, d]
 
 EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",
            "ulysses_pack_qkv", "ulysses_unpack_qkv", "ulysses_pack_rev_qkv", "ulysses_unpack_rev_qkv",
-           "ulysses_xattn_fwd", "ulysses_xattn_bwd_workspace_bytes", "ulysses_xattn_bwd",
+           "ulysses_xattn_fwd_workspace_bytes", "ulysses_xattn_fwd", "ulysses_xattn_bwd_workspace_bytes",
+           "ulysses_xattn_bwd",
            "ulysses_sparse_attn_fwd", "ulysses_sparse_attn_bwd_workspace_bytes", "ulysses_sparse_attn_bwd",
            "ulysses_probe_mfma",
            "ulysses_attn_fwd", "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd", "ulysses_attn_bwd_stage",
@@ -58,7 +59,9 @@ def load(path: str | None = None):
     lib.ulysses_attn_bwd_workspace_bytes.restype = sz
     lib.ulysses_attn_bwd.argtypes = [vp] * 10 + [sz, i64, ci, ci, cf, ci, ci, vp]
     lib.ulysses_attn_bwd_stage.argtypes = [ci] + [vp] * 10 + [sz, i64, ci, ci, cf, ci, ci, vp]
-    lib.ulysses_xattn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, ci, ci, cf, ci, vp]
+    lib.ulysses_xattn_fwd_workspace_bytes.argtypes = [i64, i64, ci, ci]
+    lib.ulysses_xattn_fwd_workspace_bytes.restype = sz
+    lib.ulysses_xattn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, sz, i64, i64, ci, ci, cf, ci, vp]
     lib.ulysses_xattn_bwd_workspace_bytes.argtypes = [i64, i64, ci, ci]
     lib.ulysses_xattn_bwd_workspace_bytes.restype = sz
     lib.ulysses_xattn_bwd.argtypes = [vp] * 10 + [sz, i64, i64, ci, ci, cf, ci, vp]
@@ -279,9 +282,12 @@ def ulysses_xattn_fwd(q, k, v, scale: float, layout: int = LAYOUT_SEQ_HEAD):
     Nk = _attn_dims(k, layout)[0]
     o = torch.empty_like(q)
     lse = torch.empty((Hl, Nq), dtype=torch.float32, device=q.device)
+    need = int(load().ulysses_xattn_fwd_workspace_bytes(Nq, Nk, Hl, d))
+    workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
     _check(load().ulysses_xattn_fwd(_dev(q, "xattn_fwd"), _dev(k, "xattn_fwd"), _dev(v, "xattn_fwd"),
-                                    _dev(o, "xattn_fwd"), _dev(lse, "xattn_fwd"), Nq, Nk, Hl, d, scale, layout | elem,
-                                    _stream()), "ulysses_xattn_fwd")
+                                    _dev(o, "xattn_fwd"), _dev(lse, "xattn_fwd"), _dev(workspace, "xattn_fwd"),
+                                    workspace.numel(), Nq, Nk, Hl, d, scale, layout | elem, _stream()),
+           "ulysses_xattn_fwd")
     return o, lse
 
 

@@ -164,8 +164,9 @@ int ulysses_unpack_rev_qkv(const void* const recv[3], void* const y[3], int64_t 
 }
 
 // Shared by self-attention (Nk == N) and cross-attention (causal == 0, Nk keys for N queries).
-static int attn_fwd_checked(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk,
-                            int Hl, int d, float scale, int causal, int layout, void* stream) {
+static int attn_fwd_checked(const void* q, const void* k, const void* v, void* o, float* lse, void* workspace,
+                            size_t workspace_bytes, bool takes_workspace, int64_t N, int64_t Nk, int Hl, int d,
+                            float scale, int causal, int layout, void* stream) {
     uint64_t tb, tbk;
     int rc = check_attn_common(N, Hl, d, layout, &tb);
     if (rc == ULY_OK) rc = check_attn_common(Nk, Hl, d, layout, &tbk);
@@ -174,24 +175,36 @@ static int attn_fwd_checked(const void* q, const void* k, const void* v, void* o
     if (N == 0) return ULY_OK;
     if (Nk == 0) return ULY_ERR_SHAPE;                                             // softmax over no keys
     if (!q || !k || !v || !o || !lse) return ULY_ERR_NULL;
+    const size_t need = takes_workspace ? ulysses_xattn_fwd_workspace_bytes(N, Nk, Hl, d) : 0;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return ULY_ERR_WORKSPACE;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse)) return ULY_ERR_ALIGN;
+    if (need > 0 && misaligned(workspace)) return ULY_ERR_ALIGN;
     const Range in[3] = {{q, tb}, {k, tbk}, {v, tbk}};
-    const Range out[2] = {{o, tb}, {lse, (uint64_t)N * Hl * 4u}};
+    const Range out[3] = {{o, tb}, {lse, (uint64_t)N * Hl * 4u}, {need > 0 ? workspace : nullptr, need}};
     if (any_alias(in, out)) return ULY_ERR_ALIAS;
     const int lay = layout & ~ULY_ELEM_F16;
     return (layout & ULY_ELEM_F16 ? uly::f16::attn_fwd_launch : uly::bf16::attn_fwd_launch)(
-        q, k, v, o, lse, N, Nk, Hl, d, scale, causal != 0, uly::strides_for(lay, N, Hl, d),
-        uly::strides_for(lay, Nk, Hl, d), stream);
+        q, k, v, o, lse, need > 0 ? (float*)workspace : nullptr, N, Nk, Hl, d, scale, causal != 0,
+        uly::strides_for(lay, N, Hl, d), uly::strides_for(lay, Nk, Hl, d), stream);
 }
 
 int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int Hl, int d,
                      float scale, int causal, int layout, void* stream) {
-    return attn_fwd_checked(q, k, v, o, lse, N, N, Hl, d, scale, causal, layout, stream);
+    return attn_fwd_checked(q, k, v, o, lse, nullptr, 0, false, N, N, Hl, d, scale, causal, layout, stream);
 }
 
-int ulysses_xattn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t Nq, int64_t Nk,
-                      int Hl, int d, float scale, int layout, void* stream) {
-    return attn_fwd_checked(q, k, v, o, lse, Nq, Nk, Hl, d, scale, 0, layout, stream);
+size_t ulysses_xattn_fwd_workspace_bytes(int64_t Nq, int64_t Nk, int Hl, int d) {
+    uint64_t tb;
+    if (Nq <= 0 || Nk <= 0 || check_attn_common(Nq, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK ||
+        check_attn_common(Nk, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK)
+        return 0;
+    return (size_t)uly::bf16::attn_fwd_cut_workspace_floats(Nq, Nk, Hl, d) * sizeof(float);
+}
+
+int ulysses_xattn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, void* workspace,
+                      size_t workspace_bytes, int64_t Nq, int64_t Nk, int Hl, int d, float scale, int layout,
+                      void* stream) {
+    return attn_fwd_checked(q, k, v, o, lse, workspace, workspace_bytes, true, Nq, Nk, Hl, d, scale, 0, layout, stream);
 }
 
 size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
@@ -201,14 +214,17 @@ size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
 }
 
 size_t ulysses_xattn_bwd_workspace_bytes(int64_t Nq, int64_t Nk, int Hl, int d) {
-    (void)Nk;
-    return ulysses_attn_bwd_workspace_bytes(Nq, Hl, d);
+    uint64_t tb;
+    if (Nq <= 0 || Nk <= 0 || check_attn_common(Nq, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK ||
+        check_attn_common(Nk, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK)
+        return ulysses_attn_bwd_workspace_bytes(Nq, Hl, d);
+    return (size_t)uly::bf16::attn_bwd_cut_workspace_floats(Nq, Nk, Hl, d) * sizeof(float);
 }
 
 static int attn_bwd_checked(int stage_mask, const void* q, const void* k, const void* v, const void* o,
                             const void* dout, const float* lse, void* dq, void* dk, void* dv, void* workspace,
                             size_t workspace_bytes, int64_t N, int64_t Nk, int Hl, int d, float scale, int causal,
-                            int layout, void* stream) {
+                            int may_cut, int layout, void* stream) {
     uint64_t tb, tbk;
     int rc = check_attn_common(N, Hl, d, layout, &tb);
     if (rc == ULY_OK) rc = check_attn_common(Nk, Hl, d, layout, &tbk);
@@ -217,7 +233,7 @@ static int attn_bwd_checked(int stage_mask, const void* q, const void* k, const 
     if (N == 0 && Nk == 0) return ULY_OK;
     if (N == 0 || Nk == 0) return ULY_ERR_SHAPE;          // gradients of an empty side are not defined here
     if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv) return ULY_ERR_NULL;
-    const size_t need = ulysses_attn_bwd_workspace_bytes(N, Hl, d);
+    const size_t need = may_cut ? ulysses_xattn_bwd_workspace_bytes(N, Nk, Hl, d) : ulysses_attn_bwd_workspace_bytes(N, Hl, d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return ULY_ERR_WORKSPACE;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(dout) || misaligned(lse) ||
         misaligned(dq) || misaligned(dk) || misaligned(dv) || misaligned(workspace))
@@ -228,7 +244,7 @@ static int attn_bwd_checked(int stage_mask, const void* q, const void* k, const 
     if (any_alias(in, out)) return ULY_ERR_ALIAS;
     const int lay = layout & ~ULY_ELEM_F16;
     return (layout & ULY_ELEM_F16 ? uly::f16::attn_bwd_launch : uly::bf16::attn_bwd_launch)(
-        stage_mask, q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, N, Nk, Hl, d, scale, causal != 0,
+        stage_mask, q, k, v, o, dout, lse, dq, dk, dv, (float*)workspace, N, Nk, Hl, d, scale, causal != 0, may_cut,
         uly::strides_for(lay, N, Hl, d), uly::strides_for(lay, Nk, Hl, d), stream);
 }
 
@@ -236,7 +252,7 @@ int ulysses_attn_bwd(const void* q, const void* k, const void* v, const void* o,
                      void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int64_t N, int Hl,
                      int d, float scale, int causal, int layout, void* stream) {
     return attn_bwd_checked(7, q, k, v, o, dout, lse, dq, dk, dv, workspace, workspace_bytes, N, N, Hl, d, scale,
-                            causal, layout, stream);
+                            causal, /*may_cut=*/0, layout, stream);
 }
 
 int ulysses_attn_bwd_stage(int stage, const void* q, const void* k, const void* v, const void* o, const void* dout,
@@ -245,14 +261,14 @@ int ulysses_attn_bwd_stage(int stage, const void* q, const void* k, const void* 
     if (stage != ULY_BWD_STAGE_DELTA && stage != ULY_BWD_STAGE_DKV && stage != ULY_BWD_STAGE_DQ)
         return ULY_ERR_UNSUPPORTED;
     return attn_bwd_checked(1 << stage, q, k, v, o, dout, lse, dq, dk, dv, workspace, workspace_bytes, N, N, Hl, d,
-                            scale, causal, layout, stream);
+                            scale, causal, /*may_cut=*/0, layout, stream);
 }
 
 int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
                       void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int64_t Nq, int64_t Nk,
                       int Hl, int d, float scale, int layout, void* stream) {
     return attn_bwd_checked(7, q, k, v, o, dout, lse, dq, dk, dv, workspace, workspace_bytes, Nq, Nk, Hl, d, scale, 0,
-                            layout, stream);
+                            /*may_cut=*/1, layout, stream);
 }
 
 int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* row_ptr,

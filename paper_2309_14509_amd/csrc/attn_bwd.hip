@@ -71,13 +71,15 @@ constexpr int kDqRing = 4;
 // the block rows listed for its block column (col_ptr, row_idx: ascending, diagonal first).
 constexpr int kSparseBlockBwd = 256;
 
-template <int D, bool CAUSAL, bool SPARSE = false>
+template <int D, bool CAUSAL, bool SPARSE = false, bool PLAN = false>
 __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     const e16* __restrict__ Q, const e16* __restrict__ K, const e16* __restrict__ V, const e16* __restrict__ dO,
     const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, e16* __restrict__ dQ, int N,
     int Nk, int n_qtiles, int64_t row_stride, int64_t head_stride, int64_t kv_head_stride, float scale,
-    const int* __restrict__ row_ptr, const int* __restrict__ col_idx) {
+    const int* __restrict__ row_ptr, const int* __restrict__ col_idx, const int4* __restrict__ plan,
+    float* __restrict__ partial, int slots_per_head) {
     static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
+    static_assert(!PLAN || (!CAUSAL && !SPARSE), "only unmasked query tiles are cut into work items");
     constexpr int NT = D / 16, NCB = D / 32;
     constexpr int TILE = kDqBK * D;
     constexpr int TB = TILE * 2;
@@ -94,9 +96,21 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     // upwards from the start of the sequence and those of the second downwards from its diagonal: at
     // any moment all workgroups that started together read one of only two key blocks, which keeps
     // the K/V stream in the L2 caches instead of re-fetching it per workgroup.
+    // PLAN (unmasked attention with few query tiles): grid (heads, work items); an item is a query tile
+    // and a range of its key blocks, the items of a tile write fp32 partial sums (see the plan kernels).
     const int n_pairs = (CAUSAL && !SPARSE) ? (n_qtiles + 1) / 2 : n_qtiles;
-    const int head = blockIdx.x / n_pairs;
-    const int pr = blockIdx.x - head * n_pairs;
+    const int head = PLAN ? blockIdx.x : blockIdx.x / n_pairs;
+    int pr = blockIdx.x - head * n_pairs;
+    int p_off = 0, p_end = 0, slot = -1;
+    if (PLAN) {
+        const int4 hdr = plan[0];
+        if ((int)blockIdx.y >= hdr.x) return;
+        const int4 it = plan[1 + blockIdx.y];
+        pr = it.x;
+        p_off = it.y;
+        p_end = it.z;
+        slot = (int)blockIdx.y < hdr.y ? (int)blockIdx.y : -1;
+    }
     const int64_t hoff = (int64_t)head * head_stride;
     // N queries, Nk keys (Nk = N for self-attention); K and V may have their own head stride
     const e16* Kh = K + (int64_t)head * kv_head_stride;
@@ -154,10 +168,14 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     }
     // block at walk position p; positions past the end re-read the last one (their tiles are never used)
     auto blk = [&](int p) __attribute__((always_inline)) {
+        if (PLAN) p += p_off;
         p = p < cnt ? p : cnt - 1;
         if (SPARSE) return p < n_off ? BPS * col_idx[sp0 + p / BPS] + p % BPS : diag0 + (p - n_off);
         return dir > 0 ? p : cnt - 1 - p;
     };
+    // positions this workgroup processes; the last four run the masking variant, which masks nothing
+    // unless they are the end of the sequence
+    const int walk = PLAN ? p_end - p_off : cnt;
 #pragma unroll
     for (int i = 0; i < kDqRing; ++i) load_tile(i, blk(i));
 
@@ -340,7 +358,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         iteration(Masked{}, S3{}, S1{}, 3); settle();
         p = 4;
     }
-    const int plain_end = dir > 0 ? cnt - 4 : cnt;
+    const int plain_end = dir > 0 ? walk - 4 : walk;
     for (; p < plain_end; p += 4) {
         iteration(Plain{}, S0{}, S2{}, p);
         iteration(Plain{}, S1{}, S3{}, p + 1);
@@ -362,7 +380,19 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     for (int cb = 0; cb < NCB; ++cb) lds_tie(acc[cb]);
     __builtin_amdgcn_sched_barrier(0);
 
-    if (q_row < N) {
+    if (PLAN && slot >= 0) {
+        // one of several items of this query tile: fp32 partial sums [slot][query][channel]
+        float* prow = partial + ((int64_t)head * slots_per_head + slot) * (kDqBQ * D) + (wave * 32 + ln) * D;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                f32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = acc[cb][4 * rq + e] * scale;
+                *reinterpret_cast<f32x4*>(prow + 32 * cb + 8 * rq + 4 * g) = w;
+            }
+    } else if (q_row < N) {
         e16* orow = dQ + hoff + (int64_t)q_row * row_stride;
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
@@ -395,7 +425,7 @@ constexpr int kDkvBK = 128;   // keys per workgroup
 constexpr int kDkvBQ = 32;    // queries per LDS tile
 constexpr int kDkvRing = 4;   // LDS tiles per tensor
 
-template <int D, bool CAUSAL, bool SPARSE = false>
+template <int D, bool CAUSAL, bool SPARSE = false, bool PLAN = SPARSE>
 __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     const e16* __restrict__ Q, const e16* __restrict__ K, const e16* __restrict__ V, const e16* __restrict__ dO,
     const float* __restrict__ LSE2, const float* __restrict__ DELTA, int64_t ws_stride, e16* __restrict__ dK,
@@ -403,6 +433,8 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     int64_t kv_head_stride, float scale, const int* __restrict__ col_ptr, const int* __restrict__ row_idx,
     const int4* __restrict__ plan, float* __restrict__ partial, int slots_per_head) {
     static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
+    static_assert(!SPARSE || PLAN, "block columns of a pattern are walked through the work plan");
+    static_assert(!(PLAN && CAUSAL && !SPARSE), "dense causal key tiles are paired, not planned");
     constexpr int NT = D / 16, NCB = D / 32;
     constexpr int TILE = kDkvBQ * D;            // elements per tile
     constexpr int TB = TILE * 2;                // bytes per tile
@@ -422,13 +454,13 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     // the first tile downwards from the end of the sequence and those of the second upwards from its
     // diagonal: at any moment all workgroups that started together read one of only two query
     // blocks, which keeps the Q/dO stream in the L2 caches instead of re-fetching it per workgroup.
-    // SPARSE: grid (heads, work items); an item of the plan is a key tile and a range of walk
-    // positions of its block column (long columns are cut into several items, see the plan kernel).
+    // PLAN: grid (heads, work items); an item of the plan is a key tile and a range of the walk
+    // positions of its column (long columns are cut into several items, see the plan kernels).
     const int n_pairs = (CAUSAL && !SPARSE) ? (n_ktiles + 1) / 2 : n_ktiles;
-    const int head = SPARSE ? blockIdx.x : blockIdx.x / n_pairs;
+    const int head = PLAN ? blockIdx.x : blockIdx.x / n_pairs;
     int pr = blockIdx.x - head * n_pairs;
     int p_off = 0, p_end = 0, slot = -1;
-    if (SPARSE) {
+    if (PLAN) {
         const int4 hdr = plan[0];                 // {items, items that write partial sums, ..}
         if ((int)blockIdx.y >= hdr.x) return;     // the grid is an upper bound on the number of items
         const int4 it = plan[1 + blockIdx.y];     // {key tile, first walk position, end, -}
@@ -520,12 +552,12 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     }
     // block at walk position p; positions past the end re-read the last one (their tiles are never used)
     auto blk = [&](int p) __attribute__((always_inline)) {
-        if (SPARSE) p += p_off;
+        if (PLAN) p += p_off;
         p = p < cnt ? p : cnt - 1;
         if (SPARSE) return p < n_diag ? b0 + p : BPS * row_idx[sp0 + 1 + (p - n_diag) / BPS] + (p - n_diag) % BPS;
         return dir > 0 ? b0 + p : nblk4 - 1 - p;
     };
-    const int walk = SPARSE ? p_end - p_off : cnt;            // positions this workgroup processes
+    const int walk = PLAN ? p_end - p_off : cnt;              // positions this workgroup processes
 #pragma unroll
     for (int i = 0; i < kDkvRing; ++i) load_tile(i, blk(i));
 
@@ -795,7 +827,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     for (int cb = 0; cb < NCB; ++cb) lds_tie(dk_acc[cb], dv_acc[cb]);
     __builtin_amdgcn_sched_barrier(0);
 
-    if (SPARSE && slot >= 0) {
+    if (PLAN && slot >= 0) {
         // one of several items of this key tile: fp32 partial sums [slot][dK, dV][key][channel]
         float* prow = partial + ((int64_t)head * slots_per_head + slot) * (2 * kDkvBK * D) + (wave * 32 + ln) * D;
 #pragma unroll
@@ -930,36 +962,69 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_dkv_plan_kernel(const int
     }
 }
 
-// Adds the partial sums of the cut block columns (fixed order: deterministic) and writes dK, dV.
+// The same kind of plan for unmasked attention when one side has few tiles: every tile (key tile of
+// dK/dV, query tile of dQ) walks cnt blocks of the other side and is cut into `pieces` items of `len`
+// blocks, so plan and reduce table are closed forms.
+__global__ __launch_bounds__(256) void dense_plan_kernel(int n_tiles, int cnt, int pieces, int len,
+                                                         int4* __restrict__ plan, int2* __restrict__ red) {
+    const int s = blockIdx.x * 256 + threadIdx.x;
+    const int items = n_tiles * pieces;
+    if (s == 0) plan[0] = make_int4(items, pieces > 1 ? items : 0, len, 0);
+    if (s >= items) return;
+    const int t = s / pieces, i = s - t * pieces;
+    plan[1 + s] = make_int4(t, i * len, (i + 1) * len < cnt ? (i + 1) * len : cnt, 0);
+    if (i == 0) red[t] = pieces > 1 ? make_int2(s, pieces) : make_int2(-1, 1);
+}
+
+// How n_tiles tiles that walk cnt blocks each are cut: only when the tiles alone would leave most of
+// the 256 CUs idle and the walk is long enough to share out.
+struct DenseCut {
+    int pieces, len;
+};
+inline DenseCut dense_cut(int64_t n_tiles, int64_t cnt, int Hl) {
+    DenseCut c{1, (int)cnt};
+    if (n_tiles * Hl >= 512 || cnt < 2 * kPlanMinLen) return c;
+    int64_t want = (kPlanTarget + n_tiles * Hl - 1) / (n_tiles * Hl);        // pieces that give about kPlanTarget items
+    const int64_t most = cnt / kPlanMinLen;
+    want = want < most ? want : most;
+    if (want < 2) return c;
+    const int64_t len = (((cnt + want - 1) / want) + 3) & ~(int64_t)3;
+    c.len = (int)len;
+    c.pieces = (int)((cnt + len - 1) / len);
+    return c;
+}
+
+// Adds the partial sums of the cut tiles (fixed order: deterministic) and writes the NTENS outputs
+// (dK and dV of a key tile, or dQ of a query tile; 128 rows per tile either way).
 // Grid (any, heads): the workgroups of a head share out (cut item, 1024-float chunk) tasks; the task of
-// a column's first item does the column, the others are skipped.
+// a tile's first item does the tile, the others are skipped.
 constexpr int kReduceBlocks = 256;
-template <int D>
-__global__ __launch_bounds__(256) void sparse_dkv_reduce_kernel(const int4* __restrict__ plan,
-                                                                const int2* __restrict__ red,
-                                                                const float* __restrict__ partial, int slots_per_head,
-                                                                e16* __restrict__ dK, e16* __restrict__ dV, int Nk,
-                                                                int64_t row_stride, int64_t kv_head_stride) {
-    constexpr int PER = kDkvBK * D;                       // floats per tensor and slot
-    constexpr int CH = 2 * PER / 1024;                    // chunks per slot
+template <int D, int NTENS>
+__global__ __launch_bounds__(256) void partial_reduce_kernel(const int4* __restrict__ plan, const int2* __restrict__ red,
+                                                             const float* __restrict__ partial, int slots_per_head,
+                                                             e16* __restrict__ out0, e16* __restrict__ out1, int n_rows,
+                                                             int64_t row_stride, int64_t head_stride) {
+    constexpr int ROWS = 128;
+    constexpr int PER = ROWS * D;                         // floats per tensor and slot
+    constexpr int CH = NTENS * PER / 1024;                // chunks per slot
     const int head = blockIdx.y;
     const int n_cut = plan[0].y;
     for (int t = blockIdx.x; t < n_cut * CH; t += gridDim.x) {
         const int s = t / CH, e = (t % CH) * 1024 + threadIdx.x * 4;
         const int4 it = plan[1 + s];
-        if (it.y != 0) continue;                          // not the first item of its column
-        const int kt = it.x, n = red[kt].y;
-        const float* base = partial + ((int64_t)head * slots_per_head + s) * (2 * PER) + e;
+        if (it.y != 0) continue;                          // not the first item of its tile
+        const int tile = it.x, n = red[tile].y;
+        const float* base = partial + ((int64_t)head * slots_per_head + s) * (NTENS * PER) + e;
         f32x4 acc = *reinterpret_cast<const f32x4*>(base);
 #pragma unroll 4
-        for (int i = 1; i < n; ++i) acc += *reinterpret_cast<const f32x4*>(base + (int64_t)i * (2 * PER));
-        const int which = e / PER, key = (e % PER) / D, ch = e % D;
-        const int j = kt * kDkvBK + key;
-        if (j >= Nk) continue;
+        for (int i = 1; i < n; ++i) acc += *reinterpret_cast<const f32x4*>(base + (int64_t)i * (NTENS * PER));
+        const int which = e / PER, row = (e % PER) / D, ch = e % D;
+        const int j = tile * ROWS + row;
+        if (j >= n_rows) continue;
         e16x4 w;
 #pragma unroll
         for (int c = 0; c < 4; ++c) w[c] = (e16)acc[c];
-        e16* dst = (which ? dV : dK) + (int64_t)head * kv_head_stride + (int64_t)j * row_stride + ch;
+        e16* dst = (which ? out1 : out0) + (int64_t)head * head_stride + (int64_t)j * row_stride + ch;
         *reinterpret_cast<e16x4*>(dst) = w;
     }
 }
@@ -988,16 +1053,55 @@ inline SparseWorkspace sparse_workspace(int64_t N, int Hl, int d) {
     return w;
 }
 
+// Workspace of the backward of unmasked attention whose tiles may be cut (cross-attention entry
+// points): the statistics, then plan, reduce table and partial sums for dK/dV and for dQ (a side that
+// is not cut takes no space).
+struct CutWorkspace {
+    DenseCut kv, q;                       // how key tiles (dK/dV) and query tiles (dQ) are cut
+    int64_t kv_items, q_items;
+    int64_t kv_plan_at, kv_red_at, kv_partial_at, q_plan_at, q_red_at, q_partial_at, total;
+};
+inline CutWorkspace cut_workspace(int64_t N, int64_t Nk, int Hl, int d) {
+    const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (Nk + kDkvBK - 1) / kDkvBK;
+    const int64_t q_blocks4 = (((N + kDkvBQ - 1) / kDkvBQ) + 3) & ~(int64_t)3;     // walked by a key tile
+    const int64_t k_blocks4 = (((Nk + kDqBK - 1) / kDqBK) + 3) & ~(int64_t)3;      // walked by a query tile
+    auto up = [](int64_t x) { return (x + 63) & ~(int64_t)63; };
+    CutWorkspace w;
+    w.kv = dense_cut(n_ktiles, q_blocks4, Hl);
+    w.q = dense_cut(n_qtiles, k_blocks4, Hl);
+    w.kv_items = n_ktiles * w.kv.pieces;
+    w.q_items = n_qtiles * w.q.pieces;
+    int64_t at = up(2 * stats_stride(N) * Hl);
+    w.kv_plan_at = at;
+    if (w.kv.pieces > 1) at = up(at + 4 * (1 + w.kv_items));
+    w.kv_red_at = at;
+    if (w.kv.pieces > 1) at = up(at + 2 * n_ktiles);
+    w.kv_partial_at = at;
+    if (w.kv.pieces > 1) at = up(at + w.kv_items * Hl * 2 * kDkvBK * d);
+    w.q_plan_at = at;
+    if (w.q.pieces > 1) at = up(at + 4 * (1 + w.q_items));
+    w.q_red_at = at;
+    if (w.q.pieces > 1) at = up(at + 2 * n_qtiles);
+    w.q_partial_at = at;
+    if (w.q.pieces > 1) at = up(at + w.q_items * Hl * kDqBQ * d);
+    w.total = at;
+    return w;
+}
+
 template <int D>
 static int launch_bwd(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
                       const float* lse, void* dq, void* dk, void* dv, float* ws, int64_t N, int64_t Nk, int Hl,
-                      float scale, int causal, TensorStrides st, TensorStrides kv, hipStream_t stream) {
+                      float scale, int causal, bool may_cut, TensorStrides st, TensorStrides kv, hipStream_t stream) {
     const int64_t stride = stats_stride(N);
     float* delta = ws;
     float* lse2 = ws + stride * Hl;
     const int64_t delta_blocks = (stride * Hl * (D / 8) + 255) / 256;
     const int64_t n_qtiles = (N + kDqBQ - 1) / kDqBQ, n_ktiles = (Nk + kDkvBK - 1) / kDkvBK;
     if (delta_blocks > 0x7FFFFFFFll || n_qtiles * Hl > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
+    // unmasked attention with few tiles on one side (the workspace then has room for partial sums)
+    CutWorkspace cw = cut_workspace(N, Nk, Hl, D);
+    if (causal || !may_cut) cw.kv.pieces = cw.q.pieces = 1;
+    if (cw.kv_items > 65535 || cw.q_items > 65535 || Hl > 65535) cw.kv.pieces = cw.q.pieces = 1;     // grid y dimensions
     const e16 *Q = (const e16*)q, *K = (const e16*)k, *V = (const e16*)v, *dO = (const e16*)dout;
     // causal: a workgroup takes a pair of key tiles (query tiles)
     const int64_t n_kwg = causal ? (n_ktiles + 1) / 2 : n_ktiles, n_qwg = causal ? (n_qtiles + 1) / 2 : n_qtiles;
@@ -1013,7 +1117,22 @@ static int launch_bwd(int stage_mask, const void* q, const void* k, const void* 
             attn_bwd_dkv_kernel<D, true><<<gkv, dim3(kDkvThreads), 0, stream>>>(
                 Q, K, V, dO, lse2, delta, stride, (e16*)dk, (e16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
                 kv.head, scale, nullptr, nullptr, nullptr, nullptr, 0);
-        else
+        else if (cw.kv.pieces > 1) {
+            int4* plan = reinterpret_cast<int4*>(ws + cw.kv_plan_at);
+            int2* red = reinterpret_cast<int2*>(ws + cw.kv_red_at);
+            float* partial = ws + cw.kv_partial_at;
+            const int q_blocks4 = (int)((((N + kDkvBQ - 1) / kDkvBQ) + 3) & ~(int64_t)3);
+            dense_plan_kernel<<<dim3((uint32_t)((cw.kv_items + 255) / 256)), dim3(256), 0, stream>>>(
+                (int)n_ktiles, q_blocks4, cw.kv.pieces, cw.kv.len, plan, red);
+            if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+            attn_bwd_dkv_kernel<D, false, false, true>
+                <<<dim3((uint32_t)Hl, (uint32_t)cw.kv_items), dim3(kDkvThreads), 0, stream>>>(
+                    Q, K, V, dO, lse2, delta, stride, (e16*)dk, (e16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
+                    kv.head, scale, nullptr, nullptr, plan, partial, (int)cw.kv_items);
+            if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+            partial_reduce_kernel<D, 2><<<dim3(kReduceBlocks, (uint32_t)Hl), dim3(256), 0, stream>>>(
+                plan, red, partial, (int)cw.kv_items, (e16*)dk, (e16*)dv, (int)Nk, kv.row, kv.head);
+        } else
             attn_bwd_dkv_kernel<D, false><<<gkv, dim3(kDkvThreads), 0, stream>>>(
                 Q, K, V, dO, lse2, delta, stride, (e16*)dk, (e16*)dv, (int)N, (int)Nk, (int)n_ktiles, st.row, st.head,
                 kv.head, scale, nullptr, nullptr, nullptr, nullptr, 0);
@@ -1023,11 +1142,26 @@ static int launch_bwd(int stage_mask, const void* q, const void* k, const void* 
         if (causal)
             attn_bwd_dq_kernel<D, true><<<gq, dim3(kDqThreads), 0, stream>>>(
                 Q, K, V, dO, lse2, delta, stride, (e16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
-                nullptr, nullptr);
-        else
+                nullptr, nullptr, nullptr, nullptr, 0);
+        else if (cw.q.pieces > 1) {
+            int4* plan = reinterpret_cast<int4*>(ws + cw.q_plan_at);
+            int2* red = reinterpret_cast<int2*>(ws + cw.q_red_at);
+            float* partial = ws + cw.q_partial_at;
+            const int k_blocks4 = (int)((((Nk + kDqBK - 1) / kDqBK) + 3) & ~(int64_t)3);
+            dense_plan_kernel<<<dim3((uint32_t)((cw.q_items + 255) / 256)), dim3(256), 0, stream>>>(
+                (int)n_qtiles, k_blocks4, cw.q.pieces, cw.q.len, plan, red);
+            if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+            attn_bwd_dq_kernel<D, false, false, true>
+                <<<dim3((uint32_t)Hl, (uint32_t)cw.q_items), dim3(kDqThreads), 0, stream>>>(
+                    Q, K, V, dO, lse2, delta, stride, (e16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head,
+                    scale, nullptr, nullptr, plan, partial, (int)cw.q_items);
+            if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+            partial_reduce_kernel<D, 1><<<dim3(kReduceBlocks, (uint32_t)Hl), dim3(256), 0, stream>>>(
+                plan, red, partial, (int)cw.q_items, (e16*)dq, nullptr, (int)N, st.row, st.head);
+        } else
             attn_bwd_dq_kernel<D, false><<<gq, dim3(kDqThreads), 0, stream>>>(
                 Q, K, V, dO, lse2, delta, stride, (e16*)dq, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
-                nullptr, nullptr);
+                nullptr, nullptr, nullptr, nullptr, 0);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     }
     return ULY_OK;
@@ -1062,12 +1196,12 @@ static int launch_bwd_sparse(const void* q, const void* k, const void* v, const 
         Q, K, V, dO, lse2, delta, stride, (e16*)dk, (e16*)dv, (int)N, (int)N, (int)n_ktiles, st.row, st.head, st.head,
         scale, col_ptr, row_idx, plan, partial, w.slots_per_head);
     if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
-    sparse_dkv_reduce_kernel<D><<<dim3(kReduceBlocks, (uint32_t)Hl), dim3(256), 0, stream>>>(
+    partial_reduce_kernel<D, 2><<<dim3(kReduceBlocks, (uint32_t)Hl), dim3(256), 0, stream>>>(
         plan, red, partial, w.slots_per_head, (e16*)dk, (e16*)dv, (int)N, st.row, st.head);
     if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     attn_bwd_dq_kernel<D, true, true><<<dim3((uint32_t)(n_qtiles * Hl)), dim3(kDqThreads), 0, stream>>>(
         Q, K, V, dO, lse2, delta, stride, (e16*)dq, (int)N, (int)N, (int)n_qtiles, st.row, st.head, st.head, scale,
-        row_ptr, col_idx);
+        row_ptr, col_idx, nullptr, nullptr, 0);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 
@@ -1085,14 +1219,16 @@ int attn_bwd_sparse_launch(const void* q, const void* k, const void* v, const vo
 int64_t attn_bwd_workspace_floats(int64_t N, int Hl) { return 2 * stats_stride(N) * Hl; }
 int64_t attn_bwd_sparse_workspace_floats(int64_t N, int Hl, int d) { return sparse_workspace(N, Hl, d).total; }
 
+int64_t attn_bwd_cut_workspace_floats(int64_t N, int64_t Nk, int Hl, int d) { return cut_workspace(N, Nk, Hl, d).total; }
+
 int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
                     const float* lse, void* dq, void* dk, void* dv, float* ws, int64_t N, int64_t Nk, int Hl, int d,
-                    float scale, int causal, TensorStrides st, TensorStrides kv, void* stream) {
+                    float scale, int causal, int may_cut, TensorStrides st, TensorStrides kv, void* stream) {
     if (d == 128)
-        return launch_bwd<128>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Nk, Hl, scale, causal, st, kv,
-                               (hipStream_t)stream);
-    return launch_bwd<64>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Nk, Hl, scale, causal, st, kv,
-                          (hipStream_t)stream);
+        return launch_bwd<128>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Nk, Hl, scale, causal, may_cut != 0,
+                               st, kv, (hipStream_t)stream);
+    return launch_bwd<64>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Nk, Hl, scale, causal, may_cut != 0, st,
+                          kv, (hipStream_t)stream);
 }
 
 }  // namespace ULY_ELEM_NS

@@ -36,14 +36,22 @@ constexpr bool kFwdPair = false;
 constexpr int kSparseBlock = 256;
 static_assert(kFwdBQ == kSparseBlock && kSparseBlock % kFwdBK == 0, "a query tile must be one sparse block row");
 
-template <int D, bool CAUSAL, bool SPARSE = false>
+// CUT (unmasked attention with few query tiles): grid (heads, query tiles x pieces); a workgroup
+// takes `cut_len` key tiles of its query tile and writes, instead of O and LSE, what the combine kernel
+// needs to merge the pieces: the unnormalised fp32 accumulators and, per query, the maximum the
+// exponentials were taken against and the sum of the exponentials.
+//   part_o [head][item][256 queries][D] fp32,   part_ml [head][item][256 queries][2] fp32 (max, sum)
+template <int D, bool CAUSAL, bool SPARSE = false, bool CUT = false>
 __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __restrict__ Q, const e16* __restrict__ K,
                                                                    const e16* __restrict__ V, e16* __restrict__ O,
                                                                    float* __restrict__ LSE, int N, int Nk, int n_qtiles,
                                                                    int64_t row_stride, int64_t head_stride, int64_t kv_head_stride,
                                                                    float scale, const int* __restrict__ row_ptr,
-                                                                   const int* __restrict__ col_idx) {
+                                                                   const int* __restrict__ col_idx, int cut_pieces,
+                                                                   int cut_len, float* __restrict__ part_o,
+                                                                   float* __restrict__ part_ml) {
     static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
+    static_assert(!CUT || (!CAUSAL && !SPARSE), "only unmasked query tiles are cut into work items");
     constexpr int NT = D / 16;              // contraction steps over the head dim
     constexpr int NCB = D / 32;             // 32-channel blocks of the output
     constexpr int TILE = kFwdBK * D;        // elements per LDS tile
@@ -71,8 +79,9 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
     // any moment all workgroups that started together read one of only two key tiles, which keeps
     // the K/V stream in the L2 caches instead of re-fetching it per workgroup.
     const int n_pairs = (CAUSAL && kFwdPair && !SPARSE) ? (n_qtiles + 1) / 2 : n_qtiles;
-    const int head = blockIdx.x / n_pairs;
-    const int pr = blockIdx.x - head * n_pairs;
+    const int head = CUT ? blockIdx.x : blockIdx.x / n_pairs;
+    const int pr = CUT ? blockIdx.y / cut_pieces : blockIdx.x - head * n_pairs;
+    const int t_off = CUT ? (blockIdx.y - pr * cut_pieces) * cut_len : 0;      // first key tile of this piece
     const int64_t hoff = (int64_t)head * head_stride;
     const e16* Qh = Q + hoff;
     // N queries attend to Nk keys (Nk = N for self-attention); K and V may have their own head stride
@@ -124,8 +133,10 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
         // every listed block but the last (the diagonal one) is entirely visible: TPB tiles each
         n_kt = TPB * (row_ptr[qt + 1] - sp0 - 1) + (k_end - q0 + kFwdBK - 1) / kFwdBK;
     }
+    if (CUT) n_kt = n_kt - t_off < cut_len ? n_kt - t_off : cut_len;
     auto tile_of = [&](int pos) __attribute__((always_inline)) {
         if (SPARSE) return TPB * col_idx[sp0 + pos / TPB] + pos % TPB;
+        if (CUT) return t_off + pos;
         return dir > 0 ? pos : n_kt - 1 - pos;
     };
     load_tile(K0, V0, tile_of(0));
@@ -352,7 +363,24 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
     // ---- epilogue: normalise, store O (element type) and LSE (natural log)
     const float l_tot = xhalf_sum(l_run);
     const float inv = 1.f / l_tot;
-    if (q_row < N) {
+    if (CUT) {
+        const int64_t slot = (int64_t)head * gridDim.y + blockIdx.y;
+        const int row = wave * 32 + ln;
+        float* prow = part_o + (slot * kFwdBQ + row) * D;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                f32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = oacc[cb][4 * rq + e];
+                *reinterpret_cast<f32x4*>(prow + 32 * cb + 8 * rq + 4 * g) = w;
+            }
+        if (g == 0) {
+            part_ml[(slot * kFwdBQ + row) * 2] = m_used;
+            part_ml[(slot * kFwdBQ + row) * 2 + 1] = l_tot;
+        }
+    } else if (q_row < N) {
         e16* orow = O + hoff + (int64_t)q_row * row_stride;
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
@@ -369,21 +397,99 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
     }   // query tiles of this workgroup
 }
 
+// Merges the pieces of the cut query tiles: with m = max_i m_i and w_i = exp(scale (m_i - m)),
+//   l = sum_i w_i l_i,   O = sum_i w_i O_i / l,   LSE = scale m + log l        (pieces in a fixed order).
+// Grid (query tiles x 32, heads): a workgroup merges 8 query rows, 32 lanes per row (D / 32 floats each).
 template <int D>
-static int launch_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
-                      float scale, int causal, TensorStrides st, TensorStrides kv, hipStream_t stream) {
+__global__ __launch_bounds__(256) void attn_fwd_combine_kernel(const float* __restrict__ part_o,
+                                                               const float* __restrict__ part_ml, int pieces,
+                                                               e16* __restrict__ O, float* __restrict__ LSE, int N,
+                                                               int64_t row_stride, int64_t head_stride, float scale) {
+    constexpr int PER = D / 32;                                       // floats per lane and row
+    constexpr int GROUPS = kFwdBQ / 8;                                // row groups per query tile
+    const int qt = blockIdx.x / GROUPS, head = blockIdx.y;
+    const int64_t slot0 = ((int64_t)head * (gridDim.x / GROUPS) + qt) * pieces;   // the pieces of a tile are consecutive items
+    const float sl2 = scale * kLog2e;
+    {
+        const int r = (blockIdx.x % GROUPS) * 8 + threadIdx.x / 32;
+        const int q_row = qt * kFwdBQ + r;
+        if (q_row >= N) return;
+        const int c0 = (threadIdx.x % 32) * PER;
+        float m = -INFINITY;
+        for (int i = 0; i < pieces; ++i) m = fmaxf(m, part_ml[((slot0 + i) * kFwdBQ + r) * 2]);
+        float l = 0.f, acc[PER];
+#pragma unroll
+        for (int c = 0; c < PER; ++c) acc[c] = 0.f;
+        for (int i = 0; i < pieces; ++i) {
+            const float* ml = part_ml + ((slot0 + i) * kFwdBQ + r) * 2;
+            const float w = fast_exp2((ml[0] - m) * sl2);
+            l += w * ml[1];
+            const float* src = part_o + ((slot0 + i) * kFwdBQ + r) * D + c0;
+#pragma unroll
+            for (int c = 0; c < PER; ++c) acc[c] += w * src[c];
+        }
+        const float inv = 1.f / l;
+        e16* dst = O + (int64_t)head * head_stride + (int64_t)q_row * row_stride + c0;
+#pragma unroll
+        for (int c = 0; c < PER; ++c) dst[c] = (e16)(acc[c] * inv);
+        if (threadIdx.x % 32 == 0) LSE[(int64_t)head * N + q_row] = m * scale + __logf(l);
+    }
+}
+
+// How the key tiles of unmasked attention with few query tiles are cut (the forward runs two
+// workgroups per CU: 512 places).  Pieces of at least 16 tiles (1024 keys).
+struct FwdCut {
+    int pieces, len;
+};
+inline FwdCut fwd_cut(int64_t n_qtiles, int64_t n_kt, int Hl) {
+    FwdCut c{1, (int)n_kt};
+    if (n_qtiles * Hl >= 512 || n_kt < 32) return c;
+    int64_t want = (1024 + n_qtiles * Hl - 1) / (n_qtiles * Hl);
+    const int64_t most = n_kt / 16;
+    want = want < most ? want : most;
+    if (want < 2) return c;
+    const int64_t len = (((n_kt + want - 1) / want) + 1) & ~(int64_t)1;
+    c.len = (int)len;
+    c.pieces = (int)((n_kt + len - 1) / len);
+    return c;
+}
+inline int64_t fwd_cut_workspace_floats_of(int64_t N, int64_t Nk, int Hl, int d) {
+    const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ, n_kt = (Nk + kFwdBK - 1) / kFwdBK;
+    const FwdCut c = fwd_cut(n_qtiles, n_kt, Hl);
+    if (c.pieces < 2) return 0;
+    return n_qtiles * c.pieces * Hl * (int64_t)kFwdBQ * (d + 2);
+}
+
+template <int D>
+static int launch_fwd(const void* q, const void* k, const void* v, void* o, float* lse, float* ws, int64_t N,
+                      int64_t Nk, int Hl, float scale, int causal, TensorStrides st, TensorStrides kv,
+                      hipStream_t stream) {
     const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ;
+    // unmasked attention with few query tiles and a workspace for the pieces
+    const FwdCut cut = (!causal && ws) ? fwd_cut(n_qtiles, (Nk + kFwdBK - 1) / kFwdBK, Hl) : FwdCut{1, 0};
+    if (cut.pieces > 1 && n_qtiles * cut.pieces <= 65535 && Hl <= 65535) {
+        const int64_t items = n_qtiles * cut.pieces;
+        float* part_o = ws;
+        float* part_ml = ws + items * Hl * (int64_t)kFwdBQ * D;
+        attn_fwd_kernel<D, false, false, true><<<dim3((uint32_t)Hl, (uint32_t)items), dim3(kFwdThreads), 0, stream>>>(
+            (const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
+            kv.head, scale, nullptr, nullptr, cut.pieces, cut.len, part_o, part_ml);
+        if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+        attn_fwd_combine_kernel<D><<<dim3((uint32_t)(n_qtiles * (kFwdBQ / 8)), (uint32_t)Hl), dim3(256), 0, stream>>>(
+            part_o, part_ml, cut.pieces, (e16*)o, lse, (int)N, st.row, st.head, scale);
+        return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
+    }
     const int64_t blocks = ((causal && kFwdPair) ? (n_qtiles + 1) / 2 : n_qtiles) * Hl;    // causal: pairs of query tiles
     if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     dim3 grid((uint32_t)blocks), block(kFwdThreads);
     if (causal)
         attn_fwd_kernel<D, true><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
                                                              lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
-                                                             nullptr, nullptr);
+                                                             nullptr, nullptr, 1, 0, nullptr, nullptr);
     else
         attn_fwd_kernel<D, false><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v,
                                                               (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
-                                                              kv.head, scale, nullptr, nullptr);
+                                                              kv.head, scale, nullptr, nullptr, 1, 0, nullptr, nullptr);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 
@@ -397,18 +503,22 @@ int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o,
     if (d == 128)
         attn_fwd_kernel<128, true, true><<<grid, block, 0, s>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
                                                                 lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head,
-                                                                st.head, scale, row_ptr, col_idx);
+                                                                st.head, scale, row_ptr, col_idx, 1, 0, nullptr, nullptr);
     else
         attn_fwd_kernel<64, true, true><<<grid, block, 0, s>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
                                                                lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head,
-                                                               st.head, scale, row_ptr, col_idx);
+                                                               st.head, scale, row_ptr, col_idx, 1, 0, nullptr, nullptr);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 
-int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
-                    int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream) {
-    if (d == 128) return launch_fwd<128>(q, k, v, o, lse, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
-    return launch_fwd<64>(q, k, v, o, lse, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
+int64_t attn_fwd_cut_workspace_floats(int64_t N, int64_t Nk, int Hl, int d) {
+    return fwd_cut_workspace_floats_of(N, Nk, Hl, d);
+}
+
+int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, float* ws, int64_t N, int64_t Nk,
+                    int Hl, int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream) {
+    if (d == 128) return launch_fwd<128>(q, k, v, o, lse, ws, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
+    return launch_fwd<64>(q, k, v, o, lse, ws, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
 }
 
 }  // namespace ULY_ELEM_NS

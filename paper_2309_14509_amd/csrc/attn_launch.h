@@ -5,8 +5,11 @@
 
 // N queries attend to Nk keys/values (Nk = N for self-attention; causal requires Nk = N).  `st` are the
 // strides of the query-side tensors (q, o, dout, dq), `kv` those of k, v, dk, dv.
-int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
-                    int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
+// `ws` (may be null: then nothing is cut): attn_fwd_cut_workspace_floats floats of scratch that let unmasked
+// attention with few query tiles cut the keys of a tile into several work items, merged by a second kernel.
+int64_t attn_fwd_cut_workspace_floats(int64_t N, int64_t Nk, int Hl, int d);
+int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, float* ws, int64_t N, int64_t Nk,
+                    int Hl, int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
 
 // Block-sparse causal forward: keys restricted to the 256-key blocks of a CSR pattern (device arrays).
 int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, const int* row_ptr,
@@ -15,10 +18,16 @@ int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o,
 // floats of scratch the backward kernels need (padded row statistics: delta and lse*log2e); N = queries
 int64_t attn_bwd_workspace_floats(int64_t N, int Hl);
 
-// stage_mask: bit 0 delta, bit 1 dK/dV, bit 2 dQ (kernels run in that order)
+// floats of scratch when unmasked attention may cut its tiles into several work items (may_cut below):
+// the statistics plus work plans and fp32 partial sums; equals attn_bwd_workspace_floats when nothing is cut
+int64_t attn_bwd_cut_workspace_floats(int64_t N, int64_t Nk, int Hl, int d);
+
+// stage_mask: bit 0 delta, bit 1 dK/dV, bit 2 dQ (kernels run in that order).  may_cut: without a mask,
+// when one side has too few tiles to fill the device, its tiles are cut into work items (the workspace
+// must then have attn_bwd_cut_workspace_floats floats).
 int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
                     const float* lse, void* dq, void* dk, void* dv, float* delta, int64_t N, int64_t Nk, int Hl, int d,
-                    float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
+                    float scale, int causal, int may_cut, TensorStrides st, TensorStrides kv, void* stream);
 
 // floats of scratch of the block-sparse backward: the statistics, the dK/dV work plan and the fp32
 // partial sums of block columns that are cut into several work items

@@ -150,9 +150,10 @@ def test_build_scratch_report_parser():
 
 
 def test_cross_attention_validation(lib):
-    f = lambda **kw: lib.ulysses_xattn_fwd(*[{**dict(q=A, k=B, v=C_, o=D_, lse=0x7000000, Nq=128, Nk=96, Hl=2, d=64,
-                                                      scale=0.125, layout=0), **kw}[n]
-                                             for n in ("q", "k", "v", "o", "lse", "Nq", "Nk", "Hl", "d", "scale", "layout")],
+    f = lambda **kw: lib.ulysses_xattn_fwd(*[{**dict(q=A, k=B, v=C_, o=D_, lse=0x7000000, ws=None, wsb=0, Nq=128, Nk=96,
+                                                      Hl=2, d=64, scale=0.125, layout=0), **kw}[n]
+                                             for n in ("q", "k", "v", "o", "lse", "ws", "wsb", "Nq", "Nk", "Hl", "d",
+                                                       "scale", "layout")],
                                            None)
     assert f(q=None) == 1 and f(k=None) == 1
     assert f(Nq=-1) == 2 and f(Nk=-3) == 2 and f(Nk=0) == 2       # no keys: softmax undefined
@@ -160,7 +161,20 @@ def test_cross_attention_validation(lib):
     assert f(d=96) == 3 and f(scale=0.0) == 3 and f(layout=5) == 3
     assert f(v=C_ + 4) == 4
     assert f(o=B + 96 * 2 * 64 * 2 - 32) == 5                      # o overlaps the end of k (sized by Nk)
+    # workspaces: nothing extra while both sides have enough (or too few) tokens to cut; few queries over many
+    # keys take a forward workspace and a larger backward one, bounded whatever the sizes
+    assert lib.ulysses_xattn_fwd_workspace_bytes(128, 96, 2, 64) == 0
     assert lib.ulysses_xattn_bwd_workspace_bytes(128, 96, 2, 64) == lib.ulysses_attn_bwd_workspace_bytes(128, 2, 64)
+    assert lib.ulysses_xattn_fwd_workspace_bytes(1 << 17, 1 << 17, 4, 128) == 0
+    fw = lib.ulysses_xattn_fwd_workspace_bytes(2048, 1 << 17, 4, 128)
+    assert 0 < fw <= 600 << 20
+    assert lib.ulysses_xattn_bwd_workspace_bytes(2048, 1 << 17, 4, 128) > lib.ulysses_attn_bwd_workspace_bytes(2048, 4, 128)
+    for shape in ((2048, 1 << 20, 1, 128), (1 << 20, 2048, 1, 128), (300, 1 << 20, 3, 64), (1 << 20, 130, 2, 128)):
+        assert lib.ulysses_xattn_bwd_workspace_bytes(*shape) <= 600 << 20 and lib.ulysses_xattn_fwd_workspace_bytes(*shape) <= 600 << 20
+    big = dict(Nq=2048, Nk=1 << 17, Hl=4, d=128)
+    assert f(**big, ws=None, wsb=0) == 6 and f(**big, ws=0xB0000000, wsb=fw - 1) == 6
+    assert f(**big, ws=0xB0000008, wsb=fw) == 4
+    assert lib.ulysses_xattn_fwd_workspace_bytes(0, 5, 2, 64) == 0 and lib.ulysses_xattn_fwd_workspace_bytes(5, 5, 2, 100) == 0
     g = lambda **kw: lib.ulysses_xattn_bwd(*[{**dict(q=A, k=B, v=C_, o=D_, do=0x70000000, lse=0x7800000, dq=0x80000000,
                                                       dk=0x90000000, dv=0xA0000000, ws=0xB0000000, wsb=1 << 20, Nq=128,
                                                       Nk=96, Hl=2, d=64, scale=0.125, layout=0), **kw}[n]

@@ -46,6 +46,34 @@ def test_cross_attention_parity(gpu_lib, Nq, Nk, d, layout):
         assert err <= TOL_G, (name, err)
 
 
+def _parity(gpu_lib, Nq, Nk, Hl, d, layout, seed):
+    scale = 1.0 / np.sqrt(d)
+    q, k, v, do = _inputs(Nq, Nk, Hl, d, seed, layout)
+    tq, tk, tv, tdo = (to_gpu_bf16(a) for a in (q, k, v, do))
+    o, lse = gpu_lib.ulysses_xattn_fwd(tq, tk, tv, scale, layout)
+    grads = gpu_lib.ulysses_xattn_bwd(tq, tk, tv, o, tdo, lse, scale, layout)
+    again = gpu_lib.ulysses_xattn_bwd(tq, tk, tv, o, tdo, lse, scale, layout)
+    torch.cuda.synchronize()
+    fq, fk, fv, fdo = (oracle.bf16_to_f64(a) for a in (q, k, v, do))
+    o_ref, lse_ref = oracle.xattn_fwd(fq, fk, fv, scale, layout)
+    o_abs, _ = oracle.xattn_fwd(fq, fk, np.abs(fv), scale, layout)
+    ok, worst, n_bad = o_within_tolerance(f64_of(o), o_ref, o_abs, TOL_O)
+    assert ok, (worst, n_bad)
+    assert max_abs(f64_of(lse), lse_ref) <= TOL_LSE
+    for name, got, rep, ref in zip(("dq", "dk", "dv"), grads, again, oracle.xattn_bwd(fq, fk, fv, fdo, scale, layout)):
+        err = rel_l2(f64_of(got), ref)
+        assert err <= TOL_G, (name, err)
+        assert torch.equal(got, rep), name                  # partial sums are added in a fixed order
+
+
+@pytest.mark.parametrize("Nq,Nk,Hl,d,layout", [(5000, 200, 2, 128, 0), (200, 5000, 2, 128, 0), (3000, 3000, 2, 64, 0),
+                                               (2100, 4100, 3, 128, 1), (4500, 129, 1, 64, 1), (131, 6000, 3, 64, 0)])
+def test_few_tiles_on_one_side_are_cut_into_work_items(gpu_lib, Nq, Nk, Hl, d, layout):
+    """With few key tiles (query tiles) and a long other side, the backward cuts each tile's walk into several
+    work items whose fp32 partial sums a second kernel adds: every (query, key) pair must be counted once."""
+    _parity(gpu_lib, Nq, Nk, Hl, d, layout, 40 + Nq)
+
+
 def test_square_case_matches_self_attention_bits(gpu_lib):
     """Nq == Nk must give exactly what the non-causal self-attention entry points give."""
     q, k, v, do = _inputs(300, 300, 3, 128, 5, 0)
