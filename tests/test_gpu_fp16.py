@@ -67,7 +67,7 @@ def test_tiny_config(gpu_lib):
     _dense(gpu_lib, c["N"], c["H"] // c["P"], c["d"], seed=synth.config_seed("tiny"))
 
 
-@pytest.mark.parametrize("Nq,Nk,d", [(300, 1000, 128), (1000, 77, 64), (513, 513, 128)])
+@pytest.mark.parametrize("Nq,Nk,d", [(300, 1000, 128), (1000, 77, 64), (513, 513, 128), (200, 5000, 128), (5000, 200, 64)])
 def test_cross_attention(gpu_lib, Nq, Nk, d):
     scale = 1.0 / np.sqrt(d)
     _, (fq, _, _, fdo), (tq, _, _, tdo) = _inputs(Nq, 2, d, 21)
