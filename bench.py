@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--sparse-window", type=int, default=0,
                     help="also time block-sparse attention: local window of this many 256-token blocks plus the "
                          "first block column (0 = off; extra 'sparse' object in the output)")
+    ap.add_argument("--d", type=int, default=0,
+                    help="head dimension to use instead of the workload's (64, 128 or 256; N, P and the head count stay)")
     ap.add_argument("--layouts", action="store_true",
                     help="also time every layout transform (forward and reverse direction, both layouts, one and "
                          "three tensors per launch) at this workload's shapes (extra 'layout_transforms' object)")
@@ -70,7 +72,7 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     c = synth.CONFIGS[args.config]
-    N, P, H, d = c["N"], c["P"], c["H"], c["d"]
+    N, P, H, d = c["N"], c["P"], c["H"], args.d or c["d"]
     nl, Hl = N // P, H // P
     scale = 1.0 / math.sqrt(d)
     seed = synth.config_seed(args.config)
@@ -166,7 +168,8 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16" if args.elem == "fp16" else "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.config}: one GPU's share, N={N} tokens, P={P}, H={H} ({Hl} local heads), "
+        "config": {"workload": f"{args.config}{' with another head dimension' if d != c['d'] else ''}: one GPU's share, "
+                               f"N={N} tokens, P={P}, H={H} ({Hl} local heads), "
                                f"d={d}, batch 1, causal; per step pack and unpack of 3 x [{nl},{H},{d}] {args.elem} (one launch each) and "
                                "attention fwd+bwd",
                    "N": N, "P": P, "H": H, "local_heads": Hl, "d": d},
@@ -179,7 +182,7 @@ def main() -> int:
         "kernel_ms": seg_ms,
         "roofline": {"kernel": "attn_bwd_dkv_kernel", "bound": "mfma", "achieved": dkv_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dkv_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": DKV_TRAFFIC_BYTES.get(args.config)},
+                     "traffic": DKV_TRAFFIC_BYTES.get(args.config) if d == c["d"] else None},
     }
 
     # ---- the matrix rate the device sustains with nothing but MFMAs on the same kind of data -----

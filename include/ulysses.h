@@ -114,8 +114,9 @@ int ulysses_unpack_rev_qkv(const void* const recv[3], void* const y[3], int64_t 
  * layout | ULY_ELEM_F16; this holds for the cross- and sparse-attention entry points too);
  * arithmetic is 16-bit MFMA with fp32 accumulation and fp32 softmax; outputs are rounded to the
  * element type (nearest even).  The paper does not state a precision.
- * N tokens (0 <= N < 2^31), Hl local heads with Hl * d <= 2^22, d in {64, 128} (ULY_ERR_SHAPE /
- * ULY_ERR_UNSUPPORTED otherwise).  `scale` is normally 1/sqrt(d) and must
+ * N tokens (0 <= N < 2^31), Hl local heads with Hl * d <= 2^22, d in {64, 128, 256} (ULY_ERR_SHAPE /
+ * ULY_ERR_UNSUPPORTED otherwise; d = 256 runs simpler, slower kernels and is not available for the
+ * block-sparse entry points).  `scale` is normally 1/sqrt(d) and must
  * be finite and > 0 (anything else is ULY_ERR_UNSUPPORTED).
  * ------------------------------------------------------------------------------------------- */
 

@@ -9,12 +9,14 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libulysses.so")
-SOURCES = ["api.cpp", "layout.hip", "attn_fwd.hip", "attn_bwd.hip"]
+SOURCES = ["api.cpp", "layout.hip", "attn_fwd.hip", "attn_bwd.hip", "attn_d256.hip"]
 HEADERS = ["internal.h", "attn_launch.h", "attn_common.h", os.path.join("..", "..", "include", "ulysses.h")]
 # (source, object stem, extra flags): the attention sources are compiled once per element type
 UNITS = [("api.cpp", "api", []), ("layout.hip", "layout", []),
          ("attn_fwd.hip", "attn_fwd", []), ("attn_bwd.hip", "attn_bwd", []),
-         ("attn_fwd.hip", "attn_fwd_f16", ["-DULY_BUILD_F16=1"]), ("attn_bwd.hip", "attn_bwd_f16", ["-DULY_BUILD_F16=1"])]
+         ("attn_d256.hip", "attn_d256", []),
+         ("attn_fwd.hip", "attn_fwd_f16", ["-DULY_BUILD_F16=1"]), ("attn_bwd.hip", "attn_bwd_f16", ["-DULY_BUILD_F16=1"]),
+         ("attn_d256.hip", "attn_d256_f16", ["-DULY_BUILD_F16=1"])]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          # packed-fp32 VALU forms are kept off for every device function of this library

@@ -70,7 +70,7 @@ int check_layout_args3(const void* const src[3], void* const dst[3], int64_t n_l
 
 int check_attn_common(int64_t N, int Hl, int d, int layout, uint64_t* tensor_bytes) {
     if (N < 0 || Hl <= 0 || d <= 0) return ULY_ERR_SHAPE;
-    if (d != 64 && d != 128) return ULY_ERR_UNSUPPORTED;
+    if (d != 64 && d != 128 && d != 256) return ULY_ERR_UNSUPPORTED;
     layout &= ~ULY_ELEM_F16;                                           // the element type flag rides on the layout word
     if (layout != ULY_LAYOUT_SEQ_HEAD && layout != ULY_LAYOUT_HEAD_SEQ) return ULY_ERR_UNSUPPORTED;
     if (N >= (1ll << 31)) return ULY_ERR_SHAPE;                       // tile counters are 32-bit
@@ -276,6 +276,7 @@ int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o
     uint64_t tb;
     const int rc = check_attn_common(N, Hl, d, layout, &tb);
     if (rc != ULY_OK) return rc;
+    if (d == 256) return ULY_ERR_UNSUPPORTED;                    // the sparse kernels exist for d = 64 and 128
     if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;
     if (N == 0) return ULY_OK;
     if (!q || !k || !v || !o || !lse || !row_ptr || !col_idx) return ULY_ERR_NULL;
@@ -290,7 +291,8 @@ int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o
 
 size_t ulysses_sparse_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
     uint64_t tb;
-    if (check_attn_common(N, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK || N == 0 || N > ULY_SPARSE_BWD_MAX_N) return 0;
+    if (check_attn_common(N, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK || d == 256 || N == 0 || N > ULY_SPARSE_BWD_MAX_N)
+        return 0;
     return (size_t)uly::bf16::attn_bwd_sparse_workspace_floats(N, Hl, d) * sizeof(float);
 }
 
@@ -302,6 +304,7 @@ int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const v
     const int rc = check_attn_common(N, Hl, d, layout, &tb);
     if (rc != ULY_OK) return rc;
     if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;
+    if (d == 256) return ULY_ERR_UNSUPPORTED;
     if (N == 0) return ULY_OK;
     if (N > ULY_SPARSE_BWD_MAX_N) return ULY_ERR_SHAPE;          // the work items of dK/dV are a grid dimension
     if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv || !row_ptr || !col_idx || !col_ptr || !row_idx)

@@ -1219,11 +1219,28 @@ int attn_bwd_sparse_launch(const void* q, const void* k, const void* v, const vo
 int64_t attn_bwd_workspace_floats(int64_t N, int Hl) { return 2 * stats_stride(N) * Hl; }
 int64_t attn_bwd_sparse_workspace_floats(int64_t N, int Hl, int d) { return sparse_workspace(N, Hl, d).total; }
 
-int64_t attn_bwd_cut_workspace_floats(int64_t N, int64_t Nk, int Hl, int d) { return cut_workspace(N, Nk, Hl, d).total; }
+int64_t attn_bwd_cut_workspace_floats(int64_t N, int64_t Nk, int Hl, int d) {
+    if (d == 256) return attn_bwd_workspace_floats(N, Hl);      // the d = 256 kernels do not cut
+    return cut_workspace(N, Nk, Hl, d).total;
+}
 
 int attn_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* o, const void* dout,
                     const float* lse, void* dq, void* dk, void* dv, float* ws, int64_t N, int64_t Nk, int Hl, int d,
                     float scale, int causal, int may_cut, TensorStrides st, TensorStrides kv, void* stream) {
+    if (d == 256) {
+        const int64_t stride = stats_stride(N);
+        float* delta = ws;
+        float* lse2 = ws + stride * Hl;
+        if (stage_mask & 1) {
+            const int64_t delta_blocks = (stride * Hl * (256 / 8) + 255) / 256;
+            if (delta_blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
+            attn_bwd_delta_kernel<256><<<dim3((uint32_t)delta_blocks), dim3(256), 0, (hipStream_t)stream>>>(
+                (const e16*)o, (const e16*)dout, lse, delta, lse2, (int)N, Hl, stride, st.row, st.head);
+            if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+        }
+        return attn256_bwd_launch(stage_mask, q, k, v, dout, delta, lse2, stride, dq, dk, dv, N, Nk, Hl, scale, causal, st,
+                                  kv, stream);
+    }
     if (d == 128)
         return launch_bwd<128>(stage_mask, q, k, v, o, dout, lse, dq, dk, dv, ws, N, Nk, Hl, scale, causal, may_cut != 0,
                                st, kv, (hipStream_t)stream);

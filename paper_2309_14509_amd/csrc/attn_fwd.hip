@@ -512,11 +512,13 @@ int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o,
 }
 
 int64_t attn_fwd_cut_workspace_floats(int64_t N, int64_t Nk, int Hl, int d) {
+    if (d == 256) return 0;                   // the d = 256 kernels do not cut
     return fwd_cut_workspace_floats_of(N, Nk, Hl, d);
 }
 
 int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, float* ws, int64_t N, int64_t Nk,
                     int Hl, int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream) {
+    if (d == 256) return attn256_fwd_launch(q, k, v, o, lse, N, Nk, Hl, scale, causal, st, kv, stream);
     if (d == 128) return launch_fwd<128>(q, k, v, o, lse, ws, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
     return launch_fwd<64>(q, k, v, o, lse, ws, N, Nk, Hl, scale, causal, st, kv, (hipStream_t)stream);
 }

@@ -39,3 +39,11 @@ int attn_bwd_sparse_launch(const void* q, const void* k, const void* v, const vo
                            const float* lse, void* dq, void* dk, void* dv, float* delta, const int* row_ptr,
                            const int* col_idx, const int* col_ptr, const int* row_idx, int64_t N, int Hl, int d,
                            float scale, TensorStrides st, void* stream);
+
+// Head dimension 256 (attn_d256.hip): simpler kernels, no work plans.  The backward launcher runs the dK/dV
+// (bit 1) and dQ (bit 2) stages on statistics the caller has produced with the delta kernel.
+int attn256_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int64_t Nk, int Hl,
+                       float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
+int attn256_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* dout, const float* delta,
+                       const float* lse2, int64_t stride, void* dq, void* dk, void* dv, int64_t N, int64_t Nk, int Hl,
+                       float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);

@@ -193,6 +193,7 @@ def test_sparse_attention_validation(lib):
                                                              "layout")], None)
     assert f(rp=None) == 1 and f(ci=None) == 1 and f(v=None) == 1
     assert f(N=-1) == 2 and f(d=100) == 3 and f(scale=-1.0) == 3
+    assert f(d=256) == 3 and _fwd(lib, d=256, N=0) == 0         # d = 256: dense attention only
     assert f(rp=RP + 2) == 4 and f(q=A + 8) == 4
     assert f(o=A) == 5 and f(N=0, rp=None, ci=None) == 0
     # statistics as for the dense backward, plus a work plan and a bounded number of fp32 partial-sum slots

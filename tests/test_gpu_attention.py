@@ -44,6 +44,18 @@ def _full_parity(uly, N, Hl, d, causal=True, layout=0, seed=1, mult=1.0, scale=N
         assert err <= TOL_G, (name, err)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("N", [1, 31, 33, 128, 129, 200, 257, 700, 1300])
+def test_head_dimension_256(gpu_lib, N, causal):
+    """d = 256 runs its own (simpler) kernels: ragged sizes, several tiles per head, both masks."""
+    _full_parity(gpu_lib, N, 2, 256, causal=causal, seed=N + 256)
+
+
+def test_head_dimension_256_head_major_and_odd_heads(gpu_lib):
+    _full_parity(gpu_lib, 900, 3, 256, layout=1, seed=11)
+    _full_parity(gpu_lib, 515, 5, 256, causal=False, layout=1, seed=12)
+
+
 def test_tiny_config_full(gpu_lib):
     c = synth.CONFIGS["tiny"]
     _full_parity(gpu_lib, c["N"], c["H"] // c["P"], c["d"], seed=synth.config_seed("tiny"))

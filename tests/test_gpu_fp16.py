@@ -45,13 +45,13 @@ def _dense(uly, N, Hl, d, causal=True, layout=0, seed=1, mult=1.0):
     _compare(o, lse, grads, o_ref, lse_ref, oracle.attn_bwd(fq, fk, fv, fdo, scale, causal, layout))
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [64, 128, 256])
 @pytest.mark.parametrize("N", [1, 33, 128, 257, 700, 1021, 2177])
 def test_causal(gpu_lib, N, d):
     _dense(gpu_lib, N, 2, d, seed=N + d)
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [64, 128, 256])
 @pytest.mark.parametrize("N", [65, 777])
 def test_non_causal(gpu_lib, N, d):
     _dense(gpu_lib, N, 3, d, causal=False, seed=N)

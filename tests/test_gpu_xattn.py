@@ -74,6 +74,11 @@ def test_few_tiles_on_one_side_are_cut_into_work_items(gpu_lib, Nq, Nk, Hl, d, l
     _parity(gpu_lib, Nq, Nk, Hl, d, layout, 40 + Nq)
 
 
+@pytest.mark.parametrize("Nq,Nk,layout", [(300, 1000, 0), (1000, 77, 1), (129, 257, 0), (2000, 2500, 0)])
+def test_head_dimension_256(gpu_lib, Nq, Nk, layout):
+    _parity(gpu_lib, Nq, Nk, 2, 256, layout, 70 + Nq)
+
+
 def test_square_case_matches_self_attention_bits(gpu_lib):
     """Nq == Nk must give exactly what the non-causal self-attention entry points give."""
     q, k, v, do = _inputs(300, 300, 3, 128, 5, 0)
