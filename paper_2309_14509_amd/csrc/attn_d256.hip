@@ -220,24 +220,40 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd256_dkv_kernel(
         __builtin_amdgcn_sched_barrier(0);            // (phase boundaries keep the live ranges of the operand reads short)
         e16x8 pb[2], dsb[2];
         const int jrel = j_col - 4 * g - i0;          // causal: row offset c_r is masked iff c_r < jrel
+        auto softmax_half = [&](int u) __attribute__((always_inline)) {      // P and dS of C rows 8u .. 8u+7
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float x = __builtin_fmaf(s[r], sl2, -lse4[r >> 2][r & 3]);
-            if (CAUSAL) x = (8 * (r >> 2) + (r & 3) < jrel) ? -INFINITY : x;
-            const float p = fast_exp2(x);
-            const float ds = p * (dp[r] - del4[r >> 2][r & 3]);
-            pb[r >> 3][r & 7] = (e16)p;
-            dsb[r >> 3][r & 7] = (e16)ds;
+            for (int e = 0; e < 8; ++e) {
+                const int r = 8 * u + e;
+                float x = __builtin_fmaf(s[r], sl2, -lse4[r >> 2][r & 3]);
+                if (CAUSAL) x = (8 * (r >> 2) + (r & 3) < jrel) ? -INFINITY : x;
+                const float p = fast_exp2(x);
+                pb[u][e] = (e16)p;
+                dsb[u][e] = (e16)(p * (dp[r] - del4[r >> 2][r & 3]));
+            }
+        };
+        softmax_half(0);
+        __builtin_amdgcn_sched_barrier(0);
+        // the matrix products of the first half, with the vector work of the second half between them
+        softmax_half(1);
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            dv_acc[cb] = mfma32(tr_read(buf + (2 + (cb >> 2)) * kHT, 0, cb & 3, lane), pb[0], dv_acc[cb]);
+            dk_acc[cb] = mfma32(tr_read(buf + (cb >> 2) * kHT, 0, cb & 3, lane), dsb[0], dk_acc[cb]);
+        }
+#pragma unroll
+        for (int i = 0; i < 2 * NCB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);    // the two transposing reads of an operand
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);    // VALU
+            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // transcendental
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-                dv_acc[cb] = mfma32(tr_read(buf + (2 + (cb >> 2)) * kHT, u, cb & 3, lane), pb[u], dv_acc[cb]);
-                dk_acc[cb] = mfma32(tr_read(buf + (cb >> 2) * kHT, u, cb & 3, lane), dsb[u], dk_acc[cb]);
-                if ((cb & 1) == 1) __builtin_amdgcn_sched_barrier(0);
-            }
+        for (int cb = 0; cb < NCB; ++cb) {
+            dv_acc[cb] = mfma32(tr_read(buf + (2 + (cb >> 2)) * kHT, 1, cb & 3, lane), pb[1], dv_acc[cb]);
+            dk_acc[cb] = mfma32(tr_read(buf + (cb >> 2) * kHT, 1, cb & 3, lane), dsb[1], dk_acc[cb]);
+            if ((cb & 1) == 1) __builtin_amdgcn_sched_barrier(0);
+        }
     }
     if (j_col < Nk) {
         e16* krow = dK + kv_hoff + (int64_t)j_col * row_stride;
@@ -307,20 +323,35 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd256_dq_kernel(
             s = mfma32(row_read(buf + (t >> 3) * kHT, ln, 2 * (t & 7) + g), qreg[t], s);
             dp = mfma32(row_read(buf + (2 + (t >> 3)) * kHT, ln, 2 * (t & 7) + g), doreg[t], dp);
         }
+        __builtin_amdgcn_sched_barrier(0);
         e16x8 dsb[2];
         const int krel = klim - kb * kRows;           // key offset c_r is masked iff c_r > krel
+        auto softmax_half = [&](int u) __attribute__((always_inline)) {      // dS^T of C rows 8u .. 8u+7
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float x = __builtin_fmaf(s[r], sl2, -lse2);
-            x = (8 * (r >> 2) + (r & 3) > krel) ? -INFINITY : x;
-            const float p = fast_exp2(x);
-            dsb[r >> 3][r & 7] = (e16)(p * (dp[r] - delta));
+            for (int e = 0; e < 8; ++e) {
+                const int r = 8 * u + e;
+                float x = __builtin_fmaf(s[r], sl2, -lse2);
+                x = (8 * (r >> 2) + (r & 3) > krel) ? -INFINITY : x;
+                const float p = fast_exp2(x);
+                dsb[u][e] = (e16)(p * (dp[r] - delta));
+            }
+        };
+        softmax_half(0);
+        __builtin_amdgcn_sched_barrier(0);
+        // the matrix products of the first half, with the vector work of the second half between them
+        softmax_half(1);
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) acc[cb] = mfma32(tr_read(buf + (cb >> 2) * kHT, 0, cb & 3, lane), dsb[0], acc[cb]);
+#pragma unroll
+        for (int i = 0; i < NCB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);    // the two transposing reads of an operand
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);    // VALU
+            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // transcendental
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb)
-                acc[cb] = mfma32(tr_read(buf + (cb >> 2) * kHT, u, cb & 3, lane), dsb[u], acc[cb]);
+        for (int cb = 0; cb < NCB; ++cb) acc[cb] = mfma32(tr_read(buf + (cb >> 2) * kHT, 1, cb & 3, lane), dsb[1], acc[cb]);
     }
     if (q_row < N) {
         e16* orow = dQ + hoff + (int64_t)q_row * row_stride;
