@@ -74,6 +74,12 @@ def test_few_tiles_on_one_side_are_cut_into_work_items(gpu_lib, Nq, Nk, Hl, d, l
     _parity(gpu_lib, Nq, Nk, Hl, d, layout, 40 + Nq)
 
 
+@pytest.mark.parametrize("Nq,Nk", [(2048, 65536), (65536, 2048), (300, 40000)])
+def test_many_work_items_per_tile(gpu_lib, Nq, Nk):
+    """A short side against a long one: every tile of the short side is cut into 20 to 64 work items."""
+    _parity(gpu_lib, Nq, Nk, 1, 128, 0, 5)
+
+
 @pytest.mark.parametrize("Nq,Nk,layout", [(300, 1000, 0), (1000, 77, 1), (129, 257, 0), (2000, 2500, 0)])
 def test_head_dimension_256(gpu_lib, Nq, Nk, layout):
     _parity(gpu_lib, Nq, Nk, 2, 256, layout, 70 + Nq)
