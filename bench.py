@@ -51,6 +51,10 @@ def main() -> int:
     ap.add_argument("--xattn", default="",
                     help="also time attention without a mask for these (queries, keys) counts, e.g. "
                          "'131072x131072,16384x131072': rows of the same tensors (extra 'xattn' list in the output)")
+    ap.add_argument("--sparse-pattern", choices=["window_global", "fixed"], default="window_global",
+                    help="with --sparse-window W: 'window_global' = blocks r - c < W plus the first block column; "
+                         "'fixed' = windows of W blocks, a block row sees its own window and the last block of every "
+                         "earlier window")
     ap.add_argument("--elem", choices=["bf16", "fp16"], default="bf16",
                     help="element type of the tensors (the headline metric is bf16)")
     args = ap.parse_args()
@@ -283,7 +287,14 @@ def main() -> int:
     if args.sparse_window > 0:
         nb = (N + uly.SPARSE_BLOCK - 1) // uly.SPARSE_BLOCK
         bi, bj = np.indices((nb, nb))
-        pat = uly.SparsePattern((bi - bj < args.sparse_window) | (bj == 0))
+        W = args.sparse_window
+        if args.sparse_pattern == "fixed":
+            mask = (bi // W == bj // W) | ((bj % W == W - 1) & (bj < (bi // W) * W))
+            pat_name = f"windows of {W} blocks; a block row sees its own window and the last block of every earlier window"
+        else:
+            mask = (bi - bj < W) | (bj == 0)
+            pat_name = f"window of {W} blocks + first block column"
+        pat = uly.SparsePattern(mask)
         pd = pat.dev
         sws = torch.empty(int(lib.ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d)), dtype=torch.uint8, device="cuda")
         sp_ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -311,7 +322,7 @@ def main() -> int:
         # visible (query, key) pairs: full blocks count 256*256, diagonal blocks 256*257/2 (N a multiple of 256 here)
         Bk = uly.SPARSE_BLOCK
         pairs = (pat.nnz - nb) * Bk * Bk + nb * Bk * (Bk + 1) // 2
-        result["sparse"] = {"pattern": f"window of {args.sparse_window} blocks of {Bk} tokens + first block column",
+        result["sparse"] = {"pattern": f"{pat_name} (blocks of {Bk} tokens)",
                             "blocks": pat.nnz, "of_lower_triangle": pat.nnz / (nb * (nb + 1) / 2),
                             "ms_fwd_bwd": sp_ms, "ms_fwd_last_step": sp_ev[0].elapsed_time(sp_ev[1]),
                             "ms_bwd_last_step": sp_ev[1].elapsed_time(sp_ev[2]), "tflops": 14.0 * pairs * d * Hl / (sp_ms * 1e-3) / 1e12}

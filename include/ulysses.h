@@ -197,7 +197,7 @@ int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o
  * Workspace of the backward (caller-owned device memory, ulysses_sparse_attn_bwd_workspace_bytes;
  * 0 for a shape the library rejects): the row statistics of the dense backward, a work plan the
  * library derives from col_ptr on the device, and fp32 partial sums for block columns so long that
- * several workgroups share one (at most 2048 slots of 128 keys x d x 2 tensors: 256 MiB at d = 128,
+ * several workgroups share one (at most 8192 slots of 128 keys x d x 2 tensors: 1 GiB at d = 128,
  * whatever N is).  The sums are added in a fixed order: results are deterministic.
  * ------------------------------------------------------------------------------------------- */
 #define ULY_SPARSE_BLOCK 256

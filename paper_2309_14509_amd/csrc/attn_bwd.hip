@@ -877,7 +877,10 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 // One workgroup; every thread scans a contiguous range of key tiles.
 // ------------------------------------------------------------------------------------------
 constexpr int kPlanThreads = 1024;
-constexpr int kPlanTarget = 1024;   // items the cut columns are aimed at, over all heads
+constexpr int kPlanTarget = 4096;   // items the cut columns are aimed at, over all heads: 16 per CU, so that
+                                    // a CU's share is many items (with 1024 a pattern whose work sits in long
+                                    // columns left the launch a quarter longer than its average CU)
+constexpr int kDenseCutTarget = 1024;   // the same for unmasked attention with a short side (uniform items)
 constexpr int kPlanMinLen = 32;     // query blocks; below this the per-item overhead would show
 
 inline int plan_slots_per_head(int64_t n_ktiles, int64_t nblk4, int Hl) {
@@ -984,7 +987,7 @@ struct DenseCut {
 inline DenseCut dense_cut(int64_t n_tiles, int64_t cnt, int Hl) {
     DenseCut c{1, (int)cnt};
     if (n_tiles * Hl >= 512 || cnt < 2 * kPlanMinLen) return c;
-    int64_t want = (kPlanTarget + n_tiles * Hl - 1) / (n_tiles * Hl);        // pieces that give about kPlanTarget items
+    int64_t want = (kDenseCutTarget + n_tiles * Hl - 1) / (n_tiles * Hl);    // pieces that give about kDenseCutTarget items
     const int64_t most = cnt / kPlanMinLen;
     want = want < most ? want : most;
     if (want < 2) return c;

@@ -199,7 +199,7 @@ def test_sparse_attention_validation(lib):
     # statistics as for the dense backward, plus a work plan and a bounded number of fp32 partial-sum slots
     assert lib.ulysses_sparse_attn_bwd_workspace_bytes(600, 2, 64) > lib.ulysses_attn_bwd_workspace_bytes(600, 2, 64)
     big, slot = lib.ulysses_sparse_attn_bwd_workspace_bytes(1 << 20, 4, 128), 2 * 128 * 128 * 4
-    assert big - lib.ulysses_attn_bwd_workspace_bytes(1 << 20, 4, 128) <= 2048 * slot + (1 << 20)
+    assert big - lib.ulysses_attn_bwd_workspace_bytes(1 << 20, 4, 128) <= 8192 * slot + (1 << 20)
     assert lib.ulysses_sparse_attn_bwd_workspace_bytes(0, 4, 128) == 0
     assert lib.ulysses_sparse_attn_bwd_workspace_bytes(600, 2, 100) == 0
     g = lambda **kw: lib.ulysses_sparse_attn_bwd(*[{**dict(q=A, k=B, v=C_, o=D_, do=0x70000000, lse=0x7800000,
