@@ -272,12 +272,11 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
 
     // LDS reads in flight at entry, oldest first: K rows of b+1, V rows of b+1.
     // ("b+1", "b+2" below mean the blocks of the next walk positions)
-    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot2_tag, int p) __attribute__((always_inline)) {
+    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot2_tag, int p, int b_next) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr int SL = decltype(slot_tag)::value;
         constexpr int PAR = SL & 1;
-        const int krel = klim - blk(p) * kDqBK;
-        const int b_next = blk(p + kDqRing);           // the tile fetched into this position's slot
+        const int krel = klim - blk(p) * kDqBK;        // (b_next: the tile fetched into this position's slot)
         e16x8 dsb[2];
         auto softmax_half = [&](int u) __attribute__((always_inline)) {
 #pragma unroll
@@ -352,25 +351,37 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     int p = 0;
     settle();
     if (dir < 0) {
-        iteration(Masked{}, S0{}, S2{}, 0); settle();
-        iteration(Masked{}, S1{}, S3{}, 1); settle();
-        iteration(Masked{}, S2{}, S0{}, 2); settle();
-        iteration(Masked{}, S3{}, S1{}, 3); settle();
+        iteration(Masked{}, S0{}, S2{}, 0, blk(kDqRing)); settle();
+        iteration(Masked{}, S1{}, S3{}, 1, blk(1 + kDqRing)); settle();
+        iteration(Masked{}, S2{}, S0{}, 2, blk(2 + kDqRing)); settle();
+        iteration(Masked{}, S3{}, S1{}, 3, blk(3 + kDqRing)); settle();
         p = 4;
     }
     const int plain_end = dir > 0 ? walk - 4 : walk;
     for (; p < plain_end; p += 4) {
-        iteration(Plain{}, S0{}, S2{}, p);
-        iteration(Plain{}, S1{}, S3{}, p + 1);
-        iteration(Plain{}, S2{}, S0{}, p + 2);
-        iteration(Plain{}, S3{}, S1{}, p + 3);
+        // the blocks fetched during these four iterations; with a pattern they lie in one sparse block (the walk
+        // position is a multiple of 4 and a sparse block holds 8), so one look-up in the pattern serves all four
+        int bn[4];
+        if (SPARSE) {
+            const int b = blk(p + kDqRing);
+            const bool past = p + kDqRing >= cnt;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bn[i] = past ? b : b + i;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bn[i] = blk(p + kDqRing + i);
+        }
+        iteration(Plain{}, S0{}, S2{}, p, bn[0]);
+        iteration(Plain{}, S1{}, S3{}, p + 1, bn[1]);
+        iteration(Plain{}, S2{}, S0{}, p + 2, bn[2]);
+        iteration(Plain{}, S3{}, S1{}, p + 3, bn[3]);
     }
     settle();
     if (dir > 0) {
-        iteration(Masked{}, S0{}, S2{}, p); settle();
-        iteration(Masked{}, S1{}, S3{}, p + 1); settle();
-        iteration(Masked{}, S2{}, S0{}, p + 2); settle();
-        iteration(Masked{}, S3{}, S1{}, p + 3); settle();
+        iteration(Masked{}, S0{}, S2{}, p, blk(p + kDqRing)); settle();
+        iteration(Masked{}, S1{}, S3{}, p + 1, blk(p + 1 + kDqRing)); settle();
+        iteration(Masked{}, S2{}, S0{}, p + 2, blk(p + 2 + kDqRing)); settle();
+        iteration(Masked{}, S3{}, S1{}, p + 3, blk(p + 3 + kDqRing)); settle();
     }
     // Nothing may still be writing LDS when this query tile ends, and the operand reads issued for a
     // block that does not exist must have landed before their (now dead) registers are reused.
@@ -668,14 +679,13 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     // One iteration: walk position p (block b) lives in ring slot SL (its parity selects the s/dp set);
     // "b+1", "b+2" below mean the blocks of the next positions.
     // LDS reads in flight at entry, oldest first: statistics of b, Q rows of b+1, dO rows of b+1.
-    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot1_tag, auto slot2_tag, int p)
+    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot1_tag, auto slot2_tag, int p, int b_next)
                          __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr int SL = decltype(slot_tag)::value;
         constexpr int PAR = SL & 1;
         const int i0 = blk(p) * kDkvBQ;
-        const int jrel = jcol_g - i0;
-        const int b_next = blk(p + kDkvRing);          // the tile fetched into this position's slot
+        const int jrel = jcol_g - i0;                  // (b_next: the tile fetched into this position's slot)
         e16x8 pb[2], dsb[2];
         // P and dS of 8 rows of block b (vector pipe)
         auto softmax_half = [&](int u) __attribute__((always_inline)) {
@@ -799,25 +809,38 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     int p = 0;
     settle();
     if (CAUSAL && dir > 0) {
-        iteration(Masked{}, S0{}, S1{}, S2{}, 0); settle();
-        iteration(Masked{}, S1{}, S2{}, S3{}, 1); settle();
-        iteration(Masked{}, S2{}, S3{}, S0{}, 2); settle();
-        iteration(Masked{}, S3{}, S0{}, S1{}, 3); settle();
+        iteration(Masked{}, S0{}, S1{}, S2{}, 0, blk(kDkvRing)); settle();
+        iteration(Masked{}, S1{}, S2{}, S3{}, 1, blk(1 + kDkvRing)); settle();
+        iteration(Masked{}, S2{}, S3{}, S0{}, 2, blk(2 + kDkvRing)); settle();
+        iteration(Masked{}, S3{}, S0{}, S1{}, 3, blk(3 + kDkvRing)); settle();
         p = 4;
     }
     const int plain_end = (CAUSAL && dir < 0) ? walk - 4 : walk;
     for (; p < plain_end; p += 4) {
-        iteration(Plain{}, S0{}, S1{}, S2{}, p);
-        iteration(Plain{}, S1{}, S2{}, S3{}, p + 1);
-        iteration(Plain{}, S2{}, S3{}, S0{}, p + 2);
-        iteration(Plain{}, S3{}, S0{}, S1{}, p + 3);
+        // the blocks fetched during these four iterations; with a pattern they lie in one sparse block (walk
+        // positions are multiples of 4, a sparse block holds 8 and the diagonal part 4 or 8), so one look-up in
+        // the pattern serves all four
+        int bn[4];
+        if (SPARSE) {
+            const int b = blk(p + kDkvRing);
+            const bool past = p + kDkvRing + (PLAN ? p_off : 0) >= cnt;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bn[i] = past ? b : b + i;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bn[i] = blk(p + kDkvRing + i);
+        }
+        iteration(Plain{}, S0{}, S1{}, S2{}, p, bn[0]);
+        iteration(Plain{}, S1{}, S2{}, S3{}, p + 1, bn[1]);
+        iteration(Plain{}, S2{}, S3{}, S0{}, p + 2, bn[2]);
+        iteration(Plain{}, S3{}, S0{}, S1{}, p + 3, bn[3]);
     }
     settle();
     if (CAUSAL && dir < 0) {
-        iteration(Masked{}, S0{}, S1{}, S2{}, p); settle();
-        iteration(Masked{}, S1{}, S2{}, S3{}, p + 1); settle();
-        iteration(Masked{}, S2{}, S3{}, S0{}, p + 2); settle();
-        iteration(Masked{}, S3{}, S0{}, S1{}, p + 3); settle();
+        iteration(Masked{}, S0{}, S1{}, S2{}, p, blk(p + kDkvRing)); settle();
+        iteration(Masked{}, S1{}, S2{}, S3{}, p + 1, blk(p + 1 + kDkvRing)); settle();
+        iteration(Masked{}, S2{}, S3{}, S0{}, p + 2, blk(p + 2 + kDkvRing)); settle();
+        iteration(Masked{}, S3{}, S0{}, S1{}, p + 3, blk(p + 3 + kDkvRing)); settle();
     }
     // Nothing may still be writing LDS when this key tile ends, and the operand reads issued for a
     // block that does not exist must have landed before their (now dead) registers are reused.
