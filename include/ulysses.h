@@ -198,7 +198,7 @@ int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o
  * 0 for a shape the library rejects): the row statistics of the dense backward, a work plan the
  * library derives from col_ptr on the device, and fp32 partial sums for block columns so long that
  * several workgroups share one (at most 8192 slots of 128 keys x d x 2 tensors: 1 GiB at d = 128,
- * whatever N is).  The sums are added in a fixed order: results are deterministic.
+ * and never more than two slots per 128 keys and head, so short sequences take little).  The sums are added in a fixed order: results are deterministic.
  * ------------------------------------------------------------------------------------------- */
 #define ULY_SPARSE_BLOCK 256
 #define ULY_SPARSE_BWD_MAX_N 8000000   /* longer sequences: ULY_ERR_SHAPE from ulysses_sparse_attn_bwd */

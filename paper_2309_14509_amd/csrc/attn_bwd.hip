@@ -893,8 +893,10 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 // waiting for the few longest block columns.  Columns longer than L blocks are therefore cut into
 // items of at most L blocks (a multiple of 4); the workgroups of a cut column write fp32 partial
 // sums, which the reduce kernel adds in a fixed order.  L = max(kPlanMinLen, total work / kPlanTarget)
-// so that no item exceeds a small part of one CU's share, and the number of partial-sum slots is
-// bounded independently of N:  sum over cut columns of ceil(cnt / L) <= 2 * total / L <= 2 * kPlanTarget / Hl.
+// so that no item exceeds a small part of one CU's share; that needs at most
+// sum over cut columns of ceil(cnt / L) <= 2 * total / L <= 2 * kPlanTarget / Hl partial-sum slots per head.
+// The workspace holds that many, but never more than two per key tile; a pattern that would need more
+// gets L doubled until its cut items fit.
 //   plan[0] = {items, cut items, L, 0};  plan[1 + s] = {key tile, first position, end position, 0};
 //   cut items come first (s = slot of their partial sums);  red[ktile] = {first slot, items} (items 1: not cut).
 // One workgroup; every thread scans a contiguous range of key tiles.
@@ -906,12 +908,18 @@ constexpr int kPlanTarget = 4096;   // items the cut columns are aimed at, over 
 constexpr int kDenseCutTarget = 1024;   // the same for unmasked attention with a short side (uniform items)
 constexpr int kPlanMinLen = 32;     // query blocks; below this the per-item overhead would show
 
+// Slots for partial sums per head: what the target can ask for, but no more than two per key tile (the
+// partial sums then take at most four times the fp32 size of dK and dV; short sequences gain nothing from
+// finer cuts).  If a pattern would need more, the plan kernel doubles L until it fits.
 inline int plan_slots_per_head(int64_t n_ktiles, int64_t nblk4, int Hl) {
+    (void)nblk4;
     const int64_t by_target = 2 * ((kPlanTarget + Hl - 1) / Hl);
-    const int64_t by_size = 2 * (n_ktiles * nblk4 / kPlanMinLen) + 1;      // total <= n_ktiles * nblk4
+    const int64_t by_size = 2 * n_ktiles + 1;
     return (int)(by_target < by_size ? by_target : by_size);
 }
-inline int64_t plan_items_bound(int64_t n_ktiles, int Hl) { return n_ktiles + (kPlanTarget + Hl - 1) / Hl + 1; }
+inline int64_t plan_items_bound(int64_t n_ktiles, int64_t nblk4, int Hl) {
+    return n_ktiles + plan_slots_per_head(n_ktiles, nblk4, Hl) + 1;          // whole columns + cut items
+}
 
 __device__ __forceinline__ int block_scan_exclusive(int v, int* sh, int* total) {
     const int tid = threadIdx.x;
@@ -959,7 +967,7 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_dkv_plan_kernel(const int
         return (((cnt + n - 1) / n) + 3) & ~3;
     };
     int n_cut = 0, n_whole = 0, cut_total = 0, whole_total = 0, cut_at = 0, whole_at = 0;
-    for (int attempt = 0; attempt < 2; ++attempt) {
+    for (int attempt = 0; attempt < 24; ++attempt) {
         n_cut = n_whole = 0;
         for (int kt = k0; kt < k1; ++kt) {
             const int cnt = count(kt);
@@ -969,7 +977,7 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_dkv_plan_kernel(const int
         cut_at = block_scan_exclusive(n_cut, sh, &cut_total);
         whole_at = block_scan_exclusive(n_whole, sh, &whole_total);
         if (cut_total <= slots_per_head) break;
-        L = 0x3FFFFFFC;                         // cannot happen by the bound above; then nothing is cut
+        L = L < 0x1FFFFFFC ? 2 * L : 0x3FFFFFFC;        // more cut items than slots: coarser cuts (in the end none)
     }
     if (tid == 0) plan[0] = make_int4(cut_total + whole_total, cut_total, L, 0);
     int cs = cut_at, ws = cut_total + whole_at;
@@ -1070,7 +1078,7 @@ inline SparseWorkspace sparse_workspace(int64_t N, int Hl, int d) {
     const int64_t nblk4 = (((N + kDkvBQ - 1) / kDkvBQ) + 3) & ~(int64_t)3;
     auto up = [](int64_t x) { return (x + 63) & ~(int64_t)63; };
     SparseWorkspace w;
-    w.items_bound = plan_items_bound(n_ktiles, Hl);
+    w.items_bound = plan_items_bound(n_ktiles, nblk4, Hl);
     w.slots_per_head = plan_slots_per_head(n_ktiles, nblk4, Hl);
     w.plan_at = up(2 * stats_stride(N) * Hl);
     w.red_at = up(w.plan_at + 4 * (1 + w.items_bound));

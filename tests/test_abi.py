@@ -204,7 +204,7 @@ def test_sparse_attention_validation(lib):
     assert lib.ulysses_sparse_attn_bwd_workspace_bytes(600, 2, 100) == 0
     g = lambda **kw: lib.ulysses_sparse_attn_bwd(*[{**dict(q=A, k=B, v=C_, o=D_, do=0x70000000, lse=0x7800000,
                                                             dq=0x80000000, dk=0x90000000, dv=0xA0000000, rp=RP, ci=CI,
-                                                            cp=CP, ri=RI, ws=0xB0000000, wsb=1 << 20, N=600, Hl=2, d=64,
+                                                            cp=CP, ri=RI, ws=0xB0000000, wsb=4 << 20, N=600, Hl=2, d=64,
                                                             scale=0.125, layout=0), **kw}[n]
                                                    for n in ("q", "k", "v", "o", "do", "lse", "dq", "dk", "dv", "rp", "ci",
                                                              "cp", "ri", "ws", "wsb", "N", "Hl", "d", "scale", "layout")],
