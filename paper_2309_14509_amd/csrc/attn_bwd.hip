@@ -16,8 +16,6 @@
 namespace uly {
 namespace ULY_ELEM_NS {
 
-constexpr int kBwdThreads = 256;
-
 // ------------------------------------------------------------------------------------------
 // Row statistics for the backward kernels, in a padded [Hl, stride] layout (stride >= N rounded up to 128, + 64):
 //   delta[h, i] = sum_c dO[i,h,c] * O[i,h,c]        lse2[h, i] = LSE[h, i] * log2(e)
@@ -451,7 +449,6 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     constexpr int TB = TILE * 2;                // bytes per tile
     constexpr int QB = 0, DOB = kDkvRing * TB;  // byte offsets of the Q ring and the dO ring
     constexpr int HALF = 16 * D * 2;            // bytes per 16 rows
-    constexpr int ROW8 = 8 * D * 2;
     constexpr int STAT = 512;                   // bytes per ring slot of row statistics: 64 lse2, 64 delta
     using Loader = DirectTile<D, kDkvBQ, kDkvWaves, SwzBoth>;
     constexpr int LPT = 2 * Loader::kPerWave + 2;   // global loads per wave per tile (Q, dO, lse2, delta)

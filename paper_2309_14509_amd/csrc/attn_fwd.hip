@@ -206,7 +206,6 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
                         __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         constexpr int VB = decltype(vb_tag)::value;        // this block's V rows
-        constexpr int KN = decltype(kn_tag)::value;        // next block's K rows
         constexpr int KFREE = decltype(kfree_tag)::value;  // >= 0: last block of a tile; buffers to refill
         constexpr int VFREE = decltype(vfree_tag)::value;
         constexpr bool LAST = KFREE >= 0;
