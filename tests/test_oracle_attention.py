@@ -34,7 +34,7 @@ def _numpy_attn(q, k, v, scale, causal):
 
 
 @pytest.mark.parametrize("causal", [True, False])
-@pytest.mark.parametrize("N,Hl,d", [(1, 1, 4), (5, 2, 8), (33, 3, 16), (130, 2, 64)])
+@pytest.mark.parametrize("N,Hl,d", [(1, 1, 4), (5, 2, 8), (33, 3, 16), (130, 2, 64), (70, 2, 256)])
 def test_forward_equals_dense_numpy(N, Hl, d, causal):
     q, k, v, _ = _inputs(N, Hl, d)
     scale = 1.0 / np.sqrt(d)
@@ -136,7 +136,7 @@ def _torch_grads(q, k, v, do, scale, causal):
 
 
 @pytest.mark.parametrize("causal", [True, False])
-@pytest.mark.parametrize("N,Hl,d", [(1, 1, 4), (7, 2, 8), (65, 2, 32)])
+@pytest.mark.parametrize("N,Hl,d", [(1, 1, 4), (7, 2, 8), (65, 2, 32), (40, 1, 256)])
 def test_backward_equals_torch_autograd(N, Hl, d, causal):
     q, k, v, do = _inputs(N, Hl, d, seed=11)
     scale = 1.0 / np.sqrt(d)
