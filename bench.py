@@ -51,10 +51,11 @@ def main() -> int:
     ap.add_argument("--xattn", default="",
                     help="also time attention without a mask for these (queries, keys) counts, e.g. "
                          "'131072x131072,16384x131072': rows of the same tensors (extra 'xattn' list in the output)")
-    ap.add_argument("--sparse-pattern", choices=["window_global", "fixed"], default="window_global",
+    ap.add_argument("--sparse-pattern", choices=["window_global", "fixed", "global_rows"], default="window_global",
                     help="with --sparse-window W: 'window_global' = blocks r - c < W plus the first block column; "
                          "'fixed' = windows of W blocks, a block row sees its own window and the last block of every "
-                         "earlier window")
+                         "earlier window; 'global_rows' = blocks r - c < W, and every 64th block row sees everything "
+                         "before it")
     ap.add_argument("--elem", choices=["bf16", "fp16"], default="bf16",
                     help="element type of the tensors (the headline metric is bf16)")
     args = ap.parse_args()
@@ -291,19 +292,23 @@ def main() -> int:
         if args.sparse_pattern == "fixed":
             mask = (bi // W == bj // W) | ((bj % W == W - 1) & (bj < (bi // W) * W))
             pat_name = f"windows of {W} blocks; a block row sees its own window and the last block of every earlier window"
+        elif args.sparse_pattern == "global_rows":
+            mask = (bi - bj < W) | (bi % 64 == 63)
+            pat_name = f"window of {W} blocks; every 64th block row sees everything before it"
         else:
             mask = (bi - bj < W) | (bj == 0)
             pat_name = f"window of {W} blocks + first block column"
         pat = uly.SparsePattern(mask)
         pd = pat.dev
         sws = torch.empty(int(lib.ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d)), dtype=torch.uint8, device="cuda")
+        sfw = torch.empty(int(lib.ulysses_sparse_attn_fwd_workspace_bytes(N, Hl, d)), dtype=torch.uint8, device="cuda")
         sp_ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
         def sparse_step():
             sp_ev[0].record(stream)
             uly._check(lib.ulysses_sparse_attn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse),
-                                                   ptr(pd["row_ptr"]), ptr(pd["col_idx"]), N, Hl, d, scale,
-                                                   lay, sp), "sparse_attn_fwd")
+                                                   ptr(pd["row_ptr"]), ptr(pd["col_idx"]), ptr(sfw), sfw.numel(), N, Hl,
+                                                   d, scale, lay, sp), "sparse_attn_fwd")
             sp_ev[1].record(stream)
             uly._check(lib.ulysses_sparse_attn_bwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(dout), ptr(lse),
                                                    ptr(grads[0]), ptr(grads[1]), ptr(grads[2]), ptr(pd["row_ptr"]),

@@ -194,16 +194,25 @@ int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o
  * breaks these rules is undefined behaviour (the Python binding builds and checks them on the host).
  * Other arguments, precision and status codes are those of ulysses_attn_fwd / _bwd with causal = 1;
  * the pattern arrays must be non-NULL and 4-byte aligned.
- * Workspace of the backward (caller-owned device memory, ulysses_sparse_attn_bwd_workspace_bytes;
- * 0 for a shape the library rejects): the row statistics of the dense backward, a work plan the
- * library derives from col_ptr on the device, and fp32 partial sums for block columns so long that
- * several workgroups share one (at most 8192 slots of 128 keys x d x 2 tensors: 1 GiB at d = 128,
- * and never more than two slots per 128 keys and head, so short sequences take little).  The sums are added in a fixed order: results are deterministic.
+ * Workspaces (caller-owned device memory, 16-byte aligned, required for N > 0; the *_workspace_bytes
+ * functions return 0 for a shape the library rejects).  Both hold a work plan that the library derives
+ * from the pattern on the device: one workgroup per tile would leave the launch waiting for a few long
+ * block rows or columns (global tokens, summary blocks), so tiles whose walk is long are cut into
+ * several work items whose fp32 partial results a second kernel merges in a fixed order (results are
+ * deterministic).  Forward: the plan and the partial results of cut block rows (at most one slot of
+ * 256 queries x (d + 2) floats per query tile and head, and at most 2048 in all).  Backward: the row
+ * statistics of the dense backward, plans, and partial sums of cut block columns (dK/dV: at most 8192
+ * slots of 128 keys x d x 2 tensors, 1 GiB at d = 128, never more than two per 128 keys and head) and
+ * of cut block rows (dQ: at most 4096 slots of 128 queries x d, never more than one per 128 queries
+ * and head).  A pattern that would need more slots gets coarser cuts.
+ * Sequences beyond ULY_SPARSE_MAX_N tokens are ULY_ERR_SHAPE (work items are a grid dimension).
  * ------------------------------------------------------------------------------------------- */
 #define ULY_SPARSE_BLOCK 256
-#define ULY_SPARSE_BWD_MAX_N 8000000   /* longer sequences: ULY_ERR_SHAPE from ulysses_sparse_attn_bwd */
+#define ULY_SPARSE_MAX_N 8000000
+size_t ulysses_sparse_attn_fwd_workspace_bytes(int64_t N, int Hl, int d);
 int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                             const int32_t* row_ptr, const int32_t* col_idx,
+                            void* workspace, size_t workspace_bytes,
                             int64_t N, int Hl, int d, float scale, int layout, void* stream);
 size_t ulysses_sparse_attn_bwd_workspace_bytes(int64_t N, int Hl, int d);
 int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout,

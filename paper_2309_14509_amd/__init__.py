@@ -20,7 +20,8 @@ EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack
            "ulysses_pack_qkv", "ulysses_unpack_qkv", "ulysses_pack_rev_qkv", "ulysses_unpack_rev_qkv",
            "ulysses_xattn_fwd_workspace_bytes", "ulysses_xattn_fwd", "ulysses_xattn_bwd_workspace_bytes",
            "ulysses_xattn_bwd",
-           "ulysses_sparse_attn_fwd", "ulysses_sparse_attn_bwd_workspace_bytes", "ulysses_sparse_attn_bwd",
+           "ulysses_sparse_attn_fwd_workspace_bytes", "ulysses_sparse_attn_fwd",
+           "ulysses_sparse_attn_bwd_workspace_bytes", "ulysses_sparse_attn_bwd",
            "ulysses_probe_mfma",
            "ulysses_attn_fwd", "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd", "ulysses_attn_bwd_stage",
            "ulysses_status_string", "ulysses_abi_version")
@@ -65,7 +66,9 @@ def load(path: str | None = None):
     lib.ulysses_xattn_bwd_workspace_bytes.argtypes = [i64, i64, ci, ci]
     lib.ulysses_xattn_bwd_workspace_bytes.restype = sz
     lib.ulysses_xattn_bwd.argtypes = [vp] * 10 + [sz, i64, i64, ci, ci, cf, ci, vp]
-    lib.ulysses_sparse_attn_fwd.argtypes = [vp] * 7 + [i64, ci, ci, cf, ci, vp]
+    lib.ulysses_sparse_attn_fwd_workspace_bytes.argtypes = [i64, ci, ci]
+    lib.ulysses_sparse_attn_fwd_workspace_bytes.restype = sz
+    lib.ulysses_sparse_attn_fwd.argtypes = [vp] * 8 + [sz, i64, ci, ci, cf, ci, vp]
     lib.ulysses_sparse_attn_bwd_workspace_bytes.argtypes = [i64, ci, ci]
     lib.ulysses_sparse_attn_bwd_workspace_bytes.restype = sz
     lib.ulysses_sparse_attn_bwd.argtypes = [vp] * 14 + [sz, i64, ci, ci, cf, ci, vp]
@@ -342,19 +345,28 @@ def _pattern_for(pattern, N):
     return pattern.dev
 
 
+def ulysses_sparse_attn_fwd_workspace_bytes(N: int, Hl: int, d: int) -> int:
+    return int(load().ulysses_sparse_attn_fwd_workspace_bytes(N, Hl, d))
+
+
 def ulysses_sparse_attn_fwd(q, k, v, pattern: SparsePattern, scale: float, layout: int = LAYOUT_SEQ_HEAD,
-                            out=None, lse=None):
-    """Causal attention restricted to the blocks of ``pattern`` -> (o, lse)."""
+                            out=None, lse=None, workspace=None):
+    """Causal attention restricted to the blocks of ``pattern`` -> (o, lse).  ``workspace`` (uint8,
+    ulysses_sparse_attn_fwd_workspace_bytes) is allocated here unless the caller brings it."""
     import torch
     elem = _elem_flag(q, k, v)
     N, Hl, d = _attn_dims(q, layout)
     p = _pattern_for(pattern, N)
     o = torch.empty_like(q) if out is None else out
     lse = torch.empty((Hl, N), dtype=torch.float32, device=q.device) if lse is None else lse
+    if workspace is None:
+        workspace = torch.empty(max(ulysses_sparse_attn_fwd_workspace_bytes(N, Hl, d), 16), dtype=torch.uint8,
+                                device=q.device)
     w = "sparse_attn_fwd"
     _check(load().ulysses_sparse_attn_fwd(_dev(q, w), _dev(k, w), _dev(v, w), _dev(o, w), _dev(lse, w),
-                                          _dev(p["row_ptr"], w), _dev(p["col_idx"], w), N, Hl, d, scale, layout | elem,
-                                          _stream()), "ulysses_sparse_attn_fwd")
+                                          _dev(p["row_ptr"], w), _dev(p["col_idx"], w), _dev(workspace, w),
+                                          workspace.numel(), N, Hl, d, scale, layout | elem, _stream()),
+           "ulysses_sparse_attn_fwd")
     return o, lse
 
 

@@ -271,27 +271,40 @@ int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o
                             /*may_cut=*/1, layout, stream);
 }
 
+size_t ulysses_sparse_attn_fwd_workspace_bytes(int64_t N, int Hl, int d) {
+    uint64_t tb;
+    if (check_attn_common(N, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK || d == 256 || N == 0 || N > ULY_SPARSE_MAX_N)
+        return 0;
+    return (size_t)uly::bf16::attn_fwd_sparse_workspace_floats(N, Hl, d) * sizeof(float);
+}
+
 int ulysses_sparse_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* row_ptr,
-                            const int32_t* col_idx, int64_t N, int Hl, int d, float scale, int layout, void* stream) {
+                            const int32_t* col_idx, void* workspace, size_t workspace_bytes, int64_t N, int Hl, int d,
+                            float scale, int layout, void* stream) {
     uint64_t tb;
     const int rc = check_attn_common(N, Hl, d, layout, &tb);
     if (rc != ULY_OK) return rc;
     if (d == 256) return ULY_ERR_UNSUPPORTED;                    // the sparse kernels exist for d = 64 and 128
     if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;
     if (N == 0) return ULY_OK;
+    if (N > ULY_SPARSE_MAX_N) return ULY_ERR_SHAPE;              // the work items are a grid dimension
     if (!q || !k || !v || !o || !lse || !row_ptr || !col_idx) return ULY_ERR_NULL;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse)) return ULY_ERR_ALIGN;
+    const size_t need = ulysses_sparse_attn_fwd_workspace_bytes(N, Hl, d);
+    if (!workspace || workspace_bytes < need) return ULY_ERR_WORKSPACE;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) || misaligned(workspace))
+        return ULY_ERR_ALIGN;
     if (((uintptr_t)row_ptr | (uintptr_t)col_idx) & 3u) return ULY_ERR_ALIGN;
     const Range in[3] = {{q, tb}, {k, tb}, {v, tb}};
-    const Range out[2] = {{o, tb}, {lse, (uint64_t)N * Hl * 4u}};
+    const Range out[3] = {{o, tb}, {lse, (uint64_t)N * Hl * 4u}, {workspace, need}};
     if (any_alias(in, out)) return ULY_ERR_ALIAS;
     return (layout & ULY_ELEM_F16 ? uly::f16::attn_fwd_sparse_launch : uly::bf16::attn_fwd_sparse_launch)(
-        q, k, v, o, lse, row_ptr, col_idx, N, Hl, d, scale, uly::strides_for(layout & ~ULY_ELEM_F16, N, Hl, d), stream);
+        q, k, v, o, lse, (float*)workspace, row_ptr, col_idx, N, Hl, d, scale,
+        uly::strides_for(layout & ~ULY_ELEM_F16, N, Hl, d), stream);
 }
 
 size_t ulysses_sparse_attn_bwd_workspace_bytes(int64_t N, int Hl, int d) {
     uint64_t tb;
-    if (check_attn_common(N, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK || d == 256 || N == 0 || N > ULY_SPARSE_BWD_MAX_N)
+    if (check_attn_common(N, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK || d == 256 || N == 0 || N > ULY_SPARSE_MAX_N)
         return 0;
     return (size_t)uly::bf16::attn_bwd_sparse_workspace_floats(N, Hl, d) * sizeof(float);
 }
@@ -306,7 +319,7 @@ int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const v
     if (!(scale > 0.0f) || scale - scale != 0.0f) return ULY_ERR_UNSUPPORTED;
     if (d == 256) return ULY_ERR_UNSUPPORTED;
     if (N == 0) return ULY_OK;
-    if (N > ULY_SPARSE_BWD_MAX_N) return ULY_ERR_SHAPE;          // the work items of dK/dV are a grid dimension
+    if (N > ULY_SPARSE_MAX_N) return ULY_ERR_SHAPE;          // the work items of dK/dV are a grid dimension
     if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv || !row_ptr || !col_idx || !col_ptr || !row_idx)
         return ULY_ERR_NULL;
     const size_t need = ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d);

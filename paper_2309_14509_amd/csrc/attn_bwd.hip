@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     const int* __restrict__ row_ptr, const int* __restrict__ col_idx, const int4* __restrict__ plan,
     float* __restrict__ partial, int slots_per_head) {
     static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
-    static_assert(!PLAN || (!CAUSAL && !SPARSE), "only unmasked query tiles are cut into work items");
+    static_assert(!PLAN || SPARSE || !CAUSAL, "dense causal query tiles are paired, not planned");
     constexpr int NT = D / 16, NCB = D / 32;
     constexpr int TILE = kDqBK * D;
     constexpr int TB = TILE * 2;
@@ -94,8 +94,9 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     // upwards from the start of the sequence and those of the second downwards from its diagonal: at
     // any moment all workgroups that started together read one of only two key blocks, which keeps
     // the K/V stream in the L2 caches instead of re-fetching it per workgroup.
-    // PLAN (unmasked attention with few query tiles): grid (heads, work items); an item is a query tile
-    // and a range of its key blocks, the items of a tile write fp32 partial sums (see the plan kernels).
+    // PLAN (unmasked attention with few query tiles; block rows of a pattern): grid (heads, work items); an
+    // item is a query tile and a range of its walk, the items of a cut tile write fp32 partial sums (see the
+    // plan kernels).
     const int n_pairs = (CAUSAL && !SPARSE) ? (n_qtiles + 1) / 2 : n_qtiles;
     const int head = PLAN ? blockIdx.x : blockIdx.x / n_pairs;
     int pr = blockIdx.x - head * n_pairs;
@@ -362,7 +363,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         int bn[4];
         if (SPARSE) {
             const int b = blk(p + kDqRing);
-            const bool past = p + kDqRing >= cnt;
+            const bool past = p + kDqRing + (PLAN ? p_off : 0) >= cnt;
 #pragma unroll
             for (int i = 0; i < 4; ++i) bn[i] = past ? b : b + i;
         } else {
@@ -934,31 +935,38 @@ __device__ __forceinline__ int block_scan_exclusive(int v, int* sh, int* total) 
     return incl - v;
 }
 
-__global__ __launch_bounds__(kPlanThreads) void sparse_dkv_plan_kernel(const int* __restrict__ col_ptr, int n_ktiles,
-                                                                       int Hl, int slots_per_head,
-                                                                       int4* __restrict__ plan, int2* __restrict__ red) {
+// mode 0: key tiles of dK/dV walk query blocks (ptr = col_ptr);  mode 1: query tiles of dQ walk key blocks
+// (ptr = row_ptr);  mode 2: query tiles of the forward walk 64-key tiles (ptr = row_ptr).  Whole tiles are
+// listed longest first: ascending for columns, descending for rows (later rows see more).
+__global__ __launch_bounds__(kPlanThreads) void sparse_plan_kernel(int mode, const int* __restrict__ ptr, int n_tiles,
+                                                                   int N, int Hl, int slots_per_head, int target,
+                                                                   int4* __restrict__ plan, int2* __restrict__ red) {
     __shared__ int sh[kPlanThreads];
     __shared__ unsigned long long sh_total;
-    constexpr int BPS = kSparseBlockBwd / kDkvBQ, TPB = kSparseBlockBwd / kDkvBK;
     const int tid = threadIdx.x;
-    const int chunk = (n_ktiles + kPlanThreads - 1) / kPlanThreads;
-    const int k0 = tid * chunk < n_ktiles ? tid * chunk : n_ktiles;
-    const int k1 = k0 + chunk < n_ktiles ? k0 + chunk : n_ktiles;
-    auto count = [&](int kt) {
-        const int bcol = kt / TPB;
-        return (bcol + 1) * BPS - kt * (kDkvBK / kDkvBQ) + BPS * (col_ptr[bcol + 1] - col_ptr[bcol] - 1);
+    const int chunk = (n_tiles + kPlanThreads - 1) / kPlanThreads;
+    const int k0 = tid * chunk < n_tiles ? tid * chunk : n_tiles;
+    const int k1 = k0 + chunk < n_tiles ? k0 + chunk : n_tiles;
+    auto count = [&](int t) {
+        if (mode == 2) {                                   // forward: 256 queries, 4 tiles of 64 keys per sparse block
+            const int q0 = t * 256, k_end = q0 + 256 < N ? q0 + 256 : N;
+            return 4 * (ptr[t + 1] - ptr[t] - 1) + (k_end - q0 + 63) / 64;
+        }
+        const int b = t / 2, listed = ptr[b + 1] - ptr[b] - 1;   // 128-token tiles: two per sparse block, 8 blocks of 32
+        return 8 * listed + (mode == 0 ? 8 - 4 * (t & 1) : 4 + 4 * (t & 1));
     };
     if (tid == 0) sh_total = 0;
     __syncthreads();
     unsigned long long mine = 0;
-    for (int kt = k0; kt < k1; ++kt) mine += (unsigned long long)count(kt);
+    for (int t = k0; t < k1; ++t) mine += (unsigned long long)count(t);
     atomicAdd(&sh_total, mine);
     __syncthreads();
-    const unsigned long long want = (sh_total * (unsigned long long)Hl + kPlanTarget - 1) / kPlanTarget;
+    const unsigned long long want = (sh_total * (unsigned long long)Hl + target - 1) / target;
     int L = want > 0x3FFFFFFFull ? 0x3FFFFFFF : (int)want;
     L = (L + 3) & ~3;
-    L = L < kPlanMinLen ? kPlanMinLen : L;
-    // items of a column of cnt blocks: pieces of len blocks
+    const int min_len = mode == 2 ? kPlanMinLen / 2 : kPlanMinLen;      // 1024 tokens either way
+    L = L < min_len ? min_len : L;
+    // items of a tile that walks cnt units: pieces of len units
     auto piece_len = [&](int cnt) {
         const int n = (cnt + L - 1) / L;
         return (((cnt + n - 1) / n) + 3) & ~3;
@@ -966,8 +974,8 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_dkv_plan_kernel(const int
     int n_cut = 0, n_whole = 0, cut_total = 0, whole_total = 0, cut_at = 0, whole_at = 0;
     for (int attempt = 0; attempt < 24; ++attempt) {
         n_cut = n_whole = 0;
-        for (int kt = k0; kt < k1; ++kt) {
-            const int cnt = count(kt);
+        for (int t = k0; t < k1; ++t) {
+            const int cnt = count(t);
             if (cnt > L) n_cut += (cnt + piece_len(cnt) - 1) / piece_len(cnt);
             else ++n_whole;
         }
@@ -977,20 +985,27 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_dkv_plan_kernel(const int
         L = L < 0x1FFFFFFC ? 2 * L : 0x3FFFFFFC;        // more cut items than slots: coarser cuts (in the end none)
     }
     if (tid == 0) plan[0] = make_int4(cut_total + whole_total, cut_total, L, 0);
-    int cs = cut_at, ws = cut_total + whole_at;
-    for (int kt = k0; kt < k1; ++kt) {
-        const int cnt = count(kt);
+    int cs = cut_at, wi = whole_at;
+    for (int t = k0; t < k1; ++t) {
+        const int cnt = count(t);
         if (cnt > L) {
             const int len = piece_len(cnt), n = (cnt + len - 1) / len;
-            red[kt] = make_int2(cs, n);
+            red[t] = make_int2(cs, n);
             for (int i = 0; i < n; ++i, ++cs)
-                plan[1 + cs] = make_int4(kt, i * len, (i + 1) * len < cnt ? (i + 1) * len : cnt, 0);
+                plan[1 + cs] = make_int4(t, i * len, (i + 1) * len < cnt ? (i + 1) * len : cnt, 0);
         } else {
-            red[kt] = make_int2(-1, 1);
-            plan[1 + ws] = make_int4(kt, 0, cnt, 0);
-            ++ws;
+            red[t] = make_int2(-1, 1);
+            plan[1 + cut_total + (mode == 0 ? wi : whole_total - 1 - wi)] = make_int4(t, 0, cnt, 0);
+            ++wi;
         }
     }
+}
+
+int sparse_plan_launch(int mode, const int* ptr, int64_t n_tiles, int64_t N, int Hl, int slots_per_head, int target,
+                       void* plan, void* red, void* stream) {
+    sparse_plan_kernel<<<dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream>>>(
+        mode, ptr, (int)n_tiles, (int)N, Hl, slots_per_head, target, (int4*)plan, (int2*)red);
+    return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 
 // The same kind of plan for unmasked attention when one side has few tiles: every tile (key tile of
@@ -1063,24 +1078,35 @@ __global__ __launch_bounds__(256) void partial_reduce_kernel(const int4* __restr
 // padded row stride of the statistics arrays in the workspace
 inline int64_t stats_stride(int64_t N) { return ((N + 255) / 256) * 256 + 64; }   // covers whole sparse blocks
 
-// Workspace of the block-sparse backward, in floats from its start: the two statistics arrays, the
-// dK/dV work plan, the per-key-tile reduce table, the partial sums (each section 256-byte aligned).
+// Workspace of the block-sparse backward, in floats from its start: the two statistics arrays, then work
+// plan, per-tile reduce table and partial sums of the dK/dV kernel and the same three of the dQ kernel
+// (each section 256-byte aligned).
+constexpr int kRowPlanTarget = 2048;      // items the cut block rows are aimed at (dQ), over all heads
 struct SparseWorkspace {
-    int64_t plan_at, red_at, partial_at, total;
-    int64_t items_bound;
-    int slots_per_head;
+    int64_t plan_at, red_at, partial_at, q_plan_at, q_red_at, q_partial_at, total;
+    int64_t items_bound, q_items_bound;
+    int slots_per_head, q_slots_per_head;
 };
+inline int row_slots_per_head(int64_t n_tiles, int target, int Hl) {
+    const int64_t by_target = 2 * ((target + Hl - 1) / Hl), by_size = n_tiles + 1;    // at most one slot per tile
+    return (int)(by_target < by_size ? by_target : by_size);
+}
 inline SparseWorkspace sparse_workspace(int64_t N, int Hl, int d) {
-    const int64_t n_ktiles = (N + kDkvBK - 1) / kDkvBK;
+    const int64_t n_ktiles = (N + kDkvBK - 1) / kDkvBK, n_qtiles = (N + kDqBQ - 1) / kDqBQ;
     const int64_t nblk4 = (((N + kDkvBQ - 1) / kDkvBQ) + 3) & ~(int64_t)3;
     auto up = [](int64_t x) { return (x + 63) & ~(int64_t)63; };
     SparseWorkspace w;
     w.items_bound = plan_items_bound(n_ktiles, nblk4, Hl);
     w.slots_per_head = plan_slots_per_head(n_ktiles, nblk4, Hl);
+    w.q_slots_per_head = row_slots_per_head(n_qtiles, kRowPlanTarget, Hl);
+    w.q_items_bound = n_qtiles + w.q_slots_per_head + 1;
     w.plan_at = up(2 * stats_stride(N) * Hl);
     w.red_at = up(w.plan_at + 4 * (1 + w.items_bound));
     w.partial_at = up(w.red_at + 2 * n_ktiles);
-    w.total = w.partial_at + (int64_t)w.slots_per_head * Hl * 2 * kDkvBK * d;
+    w.q_plan_at = up(w.partial_at + (int64_t)w.slots_per_head * Hl * 2 * kDkvBK * d);
+    w.q_red_at = up(w.q_plan_at + 4 * (1 + w.q_items_bound));
+    w.q_partial_at = up(w.q_red_at + 2 * n_qtiles);
+    w.total = w.q_partial_at + (int64_t)w.q_slots_per_head * Hl * kDqBQ * d;
     return w;
 }
 
@@ -1216,13 +1242,12 @@ static int launch_bwd_sparse(const void* q, const void* k, const void* v, const 
     if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
     // work plan, then the items, then the sums of the cut columns
     const SparseWorkspace w = sparse_workspace(N, Hl, D);
-    if (w.items_bound > 65535 || Hl > 65535) return ULY_ERR_SHAPE;      // grid y dimensions
+    if (w.items_bound > 65535 || w.q_items_bound > 65535 || Hl > 65535) return ULY_ERR_SHAPE;      // grid y dimensions
     int4* plan = reinterpret_cast<int4*>(ws + w.plan_at);
     int2* red = reinterpret_cast<int2*>(ws + w.red_at);
     float* partial = ws + w.partial_at;
-    sparse_dkv_plan_kernel<<<dim3(1), dim3(kPlanThreads), 0, stream>>>(col_ptr, (int)n_ktiles, Hl, w.slots_per_head, plan,
-                                                                      red);
-    if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+    if (sparse_plan_launch(0, col_ptr, n_ktiles, N, Hl, w.slots_per_head, kPlanTarget, plan, red, stream) != ULY_OK)
+        return ULY_ERR_LAUNCH;
     attn_bwd_dkv_kernel<D, true, true><<<dim3((uint32_t)Hl, (uint32_t)w.items_bound), dim3(kDkvThreads), 0, stream>>>(
         Q, K, V, dO, lse2, delta, stride, (e16*)dk, (e16*)dv, (int)N, (int)N, (int)n_ktiles, st.row, st.head, st.head,
         scale, col_ptr, row_idx, plan, partial, w.slots_per_head);
@@ -1230,9 +1255,19 @@ static int launch_bwd_sparse(const void* q, const void* k, const void* v, const 
     partial_reduce_kernel<D, 2><<<dim3(kReduceBlocks, (uint32_t)Hl), dim3(256), 0, stream>>>(
         plan, red, partial, w.slots_per_head, (e16*)dk, (e16*)dv, (int)N, st.row, st.head);
     if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
-    attn_bwd_dq_kernel<D, true, true><<<dim3((uint32_t)(n_qtiles * Hl)), dim3(kDqThreads), 0, stream>>>(
-        Q, K, V, dO, lse2, delta, stride, (e16*)dq, (int)N, (int)N, (int)n_qtiles, st.row, st.head, st.head, scale,
-        row_ptr, col_idx, nullptr, nullptr, 0);
+    // the same for the block rows of the dQ kernel
+    int4* q_plan = reinterpret_cast<int4*>(ws + w.q_plan_at);
+    int2* q_red = reinterpret_cast<int2*>(ws + w.q_red_at);
+    float* q_partial = ws + w.q_partial_at;
+    if (sparse_plan_launch(1, row_ptr, n_qtiles, N, Hl, w.q_slots_per_head, kRowPlanTarget, q_plan, q_red, stream) != ULY_OK)
+        return ULY_ERR_LAUNCH;
+    attn_bwd_dq_kernel<D, true, true, true>
+        <<<dim3((uint32_t)Hl, (uint32_t)w.q_items_bound), dim3(kDqThreads), 0, stream>>>(
+            Q, K, V, dO, lse2, delta, stride, (e16*)dq, (int)N, (int)N, (int)n_qtiles, st.row, st.head, st.head, scale,
+            row_ptr, col_idx, q_plan, q_partial, w.q_slots_per_head);
+    if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+    partial_reduce_kernel<D, 1><<<dim3(kReduceBlocks, (uint32_t)Hl), dim3(256), 0, stream>>>(
+        q_plan, q_red, q_partial, w.q_slots_per_head, (e16*)dq, nullptr, (int)N, st.row, st.head);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 

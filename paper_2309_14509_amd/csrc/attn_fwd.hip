@@ -36,11 +36,13 @@ constexpr bool kFwdPair = false;
 constexpr int kSparseBlock = 256;
 static_assert(kFwdBQ == kSparseBlock && kSparseBlock % kFwdBK == 0, "a query tile must be one sparse block row");
 
-// CUT (unmasked attention with few query tiles): grid (heads, query tiles x pieces); a workgroup
-// takes `cut_len` key tiles of its query tile and writes, instead of O and LSE, what the combine kernel
-// needs to merge the pieces: the unnormalised fp32 accumulators and, per query, the maximum the
-// exponentials were taken against and the sum of the exponentials.
-//   part_o [head][item][256 queries][D] fp32,   part_ml [head][item][256 queries][2] fp32 (max, sum)
+// CUT: grid (heads, work items); a workgroup takes a range of the key tiles of its query tile and, when the
+// tile has several such items, writes instead of O and LSE what the combine kernel needs to merge them:
+// the unnormalised fp32 accumulators and, per query, the maximum the exponentials were taken against and
+// the sum of the exponentials.
+//   unmasked attention with few query tiles: item = query tile x piece of `cut_len` tiles (closed form);
+//   block-sparse: items come from a device-made plan (long block rows are cut, see sparse_plan_launch).
+//   part_o [head][slot][256 queries][D] fp32,   part_ml [head][slot][256 queries][2] fp32 (max, sum)
 template <int D, bool CAUSAL, bool SPARSE = false, bool CUT = false>
 __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __restrict__ Q, const e16* __restrict__ K,
                                                                    const e16* __restrict__ V, e16* __restrict__ O,
@@ -49,9 +51,10 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
                                                                    float scale, const int* __restrict__ row_ptr,
                                                                    const int* __restrict__ col_idx, int cut_pieces,
                                                                    int cut_len, float* __restrict__ part_o,
-                                                                   float* __restrict__ part_ml) {
+                                                                   float* __restrict__ part_ml,
+                                                                   const int4* __restrict__ plan, int slots_per_head) {
     static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
-    static_assert(!CUT || (!CAUSAL && !SPARSE), "only unmasked query tiles are cut into work items");
+    static_assert(!CUT || SPARSE || !CAUSAL, "dense causal query tiles are not cut into work items");
     constexpr int NT = D / 16;              // contraction steps over the head dim
     constexpr int NCB = D / 32;             // 32-channel blocks of the output
     constexpr int TILE = kFwdBK * D;        // elements per LDS tile
@@ -80,8 +83,22 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
     // the K/V stream in the L2 caches instead of re-fetching it per workgroup.
     const int n_pairs = (CAUSAL && kFwdPair && !SPARSE) ? (n_qtiles + 1) / 2 : n_qtiles;
     const int head = CUT ? blockIdx.x : blockIdx.x / n_pairs;
-    const int pr = CUT ? blockIdx.y / cut_pieces : blockIdx.x - head * n_pairs;
-    const int t_off = CUT ? (blockIdx.y - pr * cut_pieces) * cut_len : 0;      // first key tile of this piece
+    int pr = blockIdx.x - head * n_pairs;
+    int t_off = 0, t_len = 0, slot = -1;          // CUT: first key tile (walk position) of this item, their number
+    if (CUT && SPARSE) {
+        const int4 hdr = plan[0];                 // {items, items that write partial results, ..}
+        if ((int)blockIdx.y >= hdr.x) return;     // the grid is an upper bound on the number of items
+        const int4 it = plan[1 + blockIdx.y];     // {query tile, first walk position, end, -}
+        pr = it.x;
+        t_off = it.y;
+        t_len = it.z - it.y;
+        slot = (int)blockIdx.y < hdr.y ? (int)blockIdx.y : -1;
+    } else if (CUT) {
+        pr = blockIdx.y / cut_pieces;
+        t_off = (blockIdx.y - pr * cut_pieces) * cut_len;
+        t_len = cut_len;
+        slot = blockIdx.y;
+    }
     const int64_t hoff = (int64_t)head * head_stride;
     const e16* Qh = Q + hoff;
     // N queries attend to Nk keys (Nk = N for self-attention); K and V may have their own head stride
@@ -120,7 +137,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
     const int n_parts = (CAUSAL && kFwdPair && !SPARSE && n_qtiles - 1 - pr != pr) ? 2 : 1;
 #pragma unroll 1
     for (int part = 0; part < n_parts; ++part) {
-    const int qt = (CAUSAL && part == 0) ? n_qtiles - 1 - pr : pr;
+    const int qt = (!CUT && CAUSAL && part == 0) ? n_qtiles - 1 - pr : pr;
     const int dir = part == 0 ? 1 : -1;                        // walking direction over the key tiles
     const int q0 = qt * kFwdBQ;
     int k_end = Nk;
@@ -133,9 +150,9 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
         // every listed block but the last (the diagonal one) is entirely visible: TPB tiles each
         n_kt = TPB * (row_ptr[qt + 1] - sp0 - 1) + (k_end - q0 + kFwdBK - 1) / kFwdBK;
     }
-    if (CUT) n_kt = n_kt - t_off < cut_len ? n_kt - t_off : cut_len;
+    if (CUT) n_kt = n_kt - t_off < t_len ? n_kt - t_off : t_len;
     auto tile_of = [&](int pos) __attribute__((always_inline)) {
-        if (SPARSE) return TPB * col_idx[sp0 + pos / TPB] + pos % TPB;
+        if (SPARSE) return TPB * col_idx[sp0 + (pos + t_off) / TPB] + (pos + t_off) % TPB;
         if (CUT) return t_off + pos;
         return dir > 0 ? pos : n_kt - 1 - pos;
     };
@@ -362,10 +379,10 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
     // ---- epilogue: normalise, store O (element type) and LSE (natural log)
     const float l_tot = xhalf_sum(l_run);
     const float inv = 1.f / l_tot;
-    if (CUT) {
-        const int64_t slot = (int64_t)head * gridDim.y + blockIdx.y;
+    if (CUT && slot >= 0) {
+        const int64_t at = (int64_t)head * slots_per_head + slot;
         const int row = wave * 32 + ln;
-        float* prow = part_o + (slot * kFwdBQ + row) * D;
+        float* prow = part_o + (at * kFwdBQ + row) * D;
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
@@ -376,8 +393,8 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
                 *reinterpret_cast<f32x4*>(prow + 32 * cb + 8 * rq + 4 * g) = w;
             }
         if (g == 0) {
-            part_ml[(slot * kFwdBQ + row) * 2] = m_used;
-            part_ml[(slot * kFwdBQ + row) * 2 + 1] = l_tot;
+            part_ml[(at * kFwdBQ + row) * 2] = m_used;
+            part_ml[(at * kFwdBQ + row) * 2 + 1] = l_tot;
         }
     } else if (q_row < N) {
         e16* orow = O + hoff + (int64_t)q_row * row_stride;
@@ -399,15 +416,25 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
 // Merges the pieces of the cut query tiles: with m = max_i m_i and w_i = exp(scale (m_i - m)),
 //   l = sum_i w_i l_i,   O = sum_i w_i O_i / l,   LSE = scale m + log l        (pieces in a fixed order).
 // Grid (query tiles x 32, heads): a workgroup merges 8 query rows, 32 lanes per row (D / 32 floats each).
+// `red` (block-sparse: from the plan) gives a tile's first slot and its number of pieces; without it every tile has
+// `pieces` consecutive slots.
 template <int D>
 __global__ __launch_bounds__(256) void attn_fwd_combine_kernel(const float* __restrict__ part_o,
                                                                const float* __restrict__ part_ml, int pieces,
+                                                               const int2* __restrict__ red, int slots_per_head,
                                                                e16* __restrict__ O, float* __restrict__ LSE, int N,
                                                                int64_t row_stride, int64_t head_stride, float scale) {
     constexpr int PER = D / 32;                                       // floats per lane and row
     constexpr int GROUPS = kFwdBQ / 8;                                // row groups per query tile
     const int qt = blockIdx.x / GROUPS, head = blockIdx.y;
-    const int64_t slot0 = ((int64_t)head * (gridDim.x / GROUPS) + qt) * pieces;   // the pieces of a tile are consecutive items
+    int first = qt * pieces;
+    if (red) {
+        const int2 r = red[qt];
+        if (r.y <= 1) return;                                         // not cut: its workgroup wrote O and LSE itself
+        first = r.x;
+        pieces = r.y;
+    }
+    const int64_t slot0 = (int64_t)head * slots_per_head + first;     // the pieces of a tile are consecutive slots
     const float sl2 = scale * kLog2e;
     {
         const int r = (blockIdx.x % GROUPS) * 8 + threadIdx.x / 32;
@@ -472,10 +499,10 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
         float* part_ml = ws + items * Hl * (int64_t)kFwdBQ * D;
         attn_fwd_kernel<D, false, false, true><<<dim3((uint32_t)Hl, (uint32_t)items), dim3(kFwdThreads), 0, stream>>>(
             (const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
-            kv.head, scale, nullptr, nullptr, cut.pieces, cut.len, part_o, part_ml);
+            kv.head, scale, nullptr, nullptr, cut.pieces, cut.len, part_o, part_ml, nullptr, (int)items);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
         attn_fwd_combine_kernel<D><<<dim3((uint32_t)(n_qtiles * (kFwdBQ / 8)), (uint32_t)Hl), dim3(256), 0, stream>>>(
-            part_o, part_ml, cut.pieces, (e16*)o, lse, (int)N, st.row, st.head, scale);
+            part_o, part_ml, cut.pieces, nullptr, (int)items, (e16*)o, lse, (int)N, st.row, st.head, scale);
         return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
     }
     const int64_t blocks = ((causal && kFwdPair) ? (n_qtiles + 1) / 2 : n_qtiles) * Hl;    // causal: pairs of query tiles
@@ -484,30 +511,65 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
     if (causal)
         attn_fwd_kernel<D, true><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
                                                              lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
-                                                             nullptr, nullptr, 1, 0, nullptr, nullptr);
+                                                             nullptr, nullptr, 1, 0, nullptr, nullptr, nullptr, 0);
     else
         attn_fwd_kernel<D, false><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v,
                                                               (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
-                                                              kv.head, scale, nullptr, nullptr, 1, 0, nullptr, nullptr);
+                                                              kv.head, scale, nullptr, nullptr, 1, 0, nullptr, nullptr, nullptr, 0);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 
-int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, const int* row_ptr,
-                           const int* col_idx, int64_t N, int Hl, int d, float scale, TensorStrides st, void* stream) {
+// Workspace of the block-sparse forward, in floats: work plan, per-tile table, partial results of the cut
+// block rows (at most one slot per query tile and head, and no more than the target asks for).
+constexpr int kFwdRowPlanTarget = 1024;
+struct SparseFwdWorkspace {
+    int64_t plan_at, red_at, part_o_at, part_ml_at, total, items_bound;
+    int slots_per_head;
+};
+inline SparseFwdWorkspace sparse_fwd_workspace(int64_t N, int Hl, int d) {
     const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ;
-    const int64_t blocks = n_qtiles * Hl;
-    if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
-    dim3 grid((uint32_t)blocks), block(kFwdThreads);
-    hipStream_t s = (hipStream_t)stream;
-    if (d == 128)
-        attn_fwd_kernel<128, true, true><<<grid, block, 0, s>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
-                                                                lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head,
-                                                                st.head, scale, row_ptr, col_idx, 1, 0, nullptr, nullptr);
-    else
-        attn_fwd_kernel<64, true, true><<<grid, block, 0, s>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
-                                                               lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head,
-                                                               st.head, scale, row_ptr, col_idx, 1, 0, nullptr, nullptr);
+    auto up = [](int64_t x) { return (x + 63) & ~(int64_t)63; };
+    SparseFwdWorkspace w;
+    const int64_t by_target = 2 * ((kFwdRowPlanTarget + Hl - 1) / Hl), by_size = n_qtiles + 1;
+    w.slots_per_head = (int)(by_target < by_size ? by_target : by_size);
+    w.items_bound = n_qtiles + w.slots_per_head + 1;
+    w.plan_at = 0;
+    w.red_at = up(4 * (1 + w.items_bound));
+    w.part_o_at = up(w.red_at + 2 * n_qtiles);
+    w.part_ml_at = up(w.part_o_at + (int64_t)w.slots_per_head * Hl * kFwdBQ * d);
+    w.total = w.part_ml_at + (int64_t)w.slots_per_head * Hl * kFwdBQ * 2;
+    return w;
+}
+int64_t attn_fwd_sparse_workspace_floats(int64_t N, int Hl, int d) { return sparse_fwd_workspace(N, Hl, d).total; }
+
+template <int D>
+static int launch_fwd_sparse(const void* q, const void* k, const void* v, void* o, float* lse, float* ws,
+                             const int* row_ptr, const int* col_idx, int64_t N, int Hl, float scale, TensorStrides st,
+                             hipStream_t stream) {
+    const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ;
+    const SparseFwdWorkspace w = sparse_fwd_workspace(N, Hl, D);
+    if (w.items_bound > 65535 || Hl > 65535 || n_qtiles * (kFwdBQ / 8) > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
+    int4* plan = reinterpret_cast<int4*>(ws + w.plan_at);
+    int2* red = reinterpret_cast<int2*>(ws + w.red_at);
+    float* part_o = ws + w.part_o_at;
+    float* part_ml = ws + w.part_ml_at;
+    if (sparse_plan_launch(2, row_ptr, n_qtiles, N, Hl, w.slots_per_head, kFwdRowPlanTarget, plan, red, stream) != ULY_OK)
+        return ULY_ERR_LAUNCH;
+    attn_fwd_kernel<D, true, true, true><<<dim3((uint32_t)Hl, (uint32_t)w.items_bound), dim3(kFwdThreads), 0, stream>>>(
+        (const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse, (int)N, (int)N, (int)n_qtiles, st.row, st.head, st.head,
+        scale, row_ptr, col_idx, 1, 0, part_o, part_ml, plan, w.slots_per_head);
+    if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+    attn_fwd_combine_kernel<D><<<dim3((uint32_t)(n_qtiles * (kFwdBQ / 8)), (uint32_t)Hl), dim3(256), 0, stream>>>(
+        part_o, part_ml, 0, red, w.slots_per_head, (e16*)o, lse, (int)N, st.row, st.head, scale);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
+}
+
+int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, float* ws,
+                           const int* row_ptr, const int* col_idx, int64_t N, int Hl, int d, float scale,
+                           TensorStrides st, void* stream) {
+    if (d == 128)
+        return launch_fwd_sparse<128>(q, k, v, o, lse, ws, row_ptr, col_idx, N, Hl, scale, st, (hipStream_t)stream);
+    return launch_fwd_sparse<64>(q, k, v, o, lse, ws, row_ptr, col_idx, N, Hl, scale, st, (hipStream_t)stream);
 }
 
 int64_t attn_fwd_cut_workspace_floats(int64_t N, int64_t Nk, int Hl, int d) {

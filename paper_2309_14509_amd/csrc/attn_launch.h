@@ -12,8 +12,11 @@ int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float*
                     int Hl, int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
 
 // Block-sparse causal forward: keys restricted to the 256-key blocks of a CSR pattern (device arrays).
-int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, const int* row_ptr,
-                           const int* col_idx, int64_t N, int Hl, int d, float scale, TensorStrides st, void* stream);
+// `ws`: attn_fwd_sparse_workspace_floats floats of scratch (work plan; partial results of block rows that are cut).
+int64_t attn_fwd_sparse_workspace_floats(int64_t N, int Hl, int d);
+int attn_fwd_sparse_launch(const void* q, const void* k, const void* v, void* o, float* lse, float* ws,
+                           const int* row_ptr, const int* col_idx, int64_t N, int Hl, int d, float scale,
+                           TensorStrides st, void* stream);
 
 // floats of scratch the backward kernels need (padded row statistics: delta and lse*log2e); N = queries
 int64_t attn_bwd_workspace_floats(int64_t N, int Hl);
@@ -47,3 +50,9 @@ int attn256_fwd_launch(const void* q, const void* k, const void* v, void* o, flo
 int attn256_bwd_launch(int stage_mask, const void* q, const void* k, const void* v, const void* dout, const float* delta,
                        const float* lse2, int64_t stride, void* dq, void* dk, void* dv, int64_t N, int64_t Nk, int Hl,
                        float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
+
+// Work plan of a block-sparse kernel, made on the device from one of the pattern's pointer arrays (mode 0: key
+// tiles of dK/dV from col_ptr, 1: query tiles of dQ from row_ptr, 2: query tiles of the forward from row_ptr):
+// tiles whose walk is long are cut into items; plan = int4[1 + items], red = int2[tiles].
+int sparse_plan_launch(int mode, const int* ptr, int64_t n_tiles, int64_t N, int Hl, int slots_per_head, int target,
+                       void* plan, void* red, void* stream);

@@ -187,10 +187,14 @@ def test_cross_attention_validation(lib):
 
 def test_sparse_attention_validation(lib):
     RP, CI, CP, RI = 0xC0000000, 0xC1000000, 0xC2000000, 0xC3000000
-    f = lambda **kw: lib.ulysses_sparse_attn_fwd(*[{**dict(q=A, k=B, v=C_, o=D_, lse=0x7000000, rp=RP, ci=CI, N=600, Hl=2,
-                                                            d=64, scale=0.125, layout=0), **kw}[n]
-                                                   for n in ("q", "k", "v", "o", "lse", "rp", "ci", "N", "Hl", "d", "scale",
-                                                             "layout")], None)
+    f = lambda **kw: lib.ulysses_sparse_attn_fwd(*[{**dict(q=A, k=B, v=C_, o=D_, lse=0x7000000, rp=RP, ci=CI, ws=0xB0000000,
+                                                            wsb=4 << 20, N=600, Hl=2, d=64, scale=0.125, layout=0), **kw}[n]
+                                                   for n in ("q", "k", "v", "o", "lse", "rp", "ci", "ws", "wsb", "N", "Hl", "d",
+                                                             "scale", "layout")], None)
+    fneed = lib.ulysses_sparse_attn_fwd_workspace_bytes(600, 2, 64)
+    assert 0 < fneed <= 4 << 20 and f(ws=None) == 6 and f(wsb=fneed - 1) == 6 and f(ws=0xB0000004) == 4 and f(ws=A) == 5
+    assert lib.ulysses_sparse_attn_fwd_workspace_bytes(1 << 20, 4, 128) <= 2048 * 256 * 130 * 4 + (4 << 20)
+    assert lib.ulysses_sparse_attn_fwd_workspace_bytes(0, 2, 64) == 0 and f(N=8000001) == 2
     assert f(rp=None) == 1 and f(ci=None) == 1 and f(v=None) == 1
     assert f(N=-1) == 2 and f(d=100) == 3 and f(scale=-1.0) == 3
     assert f(d=256) == 3 and _fwd(lib, d=256, N=0) == 0         # d = 256: dense attention only
@@ -199,7 +203,8 @@ def test_sparse_attention_validation(lib):
     # statistics as for the dense backward, plus a work plan and a bounded number of fp32 partial-sum slots
     assert lib.ulysses_sparse_attn_bwd_workspace_bytes(600, 2, 64) > lib.ulysses_attn_bwd_workspace_bytes(600, 2, 64)
     big, slot = lib.ulysses_sparse_attn_bwd_workspace_bytes(1 << 20, 4, 128), 2 * 128 * 128 * 4
-    assert big - lib.ulysses_attn_bwd_workspace_bytes(1 << 20, 4, 128) <= 8192 * slot + (1 << 20)
+    # dK/dV: at most 8192 slots of two 128 x d fp32 tensors; dQ: at most 4096 slots of one; plans and tables: a few MiB
+    assert big - lib.ulysses_attn_bwd_workspace_bytes(1 << 20, 4, 128) <= 8192 * slot + 4096 * slot // 2 + (4 << 20)
     assert lib.ulysses_sparse_attn_bwd_workspace_bytes(0, 4, 128) == 0
     assert lib.ulysses_sparse_attn_bwd_workspace_bytes(600, 2, 100) == 0
     g = lambda **kw: lib.ulysses_sparse_attn_bwd(*[{**dict(q=A, k=B, v=C_, o=D_, do=0x70000000, lse=0x7800000,

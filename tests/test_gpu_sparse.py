@@ -23,6 +23,9 @@ def _mask(nb, kind, seed):
     elif kind == "window_global":          # local window of 2 blocks plus the first block column
         i, j = np.indices((nb, nb))
         m = (i - j < 2) | (j == 0)
+    elif kind == "global_rows":            # local window of 2 blocks; every fifth block row sees everything before it
+        i, j = np.indices((nb, nb))
+        m = (i - j < 2) | (i % 5 == 4)
     else:
         m = rng.random((nb, nb)) < 0.4
     m = np.tril(m)
@@ -74,15 +77,21 @@ def test_long_block_columns_are_cut_into_several_work_items(gpu_lib, N, Hl, d, k
     _check(gpu_lib, N, Hl, d, kind, seed=11)
 
 
+@pytest.mark.parametrize("N,Hl,d,layout", [(6000, 2, 128, 0), (7300, 3, 64, 1), (2400, 1, 128, 0)])
+def test_long_block_rows_are_cut_into_several_work_items(gpu_lib, N, Hl, d, layout):
+    """Block rows of up to 29 visible blocks among rows of two: the dQ kernel cuts the long ones into work items."""
+    _check(gpu_lib, N, Hl, d, "global_rows", layout=layout, seed=13)
+
+
 def test_head_major_and_odd_heads(gpu_lib):
     _check(gpu_lib, 1100, 3, 128, "random", layout=1, seed=3)
 
 
 def test_full_pattern_agrees_with_the_dense_kernels(gpu_lib):
-    N, Hl, d = 1280, 2, 128
+    N, Hl, d = 1024, 2, 128                  # four block rows: none long enough to be cut into work items
     q, k, v, do = synth.attention_inputs(N, Hl, d, 9)
     tq, tk, tv, tdo = (to_gpu_bf16(a) for a in (q, k, v, do))
-    pat = gpu_lib.SparsePattern(np.ones((5, 5), bool))
+    pat = gpu_lib.SparsePattern(np.ones((4, 4), bool))
     o, lse = gpu_lib.ulysses_sparse_attn_fwd(tq, tk, tv, pat, 0.09)
     o2, lse2 = gpu_lib.ulysses_attn_fwd(tq, tk, tv, 0.09, True)
     assert torch.equal(o, o2) and torch.equal(lse, lse2)          # same tiles in the same order

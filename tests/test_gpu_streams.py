@@ -90,9 +90,10 @@ def test_sparse_graph_capture_and_replay(gpu_lib):
     o = torch.empty_like(t[0]); lse = torch.empty((Hl, N), dtype=torch.float32, device="cuda")
     grads = tuple(torch.empty_like(t[0]) for _ in range(3))
     ws = torch.empty(gpu_lib.ulysses_sparse_attn_bwd_workspace_bytes(N, Hl, d), dtype=torch.uint8, device="cuda")
+    fws = torch.empty(gpu_lib.ulysses_sparse_attn_fwd_workspace_bytes(N, Hl, d), dtype=torch.uint8, device="cuda")
 
     def run():
-        gpu_lib.ulysses_sparse_attn_fwd(t[0], t[1], t[2], pat, scale, out=o, lse=lse)
+        gpu_lib.ulysses_sparse_attn_fwd(t[0], t[1], t[2], pat, scale, out=o, lse=lse, workspace=fws)
         gpu_lib.ulysses_sparse_attn_bwd(t[0], t[1], t[2], o, t[3], lse, pat, scale, workspace=ws, out=grads)
 
     run()
@@ -107,7 +108,8 @@ def test_sparse_graph_capture_and_replay(gpu_lib):
     for rep in range(3):
         for x in (o, lse) + grads:
             x.zero_()
-        ws.fill_(rep + 1)                                # whatever the workspace holds, the replay rebuilds it
+        ws.fill_(rep + 1)                                # whatever the workspaces hold, the replay rebuilds it
+        fws.fill_(rep + 1)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
