@@ -101,6 +101,9 @@ def main() -> int:
     lse = torch.empty((Hl, N), dtype=torch.float32, device="cuda")
     grads = tuple(torch.empty((N, Hl, d), dtype=etype, device="cuda") for _ in range(3))
     ws = torch.empty(max(uly.ulysses_attn_bwd_workspace_bytes(N, Hl, d), 16), dtype=torch.uint8, device="cuda")
+    # forward workspace: empty at the headline shape; short sequences cut long rows into work items with it
+    fws_bytes = uly.ulysses_attn_fwd_workspace_bytes(N, Hl, d, True)
+    fws = torch.empty(max(fws_bytes, 16), dtype=torch.uint8, device="cuda")
 
     lib = uly.load()
     stream = torch.cuda.current_stream()
@@ -128,8 +131,8 @@ def main() -> int:
         mark()
         uly._check(lib.ulysses_unpack_qkv(recv_ptrs, qkv_ptrs, nl, H, d, P, 2, uly.LAYOUT_SEQ_HEAD, sp), "unpack_qkv")
         mark()
-        uly._check(lib.ulysses_attn_fwd(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse), N, Hl, d, scale, 1,
-                                        lay, sp), "attn_fwd")
+        uly._check(lib.ulysses_attn_fwd_ws(ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(lse), ptr(fws), fws_bytes, N,
+                                           Hl, d, scale, 1, lay, sp), "attn_fwd")
         mark()
         for stage in (uly.BWD_STAGE_DELTA, uly.BWD_STAGE_DKV, uly.BWD_STAGE_DQ):
             uly._check(lib.ulysses_attn_bwd_stage(stage, ptr(qkv[0]), ptr(qkv[1]), ptr(qkv[2]), ptr(o), ptr(dout),

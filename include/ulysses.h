@@ -126,6 +126,17 @@ int ulysses_unpack_rev_qkv(const void* const recv[3], void* const y[3], int64_t 
 int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                      int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream);
 
+/* Forward with a workspace (for callers that can give one): same result as ulysses_attn_fwd.  When the
+ * sequence is short enough that one workgroup per 256 queries would leave much of the device idle (fewer
+ * than 1024 such tiles over all heads), the keys of long rows are cut into several work items whose fp32
+ * partial results a second kernel merges in a fixed order.  ulysses_attn_fwd_workspace_bytes is 0 when
+ * nothing would be cut (workspace may then be NULL) and stays below 600 MiB otherwise; ULY_ERR_WORKSPACE
+ * if the workspace is NULL or too small, ULY_ERR_ALIGN if it is not 16-byte aligned. */
+size_t ulysses_attn_fwd_workspace_bytes(int64_t N, int Hl, int d, int causal);
+int ulysses_attn_fwd_ws(const void* q, const void* k, const void* v, void* o, float* lse,
+                        void* workspace, size_t workspace_bytes,
+                        int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream);
+
 /* Bytes of device scratch the backward pass needs (two fp32 per query row and head, rows padded). */
 size_t ulysses_attn_bwd_workspace_bytes(int64_t N, int Hl, int d);
 
@@ -199,11 +210,11 @@ int ulysses_xattn_bwd(const void* q, const void* k, const void* v, const void* o
  * from the pattern on the device: one workgroup per tile would leave the launch waiting for a few long
  * block rows or columns (global tokens, summary blocks), so tiles whose walk is long are cut into
  * several work items whose fp32 partial results a second kernel merges in a fixed order (results are
- * deterministic).  Forward: the plan and the partial results of cut block rows (at most one slot of
+ * deterministic).  Forward: the plan and the partial results of cut block rows (at most four slots of
  * 256 queries x (d + 2) floats per query tile and head, and at most 2048 in all).  Backward: the row
  * statistics of the dense backward, plans, and partial sums of cut block columns (dK/dV: at most 8192
  * slots of 128 keys x d x 2 tensors, 1 GiB at d = 128, never more than two per 128 keys and head) and
- * of cut block rows (dQ: at most 4096 slots of 128 queries x d, never more than one per 128 queries
+ * of cut block rows (dQ: at most 4096 slots of 128 queries x d, never more than four per 128 queries
  * and head).  A pattern that would need more slots gets coarser cuts.
  * Sequences beyond ULY_SPARSE_MAX_N tokens are ULY_ERR_SHAPE (work items are a grid dimension).
  * ------------------------------------------------------------------------------------------- */

@@ -23,7 +23,8 @@ EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack
            "ulysses_sparse_attn_fwd_workspace_bytes", "ulysses_sparse_attn_fwd",
            "ulysses_sparse_attn_bwd_workspace_bytes", "ulysses_sparse_attn_bwd",
            "ulysses_probe_mfma",
-           "ulysses_attn_fwd", "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd", "ulysses_attn_bwd_stage",
+           "ulysses_attn_fwd", "ulysses_attn_fwd_workspace_bytes", "ulysses_attn_fwd_ws",
+           "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd", "ulysses_attn_bwd_stage",
            "ulysses_status_string", "ulysses_abi_version")
 
 _lib = None
@@ -56,6 +57,9 @@ def load(path: str | None = None):
     lib.ulysses_pack_rev_qkv.argtypes = [p3, p3, i64, ci, ci, ci, ci, ci, vp]
     lib.ulysses_unpack_rev_qkv.argtypes = [p3, p3, i64, ci, ci, ci, ci, vp]
     lib.ulysses_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, cf, ci, ci, vp]
+    lib.ulysses_attn_fwd_workspace_bytes.argtypes = [i64, ci, ci, ci]
+    lib.ulysses_attn_fwd_workspace_bytes.restype = sz
+    lib.ulysses_attn_fwd_ws.argtypes = [vp, vp, vp, vp, vp, vp, sz, i64, ci, ci, cf, ci, ci, vp]
     lib.ulysses_attn_bwd_workspace_bytes.argtypes = [i64, ci, ci]
     lib.ulysses_attn_bwd_workspace_bytes.restype = sz
     lib.ulysses_attn_bwd.argtypes = [vp] * 10 + [sz, i64, ci, ci, cf, ci, ci, vp]
@@ -235,13 +239,24 @@ def _elem_flag(*tensors):
     raise ValueError("attention tensors must all be bfloat16 or all be float16")
 
 
-def ulysses_attn_fwd(q, k, v, scale: float, causal: bool = True, layout: int = LAYOUT_SEQ_HEAD, out=None, lse=None):
-    """bf16 (or fp16) q, k, v in ``layout`` -> (o of the same type in ``layout``, lse fp32 [Hl, N])."""
+def ulysses_attn_fwd_workspace_bytes(N: int, Hl: int, d: int, causal: bool = True) -> int:
+    return int(load().ulysses_attn_fwd_workspace_bytes(N, Hl, d, int(causal)))
+
+
+def ulysses_attn_fwd(q, k, v, scale: float, causal: bool = True, layout: int = LAYOUT_SEQ_HEAD, out=None, lse=None,
+                     workspace=None):
+    """bf16 (or fp16) q, k, v in ``layout`` -> (o of the same type in ``layout``, lse fp32 [Hl, N]).  With a
+    ``workspace`` (uint8, ulysses_attn_fwd_workspace_bytes) the call goes through ulysses_attn_fwd_ws."""
     import torch
     elem = _elem_flag(q, k, v)
     N, Hl, d = _attn_dims(q, layout)
     o = torch.empty_like(q) if out is None else out
     lse = torch.empty((Hl, N), dtype=torch.float32, device=q.device) if lse is None else lse
+    if workspace is not None:
+        _check(load().ulysses_attn_fwd_ws(_dev(q, "attn_fwd"), _dev(k, "attn_fwd"), _dev(v, "attn_fwd"), _dev(o, "attn_fwd"),
+                                          _dev(lse, "attn_fwd"), _dev(workspace, "attn_fwd"), workspace.numel(), N, Hl, d,
+                                          scale, int(causal), layout | elem, _stream()), "ulysses_attn_fwd_ws")
+        return o, lse
     _check(load().ulysses_attn_fwd(_dev(q, "attn_fwd"), _dev(k, "attn_fwd"), _dev(v, "attn_fwd"), _dev(o, "attn_fwd"),
                                    _dev(lse, "attn_fwd"), N, Hl, d, scale, int(causal), layout | elem, _stream()),
            "ulysses_attn_fwd")

@@ -175,7 +175,9 @@ static int attn_fwd_checked(const void* q, const void* k, const void* v, void* o
     if (N == 0) return ULY_OK;
     if (Nk == 0) return ULY_ERR_SHAPE;                                             // softmax over no keys
     if (!q || !k || !v || !o || !lse) return ULY_ERR_NULL;
-    const size_t need = takes_workspace ? ulysses_xattn_fwd_workspace_bytes(N, Nk, Hl, d) : 0;
+    const size_t need = !takes_workspace ? 0
+                        : causal         ? ulysses_attn_fwd_workspace_bytes(N, Hl, d, 1)
+                                         : ulysses_xattn_fwd_workspace_bytes(N, Nk, Hl, d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return ULY_ERR_WORKSPACE;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse)) return ULY_ERR_ALIGN;
     if (need > 0 && misaligned(workspace)) return ULY_ERR_ALIGN;
@@ -191,6 +193,19 @@ static int attn_fwd_checked(const void* q, const void* k, const void* v, void* o
 int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t N, int Hl, int d,
                      float scale, int causal, int layout, void* stream) {
     return attn_fwd_checked(q, k, v, o, lse, nullptr, 0, false, N, N, Hl, d, scale, causal, layout, stream);
+}
+
+size_t ulysses_attn_fwd_workspace_bytes(int64_t N, int Hl, int d, int causal) {
+    if (!causal) return ulysses_xattn_fwd_workspace_bytes(N, N, Hl, d);
+    uint64_t tb;
+    if (N <= 0 || check_attn_common(N, Hl, d, ULY_LAYOUT_SEQ_HEAD, &tb) != ULY_OK) return 0;
+    return (size_t)uly::bf16::attn_fwd_causal_workspace_floats(N, Hl, d) * sizeof(float);
+}
+
+int ulysses_attn_fwd_ws(const void* q, const void* k, const void* v, void* o, float* lse, void* workspace,
+                        size_t workspace_bytes, int64_t N, int Hl, int d, float scale, int causal, int layout,
+                        void* stream) {
+    return attn_fwd_checked(q, k, v, o, lse, workspace, workspace_bytes, true, N, N, Hl, d, scale, causal, layout, stream);
 }
 
 size_t ulysses_xattn_fwd_workspace_bytes(int64_t Nq, int64_t Nk, int Hl, int d) {

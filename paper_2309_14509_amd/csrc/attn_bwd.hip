@@ -894,7 +894,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
 // so that no item exceeds a small part of one CU's share; that needs at most
 // sum over cut columns of ceil(cnt / L) <= 2 * total / L <= 2 * kPlanTarget / Hl partial-sum slots per head.
 // The workspace holds that many, but never more than two per key tile; a pattern that would need more
-// gets L doubled until its cut items fit.
+// gets L raised until its cut items fit.
 //   plan[0] = {items, cut items, L, 0};  plan[1 + s] = {key tile, first position, end position, 0};
 //   cut items come first (s = slot of their partial sums);  red[ktile] = {first slot, items} (items 1: not cut).
 // One workgroup; every thread scans a contiguous range of key tiles.
@@ -908,7 +908,7 @@ constexpr int kPlanMinLen = 32;     // query blocks; below this the per-item ove
 
 // Slots for partial sums per head: what the target can ask for, but no more than two per key tile (the
 // partial sums then take at most four times the fp32 size of dK and dV; short sequences gain nothing from
-// finer cuts).  If a pattern would need more, the plan kernel doubles L until it fits.
+// finer cuts).  If a pattern would need more, the plan kernel raises L until it fits.
 inline int plan_slots_per_head(int64_t n_ktiles, int64_t nblk4, int Hl) {
     (void)nblk4;
     const int64_t by_target = 2 * ((kPlanTarget + Hl - 1) / Hl);
@@ -936,8 +936,9 @@ __device__ __forceinline__ int block_scan_exclusive(int v, int* sh, int* total) 
 }
 
 // mode 0: key tiles of dK/dV walk query blocks (ptr = col_ptr);  mode 1: query tiles of dQ walk key blocks
-// (ptr = row_ptr);  mode 2: query tiles of the forward walk 64-key tiles (ptr = row_ptr).  Whole tiles are
-// listed longest first: ascending for columns, descending for rows (later rows see more).
+// (ptr = row_ptr);  mode 2: query tiles of the forward walk 64-key tiles (ptr = row_ptr);  mode 3: the same for
+// dense causal attention (no pattern, ptr unused).  Whole tiles are listed longest first: ascending for
+// columns, descending for rows (later rows see more).
 __global__ __launch_bounds__(kPlanThreads) void sparse_plan_kernel(int mode, const int* __restrict__ ptr, int n_tiles,
                                                                    int N, int Hl, int slots_per_head, int target,
                                                                    int4* __restrict__ plan, int2* __restrict__ red) {
@@ -948,8 +949,9 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_plan_kernel(int mode, con
     const int k0 = tid * chunk < n_tiles ? tid * chunk : n_tiles;
     const int k1 = k0 + chunk < n_tiles ? k0 + chunk : n_tiles;
     auto count = [&](int t) {
-        if (mode == 2) {                                   // forward: 256 queries, 4 tiles of 64 keys per sparse block
+        if (mode >= 2) {                                   // forward: 256 queries, 4 tiles of 64 keys per sparse block
             const int q0 = t * 256, k_end = q0 + 256 < N ? q0 + 256 : N;
+            if (mode == 3) return (k_end + 63) / 64;      // dense causal: every key tile up to the diagonal
             return 4 * (ptr[t + 1] - ptr[t] - 1) + (k_end - q0 + 63) / 64;
         }
         const int b = t / 2, listed = ptr[b + 1] - ptr[b] - 1;   // 128-token tiles: two per sparse block, 8 blocks of 32
@@ -964,7 +966,7 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_plan_kernel(int mode, con
     const unsigned long long want = (sh_total * (unsigned long long)Hl + target - 1) / target;
     int L = want > 0x3FFFFFFFull ? 0x3FFFFFFF : (int)want;
     L = (L + 3) & ~3;
-    const int min_len = mode == 2 ? kPlanMinLen / 2 : kPlanMinLen;      // 1024 tokens either way
+    const int min_len = mode >= 2 ? kPlanMinLen / 2 : kPlanMinLen;      // 1024 tokens either way
     L = L < min_len ? min_len : L;
     // items of a tile that walks cnt units: pieces of len units
     auto piece_len = [&](int cnt) {
@@ -982,7 +984,10 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_plan_kernel(int mode, con
         cut_at = block_scan_exclusive(n_cut, sh, &cut_total);
         whole_at = block_scan_exclusive(n_whole, sh, &whole_total);
         if (cut_total <= slots_per_head) break;
-        L = L < 0x1FFFFFFC ? 2 * L : 0x3FFFFFFC;        // more cut items than slots: coarser cuts (in the end none)
+        // more cut items than slots: coarser cuts, by about the factor that is missing (in the end none)
+        const long long scaled = ((long long)L * cut_total + slots_per_head - 1) / slots_per_head;
+        const long long next = scaled > (long long)L + 4 ? scaled : (long long)L + 4;
+        L = (attempt < 22 && next < 0x3FFFFFF0ll) ? (int)((next + 3) & ~3ll) : 0x3FFFFFFC;
     }
     if (tid == 0) plan[0] = make_int4(cut_total + whole_total, cut_total, L, 0);
     int cs = cut_at, wi = whole_at;
@@ -1088,7 +1093,7 @@ struct SparseWorkspace {
     int slots_per_head, q_slots_per_head;
 };
 inline int row_slots_per_head(int64_t n_tiles, int target, int Hl) {
-    const int64_t by_target = 2 * ((target + Hl - 1) / Hl), by_size = n_tiles + 1;    // at most one slot per tile
+    const int64_t by_target = 2 * ((target + Hl - 1) / Hl), by_size = 4 * n_tiles + 1;    // at most four slots per tile
     return (int)(by_target < by_size ? by_target : by_size);
 }
 inline SparseWorkspace sparse_workspace(int64_t N, int Hl, int d) {

@@ -41,7 +41,8 @@ static_assert(kFwdBQ == kSparseBlock && kSparseBlock % kFwdBK == 0, "a query til
 // the unnormalised fp32 accumulators and, per query, the maximum the exponentials were taken against and
 // the sum of the exponentials.
 //   unmasked attention with few query tiles: item = query tile x piece of `cut_len` tiles (closed form);
-//   block-sparse: items come from a device-made plan (long block rows are cut, see sparse_plan_launch).
+//   block-sparse, and dense causal with few query tiles: items come from a device-made plan (long rows are cut,
+//   see sparse_plan_launch).
 //   part_o [head][slot][256 queries][D] fp32,   part_ml [head][slot][256 queries][2] fp32 (max, sum)
 template <int D, bool CAUSAL, bool SPARSE = false, bool CUT = false>
 __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __restrict__ Q, const e16* __restrict__ K,
@@ -54,7 +55,6 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
                                                                    float* __restrict__ part_ml,
                                                                    const int4* __restrict__ plan, int slots_per_head) {
     static_assert(!SPARSE || CAUSAL, "the sparse pattern refines the causal mask");
-    static_assert(!CUT || SPARSE || !CAUSAL, "dense causal query tiles are not cut into work items");
     constexpr int NT = D / 16;              // contraction steps over the head dim
     constexpr int NCB = D / 32;             // 32-channel blocks of the output
     constexpr int TILE = kFwdBK * D;        // elements per LDS tile
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
     const int head = CUT ? blockIdx.x : blockIdx.x / n_pairs;
     int pr = blockIdx.x - head * n_pairs;
     int t_off = 0, t_len = 0, slot = -1;          // CUT: first key tile (walk position) of this item, their number
-    if (CUT && SPARSE) {
+    if (CUT && CAUSAL) {                          // block-sparse or dense causal: items of uneven length, from a plan
         const int4 hdr = plan[0];                 // {items, items that write partial results, ..}
         if ((int)blockIdx.y >= hdr.x) return;     // the grid is an upper bound on the number of items
         const int4 it = plan[1 + blockIdx.y];     // {query tile, first walk position, end, -}
@@ -486,6 +486,38 @@ inline int64_t fwd_cut_workspace_floats_of(int64_t N, int64_t Nk, int Hl, int d)
     return n_qtiles * c.pieces * Hl * (int64_t)kFwdBQ * (d + 2);
 }
 
+// Workspace of the plan-driven forward (block-sparse; dense causal with few query tiles), in floats: work plan,
+// per-tile table, partial results of the cut rows (at most four slots per query tile and head, and no more than
+// the target asks for).
+constexpr int kFwdRowPlanTarget = 1024;
+struct SparseFwdWorkspace {
+    int64_t plan_at, red_at, part_o_at, part_ml_at, total, items_bound;
+    int slots_per_head;
+};
+inline SparseFwdWorkspace sparse_fwd_workspace(int64_t N, int Hl, int d) {
+    const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ;
+    auto up = [](int64_t x) { return (x + 63) & ~(int64_t)63; };
+    SparseFwdWorkspace w;
+    const int64_t by_target = 2 * ((kFwdRowPlanTarget + Hl - 1) / Hl), by_size = 4 * n_qtiles + 1;
+    w.slots_per_head = (int)(by_target < by_size ? by_target : by_size);
+    w.items_bound = n_qtiles + w.slots_per_head + 1;
+    w.plan_at = 0;
+    w.red_at = up(4 * (1 + w.items_bound));
+    w.part_o_at = up(w.red_at + 2 * n_qtiles);
+    w.part_ml_at = up(w.part_o_at + (int64_t)w.slots_per_head * Hl * kFwdBQ * d);
+    w.total = w.part_ml_at + (int64_t)w.slots_per_head * Hl * kFwdBQ * 2;
+    return w;
+}
+int64_t attn_fwd_sparse_workspace_floats(int64_t N, int Hl, int d) { return sparse_fwd_workspace(N, Hl, d).total; }
+
+// Dense causal attention is planned only when its query tiles alone would leave places idle or unevenly used
+// (two workgroups per CU: 512 places; beyond a thousand tiles, starting the longest first evens them out).
+inline bool causal_fwd_is_planned(int64_t N, int Hl) { return ((N + kFwdBQ - 1) / kFwdBQ) * Hl < 1024; }
+int64_t attn_fwd_causal_workspace_floats(int64_t N, int Hl, int d) {
+    if (d == 256 || !causal_fwd_is_planned(N, Hl)) return 0;
+    return sparse_fwd_workspace(N, Hl, d).total;
+}
+
 template <int D>
 static int launch_fwd(const void* q, const void* k, const void* v, void* o, float* lse, float* ws, int64_t N,
                       int64_t Nk, int Hl, float scale, int causal, TensorStrides st, TensorStrides kv,
@@ -505,6 +537,25 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
             part_o, part_ml, cut.pieces, nullptr, (int)items, (e16*)o, lse, (int)N, st.row, st.head, scale);
         return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
     }
+    if (causal && ws && causal_fwd_is_planned(N, Hl)) {
+        const SparseFwdWorkspace w = sparse_fwd_workspace(N, Hl, D);
+        if (w.items_bound <= 65535 && Hl <= 65535) {
+            int4* plan = reinterpret_cast<int4*>(ws + w.plan_at);
+            int2* red = reinterpret_cast<int2*>(ws + w.red_at);
+            float* part_o = ws + w.part_o_at;
+            float* part_ml = ws + w.part_ml_at;
+            if (sparse_plan_launch(3, nullptr, n_qtiles, N, Hl, w.slots_per_head, kFwdRowPlanTarget, plan, red, stream) != ULY_OK)
+                return ULY_ERR_LAUNCH;
+            attn_fwd_kernel<D, true, false, true>
+                <<<dim3((uint32_t)Hl, (uint32_t)w.items_bound), dim3(kFwdThreads), 0, stream>>>(
+                    (const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
+                    kv.head, scale, nullptr, nullptr, 1, 0, part_o, part_ml, plan, w.slots_per_head);
+            if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
+            attn_fwd_combine_kernel<D><<<dim3((uint32_t)(n_qtiles * (kFwdBQ / 8)), (uint32_t)Hl), dim3(256), 0, stream>>>(
+                part_o, part_ml, 0, red, w.slots_per_head, (e16*)o, lse, (int)N, st.row, st.head, scale);
+            return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
+        }
+    }
     const int64_t blocks = ((causal && kFwdPair) ? (n_qtiles + 1) / 2 : n_qtiles) * Hl;    // causal: pairs of query tiles
     if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
     dim3 grid((uint32_t)blocks), block(kFwdThreads);
@@ -518,29 +569,6 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
                                                               kv.head, scale, nullptr, nullptr, 1, 0, nullptr, nullptr, nullptr, 0);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
-
-// Workspace of the block-sparse forward, in floats: work plan, per-tile table, partial results of the cut
-// block rows (at most one slot per query tile and head, and no more than the target asks for).
-constexpr int kFwdRowPlanTarget = 1024;
-struct SparseFwdWorkspace {
-    int64_t plan_at, red_at, part_o_at, part_ml_at, total, items_bound;
-    int slots_per_head;
-};
-inline SparseFwdWorkspace sparse_fwd_workspace(int64_t N, int Hl, int d) {
-    const int64_t n_qtiles = (N + kFwdBQ - 1) / kFwdBQ;
-    auto up = [](int64_t x) { return (x + 63) & ~(int64_t)63; };
-    SparseFwdWorkspace w;
-    const int64_t by_target = 2 * ((kFwdRowPlanTarget + Hl - 1) / Hl), by_size = n_qtiles + 1;
-    w.slots_per_head = (int)(by_target < by_size ? by_target : by_size);
-    w.items_bound = n_qtiles + w.slots_per_head + 1;
-    w.plan_at = 0;
-    w.red_at = up(4 * (1 + w.items_bound));
-    w.part_o_at = up(w.red_at + 2 * n_qtiles);
-    w.part_ml_at = up(w.part_o_at + (int64_t)w.slots_per_head * Hl * kFwdBQ * d);
-    w.total = w.part_ml_at + (int64_t)w.slots_per_head * Hl * kFwdBQ * 2;
-    return w;
-}
-int64_t attn_fwd_sparse_workspace_floats(int64_t N, int Hl, int d) { return sparse_fwd_workspace(N, Hl, d).total; }
 
 template <int D>
 static int launch_fwd_sparse(const void* q, const void* k, const void* v, void* o, float* lse, float* ws,

@@ -5,9 +5,11 @@
 
 // N queries attend to Nk keys/values (Nk = N for self-attention; causal requires Nk = N).  `st` are the
 // strides of the query-side tensors (q, o, dout, dq), `kv` those of k, v, dk, dv.
-// `ws` (may be null: then nothing is cut): attn_fwd_cut_workspace_floats floats of scratch that let unmasked
-// attention with few query tiles cut the keys of a tile into several work items, merged by a second kernel.
+// `ws` (may be null: then nothing is cut): scratch that lets attention with few query tiles cut the keys of a
+// tile into several work items, merged by a second kernel: attn_fwd_cut_workspace_floats floats without a mask,
+// attn_fwd_causal_workspace_floats with the causal mask.
 int64_t attn_fwd_cut_workspace_floats(int64_t N, int64_t Nk, int Hl, int d);
+int64_t attn_fwd_causal_workspace_floats(int64_t N, int Hl, int d);
 int attn_fwd_launch(const void* q, const void* k, const void* v, void* o, float* lse, float* ws, int64_t N, int64_t Nk,
                     int Hl, int d, float scale, int causal, TensorStrides st, TensorStrides kv, void* stream);
 

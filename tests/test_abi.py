@@ -97,6 +97,20 @@ def test_attention_forward_validation(lib):
     assert _fwd(lib, N=0) == 0                                               # empty: ok, no launch
 
 
+def test_attention_forward_with_workspace_validation(lib):
+    wb = lib.ulysses_attn_fwd_workspace_bytes
+    assert wb(131072, 4, 128, 1) == 0                   # 2048 query tiles: nothing would be cut
+    need = wb(32768, 2, 128, 1)                         # 256 query tiles: long rows are cut
+    assert 0 < need <= 600 << 20 and wb(32768, 2, 256, 1) == 0 and wb(0, 2, 128, 1) == 0 and wb(-4, 2, 128, 1) == 0
+    assert wb(2048, 4, 128, 0) == lib.ulysses_xattn_fwd_workspace_bytes(2048, 2048, 4, 128)
+
+    def call(ws=0xB0000000, wsb=need, N=32768, Hl=2, d=128, causal=1, q=A):
+        return lib.ulysses_attn_fwd_ws(q, B, C_, D_, 0x7000000, ws, wsb, N, Hl, d, 0.1, causal, 0, None)
+    assert call(ws=None) == 6 and call(wsb=need - 1) == 6 and call(ws=0xB0000008) == 4 and call(ws=A) == 5
+    assert call(q=None) == 1 and call(N=-1) == 2 and call(d=80) == 3
+    assert call(N=0, ws=None, wsb=0) == 0               # empty: nothing to do
+
+
 def test_attention_backward_validation(lib):
     ws_need = lib.ulysses_attn_bwd_workspace_bytes(128, 2, 64)
     assert ws_need >= 2 * 128 * 2 * 4
