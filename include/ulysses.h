@@ -126,7 +126,8 @@ int ulysses_unpack_rev_qkv(const void* const recv[3], void* const y[3], int64_t 
 int ulysses_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                      int64_t N, int Hl, int d, float scale, int causal, int layout, void* stream);
 
-/* Forward with a workspace (for callers that can give one): same result as ulysses_attn_fwd.  When the
+/* Forward with a workspace (for callers that can give one): the same quantities as ulysses_attn_fwd
+ * (the same bits when nothing is cut, otherwise equal up to the order of fp32 sums).  When the
  * sequence is short enough that one workgroup per 256 queries would leave much of the device idle (fewer
  * than 1024 such tiles over all heads), the keys of long rows are cut into several work items whose fp32
  * partial results a second kernel merges in a fixed order.  ulysses_attn_fwd_workspace_bytes is 0 when
