@@ -209,6 +209,17 @@ def main() -> int:
     result["mfma_only_tflops"] = probe_tflops
     result["roofline"]["frac_of_mfma_only_loop"] = dkv_tflops / probe_tflops
     result["attn_frac_of_mfma_only_loop"] = result["attn_fwd_bwd_tflops"] / probe_tflops
+    # ... and with one operand of every MFMA read from LDS, which is how the attention kernels feed the matrix pipe
+    uly._check(lib.ulysses_probe_mfma_lds(*probe_args), "probe_mfma_lds")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(3):
+        uly._check(lib.ulysses_probe_mfma_lds(*probe_args), "probe_mfma_lds")
+    e1.record(stream)
+    torch.cuda.synchronize()
+    lds_probe_tflops = 3 * n_cu * 4 * probe_iters * 8 * 2.0 * 32 * 32 * 16 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    result["mfma_lds_fed_tflops"] = lds_probe_tflops
+    result["roofline"]["frac_of_lds_fed_mfma_loop"] = dkv_tflops / lds_probe_tflops
 
     # ---- optional: every layout transform at this workload's shapes --------------------------------
     if args.layouts:

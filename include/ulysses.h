@@ -243,6 +243,11 @@ int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const v
  * ULY_ERR_WORKSPACE if a buffer is too small. */
 int ulysses_probe_mfma(const void* data, size_t data_bytes, float* sink, size_t sink_bytes,
                        int blocks, int iters, void* stream);
+/* The same loop with one operand of every MFMA read from LDS (1 KiB per wave and MFMA, the way the
+ * attention kernels feed their matrix pipe; the other operand stays in registers): the rate a kernel with
+ * that operand traffic can reach at most.  iters is rounded up to an even number. */
+int ulysses_probe_mfma_lds(const void* data, size_t data_bytes, float* sink, size_t sink_bytes,
+                           int blocks, int iters, void* stream);
 
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* ulysses_status_string(int status);

@@ -22,7 +22,7 @@ EXPORTS = ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack
            "ulysses_xattn_bwd",
            "ulysses_sparse_attn_fwd_workspace_bytes", "ulysses_sparse_attn_fwd",
            "ulysses_sparse_attn_bwd_workspace_bytes", "ulysses_sparse_attn_bwd",
-           "ulysses_probe_mfma",
+           "ulysses_probe_mfma", "ulysses_probe_mfma_lds",
            "ulysses_attn_fwd", "ulysses_attn_fwd_workspace_bytes", "ulysses_attn_fwd_ws",
            "ulysses_attn_bwd_workspace_bytes", "ulysses_attn_bwd", "ulysses_attn_bwd_stage",
            "ulysses_status_string", "ulysses_abi_version")
@@ -78,6 +78,8 @@ def load(path: str | None = None):
     lib.ulysses_sparse_attn_bwd.argtypes = [vp] * 14 + [sz, i64, ci, ci, cf, ci, vp]
     lib.ulysses_probe_mfma.argtypes = [vp, sz, vp, sz, ci, ci, vp]
     lib.ulysses_probe_mfma.restype = ci
+    lib.ulysses_probe_mfma_lds.argtypes = [vp, sz, vp, sz, ci, ci, vp]
+    lib.ulysses_probe_mfma_lds.restype = ci
     lib.ulysses_status_string.argtypes = [ci]
     lib.ulysses_status_string.restype = ctypes.c_char_p
     for name in ("ulysses_pack", "ulysses_unpack", "ulysses_pack_rev", "ulysses_unpack_rev",

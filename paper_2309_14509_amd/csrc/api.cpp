@@ -352,13 +352,23 @@ int ulysses_sparse_attn_bwd(const void* q, const void* k, const void* v, const v
         uly::strides_for(layout & ~ULY_ELEM_F16, N, Hl, d), stream);
 }
 
-int ulysses_probe_mfma(const void* data, size_t data_bytes, float* sink, size_t sink_bytes, int blocks, int iters,
-                       void* stream) {
-    if (blocks <= 0 || iters <= 0 || blocks > 65536) return ULY_ERR_SHAPE;
+static int probe_checked(const void* data, size_t data_bytes, float* sink, size_t sink_bytes, int blocks, int iters,
+                         int lds_fed, void* stream) {
+    if (blocks <= 0 || iters <= 0 || blocks > 65536 || iters > (1 << 30)) return ULY_ERR_SHAPE;
     if (!data || !sink) return ULY_ERR_NULL;
     if (misaligned(data) || misaligned(sink)) return ULY_ERR_ALIGN;
     if (data_bytes < uly::kProbeBytes || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return ULY_ERR_WORKSPACE;
-    return uly::mfma_probe_launch(data, sink, blocks, iters, stream);
+    return uly::mfma_probe_launch(data, sink, blocks, iters, lds_fed, stream);
+}
+
+int ulysses_probe_mfma(const void* data, size_t data_bytes, float* sink, size_t sink_bytes, int blocks, int iters,
+                       void* stream) {
+    return probe_checked(data, data_bytes, sink, sink_bytes, blocks, iters, 0, stream);
+}
+
+int ulysses_probe_mfma_lds(const void* data, size_t data_bytes, float* sink, size_t sink_bytes, int blocks, int iters,
+                           void* stream) {
+    return probe_checked(data, data_bytes, sink, sink_bytes, blocks, iters, 1, stream);
 }
 
 const char* ulysses_status_string(int status) {

@@ -648,9 +648,70 @@ __global__ __launch_bounds__(256, 1) void mfma_probe_kernel(const e16* __restric
     if (tot == 12345.678f) sink[blockIdx.x * 256 + threadIdx.x] = tot + pad[0];   // keeps the loop alive; practically never true
 }
 
-// data: at least kProbeBytes of device memory filled by the caller; sink: at least blocks*256 floats
-int mfma_probe_launch(const void* data, float* sink, int blocks, int iters, void* stream) {
-    mfma_probe_kernel<<<dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream>>>((const e16*)data, sink, iters);
+// The same with one operand of every MFMA read from LDS (1 KiB per wave and MFMA, the operand traffic of the
+// attention kernels, whose other operand sits in registers): 64 KiB of `data` are staged in LDS, the reads of
+// the next eight MFMAs are issued before the current eight run.  What this sustains bounds any kernel that feeds
+// its matrix pipe this way.
+__global__ __launch_bounds__(256, 1) void mfma_lds_probe_kernel(const e16* __restrict__ data, float* __restrict__ sink,
+                                                                int iters) {
+    __shared__ __attribute__((aligned(1024))) e16 tile[8 * 32 * 128];      // eight 32 x 128 tiles: 64 KiB
+    __shared__ float pad[8 * 1024];                                        // keeps it at one workgroup per CU
+    if (iters < 0) pad[threadIdx.x] = 0.f;
+    const int lane = threadIdx.x & 63, g = lane >> 5, ln = lane & 31;
+    const e16x8* src = reinterpret_cast<const e16x8*>(data);
+    for (int i = threadIdx.x; i < 8 * 32 * 128 / 8; i += 256) reinterpret_cast<e16x8*>(tile)[i] = src[i];
+    e16x8 b[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) b[t] = src[threadIdx.x + 512 * t + 256];
+    __syncthreads();
+    const uint32_t base = lds_addr(tile);
+    uint32_t adr[8];                                 // row ln, chunk 2t+g of a swizzled tile: conflict-free row reads
+#pragma unroll
+    for (int t = 0; t < 8; ++t) adr[t] = base + 2 * tile_off<128>(ln, 2 * t + g);
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    e16x8 a0[8], a1[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) a0[t] = lds_b128<0>(adr[t]);
+#pragma unroll 1
+    for (int it = 0; it < iters; it += 2) {
+        const uint32_t off1 = (uint32_t)((it + 1) & 7) * 8192u, off0 = (uint32_t)((it + 2) & 7) * 8192u;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) a1[t] = lds_b128<0>(adr[t] + off1);
+        wait_lgkm<8>();
+        lds_tie(a0[0], a0[1], a0[2], a0[3], a0[4], a0[5], a0[6], a0[7]);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t & 3] = mfma32(a0[t], b[t], acc[t & 3]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) a0[t] = lds_b128<0>(adr[t] + off0);
+        wait_lgkm<8>();
+        lds_tie(a1[0], a1[1], a1[2], a1[3], a1[4], a1[5], a1[6], a1[7]);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t & 3] = mfma32(a1[t], b[t], acc[t & 3]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_lgkm<0>();
+    lds_tie(a0[0], a0[1], a0[2], a0[3], a0[4], a0[5], a0[6], a0[7]);
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tot += acc[i][r];
+    if (tot == 12345.678f) sink[blockIdx.x * 256 + threadIdx.x] = tot + pad[0] + (float)a0[0][0];
+}
+
+// data: at least kProbeBytes of device memory filled by the caller; sink: at least blocks*256 floats;
+// lds_fed: one operand of every MFMA comes from LDS (iters is rounded up to an even number)
+int mfma_probe_launch(const void* data, float* sink, int blocks, int iters, int lds_fed, void* stream) {
+    if (lds_fed)
+        mfma_lds_probe_kernel<<<dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream>>>((const e16*)data, sink,
+                                                                                             (iters + 1) & ~1);
+    else
+        mfma_probe_kernel<<<dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream>>>((const e16*)data, sink, iters);
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 #endif

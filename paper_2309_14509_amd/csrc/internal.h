@@ -29,9 +29,10 @@ inline TensorStrides strides_for(int layout, int64_t N, int Hl, int d) {
     return s;
 }
 
-// MFMA-only probe (measurement aid): `blocks` workgroups of 256 lanes, `iters` x 8 MFMAs per wave.
+// MFMA-only probe (measurement aid): `blocks` workgroups of 256 lanes, `iters` x 8 MFMAs per wave; lds_fed: one
+// operand of every MFMA is read from LDS instead of sitting in registers.
 constexpr size_t kProbeBytes = 64 * 1024;        // operand bytes read from `data`
-int mfma_probe_launch(const void* data, float* sink, int blocks, int iters, void* stream);
+int mfma_probe_launch(const void* data, float* sink, int blocks, int iters, int lds_fed, void* stream);
 
 // The attention kernels exist once per element type of Q, K, V, O and the gradients (accumulation
 // and the softmax are fp32 either way).

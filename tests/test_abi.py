@@ -234,6 +234,9 @@ def test_sparse_attention_validation(lib):
 
 def test_probe_validation(lib):
     ok = dict(data=A, db=65536, sink=B, sb=256 * 256 * 4, blocks=256, iters=10)
+    for entry in (lib.ulysses_probe_mfma, lib.ulysses_probe_mfma_lds):
+        f = lambda **kw: entry(*[{**ok, **kw}[n] for n in ("data", "db", "sink", "sb", "blocks", "iters")], None)
+        assert f(data=None) == 1 and f(sink=None) == 1 and f(blocks=0) == 2 and f(db=1000) == 6
     f = lambda **kw: lib.ulysses_probe_mfma(*[{**ok, **kw}[n] for n in ("data", "db", "sink", "sb", "blocks", "iters")], None)
     assert f(data=None) == 1 and f(sink=None) == 1
     assert f(blocks=0) == 2 and f(iters=0) == 2 and f(blocks=1 << 20) == 2
