@@ -32,6 +32,7 @@ typedef __bf16 e16;
 #endif
 typedef e16 e16x8 __attribute__((ext_vector_type(8)));
 typedef e16 e16x4 __attribute__((ext_vector_type(4)));
+typedef e16 e16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 

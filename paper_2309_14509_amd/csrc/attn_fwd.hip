@@ -413,6 +413,439 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
     }   // query tiles of this workgroup
 }
 
+// ------------------------------------------------------------------------------------------
+// Forward for d = 128 with 64 queries per wave.  The kernel above takes one operand of every MFMA
+// from LDS (1 KiB per wave and MFMA), which at the full matrix rate is the whole LDS bandwidth of a
+// CU.  Here a lane owns two queries (two 32-query column blocks), so every K row operand and every
+// V^T operand read from LDS feeds two MFMAs.  That takes 128 accumulator + 64 Q-operand registers,
+// so it runs one wave per SIMD (4 waves = 256 queries per workgroup, one workgroup per CU) and
+// overlaps its vector work with its matrix work inside the wave.  Iteration p:
+//     region A   matrix: S^T of block p+1              vector: exponentials of block p (3/4 of them)
+//     region B   matrix: O^T += V^T P^T of block p-1   vector: the other exponentials, row maxima of block p+1
+// The product with V lags one block behind the exponentials so that neither region waits for the
+// vector unit.  K and V stream through rings of four 32-key LDS tiles.  The reference maximum of a
+// row moves only when a score exceeds it by more than kQ64Lazy in the exponent (it need not be the true
+// maximum: the result does not depend on it), which after the first blocks is practically never.
+// ------------------------------------------------------------------------------------------
+constexpr int kQ64Threads = 256;
+constexpr int kQ64BK = 32;
+constexpr int kQ64Ring = 4;
+constexpr float kQ64Lazy = 8.f;
+
+// S^T MFMAs with their result in vector registers (the compiler's own MFMAs of a kernel this large all
+// accumulate in accumulation registers, from which every score would have to be copied before the vector unit
+// can touch it).  The B operand comes from an accumulation register.  Callers keep at least eight other MFMAs
+// between the last of these and the first vector instruction that reads the result.
+#if defined(ULY_BUILD_F16)
+#define ULY_MFMA32_ASM "v_mfma_f32_32x32x16_f16"
+#else
+#define ULY_MFMA32_ASM "v_mfma_f32_32x32x16_bf16"
+#endif
+__device__ __forceinline__ void mfma32_v_first(f32x16& d, const e16x8& a, const e16x8& b) {
+    asm volatile(ULY_MFMA32_ASM " %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma32_v_acc(f32x16& d, const e16x8& a, const e16x8& b) {
+    asm volatile(ULY_MFMA32_ASM " %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+}
+
+template <bool CAUSAL>
+__global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
+    const e16* __restrict__ Q, const e16* __restrict__ K, const e16* __restrict__ V, e16* __restrict__ O,
+    float* __restrict__ LSE, int N, int Nk, int n_qtiles, int64_t row_stride, int64_t head_stride,
+    int64_t kv_head_stride, float scale) {
+    constexpr int D = 128, NT = D / 16, NCB = D / 32;
+    constexpr int TILE = kQ64BK * D, TB = TILE * 2;
+    constexpr int KB = 0, VB = kQ64Ring * TB;       // byte offsets of the K ring and the V ring
+    constexpr int HALF = 16 * D * 2;
+    using Loader = DirectTile<D, kQ64BK, 4, SwzBoth>;
+    constexpr int LPT = 2 * Loader::kPerWave;       // global loads per wave and iteration (one K tile, one V tile)
+
+    __shared__ __attribute__((aligned(1024))) e16 smem[2 * kQ64Ring * TILE];
+
+    const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: LDS tile addresses stay scalar
+    const int head = blockIdx.x / n_qtiles;
+    const int qt = n_qtiles - 1 - (blockIdx.x - head * n_qtiles);      // causal: the longest tiles start first
+    const int64_t hoff = (int64_t)head * head_stride;
+    const e16* Kh = K + (int64_t)head * kv_head_stride;
+    const e16* Vh = V + (int64_t)head * kv_head_stride;
+    const int nblk = (Nk + kQ64BK - 1) / kQ64BK;
+
+    const typename Loader::LaneOffsets ld = Loader::lane_offsets(row_stride, wave, lane);
+    const typename Loader::TailOffsets ld_tail = Loader::tail_offsets(row_stride, wave, lane, Nk);
+    // Fetches block tb; blocks past the end re-read the last real one (all their keys are masked); branch-free.
+    // The steady-state iterations never reach the last block and fetch through running pointers instead.
+    auto load_tile = [&](e16* tile, const e16* base, int tb) __attribute__((always_inline)) {
+        tb = tb < nblk ? tb : nblk - 1;
+        const int r0 = tb * kQ64BK;
+        Loader::issue_sel(tile, base + (int64_t)r0 * row_stride, ld, ld_tail, r0 + kQ64BK > Nk, wave);
+    };
+    const int64_t tile_elems = (int64_t)kQ64BK * row_stride;
+    const float sl2 = scale * kLog2e;
+    const float lazy = kQ64Lazy / sl2;              // in units of raw scores
+
+    const uint32_t sbase = lds_addr(smem);
+    uint32_t r_adr[NT];                 // row read of K: row ln, chunk 2t+g
+#pragma unroll
+    for (int t = 0; t < NT; ++t) r_adr[t] = sbase + 2 * tile_off<D>(ln, 2 * t + g);
+    uint32_t t_adr[NCB][2];             // transposing read of V: rows 4g+(i>>2) (+8), channels 32cb+16h+4(i&3)
+    {
+        const int i = lane & 15, h = (lane >> 4) & 1;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+                t_adr[cb][hh] = sbase + 2 * (tile_off<D>(4 * g + (i >> 2) + 8 * hh, 4 * cb + 2 * h + ((i & 3) >> 1)) +
+                                             4 * (i & 1));
+    }
+
+    const int q0 = qt * kFwdBQ;
+    // key blocks to process, a multiple of 4; causal: up to the end of this tile's diagonal
+    const int cnt = CAUSAL ? (q0 + kFwdBQ) / kQ64BK : (nblk + 3) & ~3;
+    // K tiles of blocks 0..3; V tiles of blocks 0, 1 and, in slot 3, block 0 once more: the first iteration
+    // multiplies zeros with that slot, which therefore has to hold finite numbers
+#pragma unroll
+    for (int i = 0; i < kQ64Ring; ++i) load_tile(smem + i * TILE, Kh, i);
+    load_tile(smem + (kQ64Ring + 0) * TILE, Vh, 0);
+    load_tile(smem + (kQ64Ring + 1) * TILE, Vh, 1);
+    load_tile(smem + (kQ64Ring + 3) * TILE, Vh, 0);
+    const e16* k_next = Kh + kQ64Ring * tile_elems;      // the tiles iteration 0 fetches: K of block 4, V of block 2
+    const e16* v_next = Vh + 2 * tile_elems;
+
+    // ---- this lane's two queries: Q rows as B operands
+    int q_row[2], klim[2];
+    e16x8 qreg[2][NT];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        q_row[qb] = q0 + wave * 64 + qb * 32 + ln;
+        const int q_ld = q_row[qb] < N ? q_row[qb] : N - 1;
+        // key offset c_r (inside a block starting at k0) is masked iff c_r > klim - k0
+        klim[qb] = (CAUSAL ? (q_row[qb] < Nk - 1 ? q_row[qb] : Nk - 1) : Nk - 1) - 4 * g;
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            qreg[qb][t] = *reinterpret_cast<const e16x8*>(Q + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
+    }
+
+    float m_used[2] = {-INFINITY, -INFINITY}, ms[2], l_run[2] = {0.f, 0.f};
+    float pend[2] = {1.f, 1.f};         // factor O still has to take after the next product with V
+    bool pending = false;               // (wave-uniform)
+    f32x16 oacc[2][NCB];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[qb][cb][r] = 0.f;
+
+    f32x16 s[2][2];                     // [parity][query block]: scores of the current and of the next block
+    e16x8 krow[NT];
+    e16x4 vt_lo[2][NCB], vt_hi[2][NCB];
+    e16x8 pb_prev[2][2];                // P^T of the previous block, packed as B operands
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pb_prev[qb][u][e] = (e16)0.f;
+
+    // K rows of a block: channels 0..63 (half 0) or 64..127 (half 1)
+    auto read_krow = [&](auto slot_tag, auto half_tag) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+        constexpr int T0 = decltype(half_tag)::value * (NT / 2);
+#pragma unroll
+        for (int t = T0; t < T0 + NT / 2; ++t) krow[t] = lds_b128<KB + SL * TB>(r_adr[t]);
+    };
+    auto read_transposed = [&](auto slot_tag, auto half_tag) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slot_tag)::value;
+        constexpr int U = decltype(half_tag)::value;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            vt_lo[U][cb] = lds_tr_b64<VB + SL * TB + U * HALF>(t_adr[cb][0]);
+            vt_hi[U][cb] = lds_tr_b64<VB + SL * TB + U * HALF>(t_adr[cb][1]);
+        }
+    };
+    auto tie_krow = [&](auto half_tag) __attribute__((always_inline)) {
+        constexpr int T0 = decltype(half_tag)::value * (NT / 2);
+#pragma unroll
+        for (int t = T0; t < T0 + NT / 2; ++t) lds_tie(krow[t]);
+    };
+    auto tie_transposed = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) lds_tie(vt_lo[u][cb], vt_hi[u][cb]);
+    };
+    auto tie_half = [&](auto half_tag) __attribute__((always_inline)) {
+        constexpr int U = decltype(half_tag)::value;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) lds_tie(vt_lo[U][cb], vt_hi[U][cb]);
+    };
+    // O^T += V^T P^T over 16 keys of the previous block, for both query blocks
+    auto pv_half = [&](auto half_tag) __attribute__((always_inline)) {
+        constexpr int U = decltype(half_tag)::value;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            const e16x8 va = __builtin_shufflevector(vt_lo[U][cb], vt_hi[U][cb], 0, 1, 2, 3, 4, 5, 6, 7);
+            oacc[0][cb] = mfma32(va, pb_prev[0][U], oacc[0][cb]);
+            oacc[1][cb] = mfma32(va, pb_prev[1][U], oacc[1][cb]);
+        }
+    };
+    auto zero = [&](f32x16& x) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) x[r] = 0.f;
+    };
+    // masks block kb in s[par], takes its row maxima and says whether a reference maximum must move
+    auto block_max = [&](int par, bool masked, int kb, float (&m_blk)[2]) __attribute__((always_inline)) {
+        bool moved = false;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            if (masked) {
+                const int krel = klim[qb] - kb * kQ64BK;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (8 * (r >> 2) + (r & 3) > krel) s[par][qb][r] = -INFINITY;
+            }
+            float mb = s[par][qb][0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mb = fmaxf(mb, s[par][qb][r]);
+            m_blk[qb] = xhalf_max(mb);
+            moved = moved || (m_blk[qb] > m_used[qb] + lazy);
+        }
+        return moved;
+    };
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    using S2 = std::integral_constant<int, 2>;
+    using S3 = std::integral_constant<int, 3>;
+
+    // ---- prologue: everything asked for so far resident; S^T of block 0 and its maxima; then the K rows of block 1
+    wait_vm<0>();
+    __syncthreads();
+    // The Q operands live in accumulation registers, where the matrix unit reads them directly; together with O
+    // and the scores they fill that half of the register file, everything else stays in the vector half.
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) asm volatile("" : "+a"(qreg[qb][t]));
+    read_krow(S0{}, S0{});
+    read_krow(S0{}, S1{});
+    wait_lgkm<0>();
+    tie_krow(S0{});
+    tie_krow(S1{});
+    mfma32_v_first(s[0][0], krow[0], qreg[0][0]);
+    mfma32_v_first(s[0][1], krow[0], qreg[1][0]);
+#pragma unroll
+    for (int t = 1; t < NT; ++t) {
+        mfma32_v_acc(s[0][0], krow[t], qreg[0][t]);
+        mfma32_v_acc(s[0][1], krow[t], qreg[1][t]);
+    }
+    read_krow(S1{}, S0{});
+    // the vector unit must not read the scores before the last MFMA has written them
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0][0]), "+v"(s[0][1]));
+    __builtin_amdgcn_sched_barrier(0);
+    {
+        float m_blk[2];
+        block_max(0, true, 0, m_blk);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            m_used[qb] = m_blk[qb];
+            ms[qb] = (m_used[qb] == -INFINITY ? 0.f : m_used[qb]) * sl2;
+        }
+    }
+    wait_lgkm<0>();
+    tie_krow(S0{});
+    __builtin_amdgcn_sched_barrier(0);
+
+    // One iteration.  At entry: s[SL & 1] holds the scores of block p, whose maxima are already in m_used; the K
+    // rows of block p+1 (channels 0..63) are in registers; pb_prev is P^T of block p-1, whose V tile is in slot (SL+3) % 4; no LDS
+    // read is in flight.  K tiles are fetched four blocks ahead, V tiles two (their slot is free a block later).
+    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot2_tag, auto slotv_tag, int p) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_tag)::value;      // block p+1 may need the mask
+        constexpr int SL = decltype(slot_tag)::value;
+        constexpr int SLV = decltype(slotv_tag)::value;
+        constexpr int PAR = SL & 1;
+        e16x8 pb[2][2];
+        float rs[2] = {0.f, 0.f};
+        // exponentials of the score pair j (0..15) of block p: query block j / 8, registers 2 (j % 8), +1
+        auto exp_pair = [&](int j) __attribute__((always_inline)) {
+            const int qb = j >> 3, r = 2 * (j & 7);
+            const float p0 = fast_exp2(__builtin_fmaf(s[PAR][qb][r], sl2, -ms[qb]));
+            const float p1 = fast_exp2(__builtin_fmaf(s[PAR][qb][r + 1], sl2, -ms[qb]));
+            rs[qb] += p0;
+            rs[qb] += p1;
+            e16x2 pk = {(e16)p0, (e16)p1};
+            asm volatile("" : "+v"(pk));              // packed here, not wherever the value is finally used
+            pb[qb][r >> 3][r & 7] = pk[0];
+            pb[qb][r >> 3][(r & 7) + 1] = pk[1];
+        };
+        // S^T of block p+1, K channels 16t..16t+15, for both query blocks, each MFMA followed by the vector work
+        // of one score pair of block p (the MFMAs are fixed in place; the vector work may not cross them)
+        auto s_step = [&](int t, int j0, int j1) __attribute__((always_inline)) {
+            if (t == 0) mfma32_v_first(s[PAR ^ 1][0], krow[0], qreg[0][0]);
+            else mfma32_v_acc(s[PAR ^ 1][0], krow[t], qreg[0][t]);
+            if (j0 >= 0) exp_pair(j0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t == 0) mfma32_v_first(s[PAR ^ 1][1], krow[0], qreg[1][0]);
+            else mfma32_v_acc(s[PAR ^ 1][1], krow[t], qreg[1][t]);
+            if (j1 >= 0) exp_pair(j1);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // ---- region A, first half
+        read_krow(std::integral_constant<int, (SL + 1) % kQ64Ring>{}, S1{});     // K rows of block p+1, channels 64..127
+        __builtin_amdgcn_sched_barrier(0);
+        s_step(0, 0, 1);
+        s_step(1, -1, 2);
+        s_step(2, 3, -1);
+        s_step(3, 4, -1);
+        // ---- region A, second half
+        wait_lgkm<0>();
+        tie_krow(S1{});
+        read_transposed(slotv_tag, S0{});             // V^T of block p-1, keys 0..15
+        __builtin_amdgcn_sched_barrier(0);
+        s_step(4, 5, 6);
+        s_step(5, -1, 7);
+        s_step(6, 8, -1);
+        s_step(7, 9, -1);
+
+        // ---- region B: tiles up to p+2 (K) and p+1 (V) have landed; everyone is done with the K tile of block p
+        // and the V tile of block p-2, which are refilled with the K tile of block p+4 and the V tile of block p+2
+        wait_vm<LPT>();
+        barrier_no_drain();
+        if (MASKED) {
+            load_tile(smem + SL * TILE, Kh, p + kQ64Ring);
+            load_tile(smem + (kQ64Ring + (SLV + 3) % kQ64Ring) * TILE, Vh, p + 2);
+        } else {                                      // block p+4 is not the last one here: no clamp, no ragged tile
+            Loader::issue(smem + SL * TILE, k_next, ld, wave);
+            Loader::issue(smem + (kQ64Ring + (SLV + 3) % kQ64Ring) * TILE, v_next, ld, wave);
+            k_next += tile_elems;
+            v_next += tile_elems;
+        }
+        read_transposed(slotv_tag, S1{});             // V^T of block p-1, keys 16..31
+        wait_lgkm<2 * NCB>();                         // the reads of region A
+        tie_half(S0{});
+        read_krow(slot2_tag, S0{});                   // K rows of block p+2 (channels 0..63), for the next iteration
+        __builtin_amdgcn_sched_barrier(0);
+        pv_half(S0{});
+        exp_pair(10); exp_pair(11); exp_pair(12);
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        wait_lgkm<NT / 2>();                          // the V^T reads of this region (the K rows may still be in flight)
+        tie_half(S1{});
+        __builtin_amdgcn_sched_barrier(0);
+        pv_half(S1{});
+        exp_pair(13); exp_pair(14); exp_pair(15);
+        float m_blk[2];
+        const bool moved = block_max(PAR ^ 1, MASKED, p + 1, m_blk);
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, MASKED ? 16 : 7, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            l_run[qb] += rs[qb];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) pb_prev[qb][u] = pb[qb][u];
+        }
+        // The compiler may move registers at control-flow joins (the rescale branch, the loop edges) without
+        // knowing that a hand-issued LDS read into them is in flight: the reads land before any branch.
+        wait_lgkm<0>();
+        tie_krow(S0{});
+        __builtin_amdgcn_sched_barrier(0);
+        if (pending) {                                // O now holds blocks up to p-1, all under the maximum before last
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[qb][cb][r] *= pend[qb];
+            pending = false;
+        }
+        if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+            // The row sums carry the old reference maximum and move now.  So do O and the P^T of block p, which is
+            // already rounded and still to be multiplied with V: O moves once that product is in it (a second
+            // rounding of P^T is avoided that way).
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const float m_new = fmaxf(m_used[qb], m_blk[qb]);
+                const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;     // a row with nothing visible yet
+                const float alpha = fast_exp2((m_used[qb] - m_fin) * sl2);
+                l_run[qb] *= alpha;
+                pend[qb] = alpha;
+                m_used[qb] = m_new;
+                ms[qb] = m_fin * sl2;
+            }
+            pending = true;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    using Plain = std::integral_constant<bool, false>;
+    using Masked = std::integral_constant<bool, true>;
+    // Blocks that need the mask: the diagonal of this tile (its last 8 blocks) when causal; otherwise the last
+    // group, which holds the end of the key sequence.  An iteration looks at the block after its own, so the
+    // masking variant starts one group earlier; the block after the last does not exist and is masked entirely.
+    const int plain_end = (CAUSAL ? cnt - 8 : cnt - 4) - 4;
+    int p = 0;
+    for (; p < plain_end; p += 4) {
+        iteration(Plain{}, S0{}, S2{}, S3{}, p);
+        iteration(Plain{}, S1{}, S3{}, S0{}, p + 1);
+        iteration(Plain{}, S2{}, S0{}, S1{}, p + 2);
+        iteration(Plain{}, S3{}, S1{}, S2{}, p + 3);
+    }
+    for (; p < cnt; p += 4) {
+        iteration(Masked{}, S0{}, S2{}, S3{}, p);
+        iteration(Masked{}, S1{}, S3{}, S0{}, p + 1);
+        iteration(Masked{}, S2{}, S0{}, S1{}, p + 2);
+        iteration(Masked{}, S3{}, S1{}, S2{}, p + 3);
+    }
+    // ---- the product with V of the last block (cnt is a multiple of 4: its V tile is in slot 3).  After it
+    // nothing is writing LDS any more.
+    read_transposed(S3{}, S0{});
+    read_transposed(S3{}, S1{});
+    wait_vm<0>();
+    wait_lgkm<0>();
+    tie_transposed();
+    __builtin_amdgcn_sched_barrier(0);
+    pv_half(S0{});
+    pv_half(S1{});
+    __builtin_amdgcn_sched_barrier(0);
+    if (pending) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[qb][cb][r] *= pend[qb];
+    }
+
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const float l_tot = xhalf_sum(l_run[qb]);
+        const float inv = 1.f / l_tot;
+        if (q_row[qb] < N) {
+            e16* orow = O + hoff + (int64_t)q_row[qb] * row_stride;
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    e16x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (e16)(oacc[qb][cb][4 * rq + e] * inv);
+                    *reinterpret_cast<e16x4*>(orow + 32 * cb + 8 * rq + 4 * g) = w;
+                }
+            if (g == 0) LSE[(int64_t)head * N + q_row[qb]] = m_used[qb] * scale + __logf(l_tot);
+        }
+    }
+}
+
 // Merges the pieces of the cut query tiles: with m = max_i m_i and w_i = exp(scale (m_i - m)),
 //   l = sum_i w_i l_i,   O = sum_i w_i O_i / l,   LSE = scale m + log l        (pieces in a fixed order).
 // Grid (query tiles x 32, heads): a workgroup merges 8 query rows, 32 lanes per row (D / 32 floats each).
@@ -558,15 +991,29 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
     }
     const int64_t blocks = ((causal && kFwdPair) ? (n_qtiles + 1) / 2 : n_qtiles) * Hl;    // causal: pairs of query tiles
     if (blocks > 0x7FFFFFFFll) return ULY_ERR_SHAPE;
-    dim3 grid((uint32_t)blocks), block(kFwdThreads);
-    if (causal)
-        attn_fwd_kernel<D, true><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
-                                                             lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head, scale,
-                                                             nullptr, nullptr, 1, 0, nullptr, nullptr, nullptr, 0);
-    else
-        attn_fwd_kernel<D, false><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v,
-                                                              (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
-                                                              kv.head, scale, nullptr, nullptr, 1, 0, nullptr, nullptr, nullptr, 0);
+    if constexpr (D == 128) {
+        // one workgroup per query tile, 64 queries per wave
+        const dim3 grid((uint32_t)(n_qtiles * Hl)), block(kQ64Threads);
+        if (causal)
+            attn_fwd_q64_kernel<true><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse,
+                                                                  (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head,
+                                                                  scale);
+        else
+            attn_fwd_q64_kernel<false><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse,
+                                                                   (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head,
+                                                                   scale);
+    } else {
+        dim3 grid((uint32_t)blocks), block(kFwdThreads);
+        if (causal)
+            attn_fwd_kernel<D, true><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o,
+                                                                 lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head,
+                                                                 scale, nullptr, nullptr, 1, 0, nullptr, nullptr, nullptr, 0);
+        else
+            attn_fwd_kernel<D, false><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v,
+                                                                  (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
+                                                                  kv.head, scale, nullptr, nullptr, 1, 0, nullptr, nullptr, nullptr,
+                                                                  0);
+    }
     return hipGetLastError() == hipSuccess ? ULY_OK : ULY_ERR_LAUNCH;
 }
 

@@ -53,13 +53,17 @@ def sample_rows(N: int, n_rows: int, P: int, seed: int) -> np.ndarray:
 def o_tolerance(ref: np.ndarray, absv: np.ndarray, base: float = 1e-2) -> np.ndarray:
     """Per-element bound on |O_gpu - O_oracle|: the stated max-abs 1e-2, except where the arithmetic
     the path is specified to use cannot meet it.  The kernel rounds P to bf16 before the PV matrix
-    product (relative error <= 2^-9 per probability) and rounds O to bf16 (half an output ulp), so
-        |O_gpu - O| <= 2^-9 * A + ulp_bf16(|O| + 2^-9 * A) / 2,      A_ic = sum_j P_ij |V_jc|,
+    product and rounds O to bf16.  bf16 keeps 8 significant bits, so rounding to nearest moves a value
+    in [2^e, 2^(e+1)) by at most half an ulp = 2^(e-8), a relative error of at most 2^-8 (reached just
+    above a power of two).  Hence
+        |O_gpu - O| <= 2^-8 * A + ulp_bf16(|O| + 2^-8 * A) / 2,      A_ic = sum_j P_ij |V_jc|,
     plus fp32 accumulation effects (1e-4 allowed).  `absv` is A, which the oracle computes as the
-    attention output for |V|.  Wherever this bound is below 1e-2 (|O| < 2 for ordinary rows) the
-    stated 1e-2 applies unchanged."""
+    attention output for |V|.  Wherever this bound is below 1e-2 (|O| < 1.5 or so for ordinary rows)
+    the stated 1e-2 applies unchanged.  (A kernel whose softmax is taken relative to the exact row
+    maximum represents the largest probability of a row, 1, exactly and stays well inside this bound
+    on near-one-hot rows; one that uses any other reference point does not, and need not.)"""
     a = np.abs(np.asarray(ref, np.float64))
-    p_err = np.asarray(absv, np.float64) * 2.0 ** -9
+    p_err = np.asarray(absv, np.float64) * 2.0 ** -8
     ulp = np.exp2(np.floor(np.log2(np.maximum(a + p_err, 1e-30))) - 7)
     return np.maximum(base, p_err + 0.5 * ulp + 1e-4)
 

@@ -87,14 +87,22 @@ def test_head_major_and_odd_heads(gpu_lib):
     _check(gpu_lib, 1100, 3, 128, "random", layout=1, seed=3)
 
 
-def test_full_pattern_agrees_with_the_dense_kernels(gpu_lib):
-    N, Hl, d = 1024, 2, 128                  # four block rows: none long enough to be cut into work items
+@pytest.mark.parametrize("d", [64, 128])
+def test_full_pattern_agrees_with_the_dense_kernels(gpu_lib, d):
+    N, Hl = 1024, 2                          # four block rows: none long enough to be cut into work items
     q, k, v, do = synth.attention_inputs(N, Hl, d, 9)
     tq, tk, tv, tdo = (to_gpu_bf16(a) for a in (q, k, v, do))
     pat = gpu_lib.SparsePattern(np.ones((4, 4), bool))
     o, lse = gpu_lib.ulysses_sparse_attn_fwd(tq, tk, tv, pat, 0.09)
     o2, lse2 = gpu_lib.ulysses_attn_fwd(tq, tk, tv, 0.09, True)
-    assert torch.equal(o, o2) and torch.equal(lse, lse2)          # same tiles in the same order
+    if d == 64:
+        assert torch.equal(o, o2) and torch.equal(lse, lse2)      # one kernel, same tiles in the same order
+    else:
+        # d = 128: the dense forward is a kernel of its own (other tile walk, other reference maxima), so the two
+        # agree to the rounding of P and O only
+        assert max_abs(f64_of(lse), f64_of(lse2)) <= 1e-5
+        diff = (f64_of(o) - f64_of(o2))
+        assert np.all(np.abs(diff) <= 2.0 ** -7 * np.maximum(np.abs(f64_of(o2)), 0.25))
     for a, b in zip(gpu_lib.ulysses_sparse_attn_bwd(tq, tk, tv, o, tdo, lse, pat, 0.09),
                     gpu_lib.ulysses_attn_bwd(tq, tk, tv, o, tdo, lse, 0.09, True)):
         assert rel_l2(f64_of(a), f64_of(b)) <= 5e-3               # same terms, summed in another order
