@@ -457,7 +457,8 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     __shared__ __attribute__((aligned(1024))) e16 smem[2 * kDkvRing * TILE];
     __shared__ __attribute__((aligned(256))) float stat[kDkvRing * (STAT / 4)];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ln = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: LDS tile addresses stay scalar
     // Work assignment (causal): a workgroup takes key tile `pr` and then its mirror image
     // n_ktiles-1-pr, so every workgroup does the same amount of work.  It walks the query blocks of
     // the first tile downwards from the end of the sequence and those of the second upwards from its
@@ -663,16 +664,25 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
     wait_lgkm<0>();
     tie_rowq();
     tie_rowdo();
-    zero(s[0]); zero(dp[0]);
+    // The K and V operands live in accumulation registers, where the matrix unit reads them directly; S and dP
+    // come out in vector registers, where the vector unit reads them directly (mfma32_v_*).
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        s[0] = mfma32(rowq[t], kreg[t], s[0]);
-        dp[0] = mfma32(rowdo[t], vreg[t], dp[0]);
+        asm volatile("" : "+a"(kreg[t]));
+        asm volatile("" : "+a"(vreg[t]));
     }
-    __builtin_amdgcn_sched_barrier(0);
+    mfma32_v_first(s[0], rowq[0], kreg[0]);
+    mfma32_v_first(dp[0], rowdo[0], vreg[0]);
+#pragma unroll
+    for (int t = 1; t < NT; ++t) {
+        mfma32_v_acc(s[0], rowq[t], kreg[t]);
+        mfma32_v_acc(dp[0], rowdo[t], vreg[t]);
+    }
     read_stats(S0{});
     read_rowq(S1{});
     read_rowdo(S1{});
+    mfma32_v_settle(s[0], dp[0]);
+    __builtin_amdgcn_sched_barrier(0);
 
     // One iteration: walk position p (block b) lives in ring slot SL (its parity selects the s/dp set);
     // "b+1", "b+2" below mean the blocks of the next positions.
@@ -685,52 +695,58 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         const int i0 = blk(p) * kDkvBQ;
         const int jrel = jcol_g - i0;                  // (b_next: the tile fetched into this position's slot)
         e16x8 pb[2], dsb[2];
-        // P and dS of 8 rows of block b (vector pipe)
-        auto softmax_half = [&](int u) __attribute__((always_inline)) {
+        // P and dS of rows r, r+1 (r even) of block b (vector pipe), packed as soon as both are there
+        auto softmax_pair = [&](int r) __attribute__((always_inline)) {
+            float pv[2], dsv[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int r = 8 * u + e;
-                float x = __builtin_fmaf(s[PAR][r], sl2, -lse4[r >> 2][r & 3]);
-                if (MASKED && CAUSAL) x = (8 * (r >> 2) + (r & 3) < jrel) ? -INFINITY : x;
-                const float p = fast_exp2(x);
-                const float ds = p * (dp[PAR][r] - del4[r >> 2][r & 3]);
-                pb[u][e] = (e16)p;
-                dsb[u][e] = (e16)ds;
+            for (int e = 0; e < 2; ++e) {
+                const int rr = r + e;
+                float x = __builtin_fmaf(s[PAR][rr], sl2, -lse4[rr >> 2][rr & 3]);
+                if (MASKED && CAUSAL) x = (8 * (rr >> 2) + (rr & 3) < jrel) ? -INFINITY : x;
+                pv[e] = fast_exp2(x);
+                dsv[e] = pv[e] * (dp[PAR][rr] - del4[rr >> 2][rr & 3]);
             }
+            e16x2 pk = {(e16)pv[0], (e16)pv[1]}, dk = {(e16)dsv[0], (e16)dsv[1]};
+            asm volatile("" : "+v"(pk), "+v"(dk));    // packed here, not wherever the values are finally used
+            pb[r >> 3][r & 7] = pk[0];
+            pb[r >> 3][(r & 7) + 1] = pk[1];
+            dsb[r >> 3][r & 7] = dk[0];
+            dsb[r >> 3][(r & 7) + 1] = dk[1];
         };
-        auto interleave = [&]() __attribute__((always_inline)) {     // one MFMA, then a share of the vector work
-#pragma unroll
-            for (int i = 0; i < NT; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, MASKED ? 8 : 6, 0);    // VALU
-                __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // transcendental
+        // One MFMA of the next block's S (WHICH = 0) or dP (1), then this step's share of the vector work on rows
+        // 8u .. 8u+7 of block b; the MFMAs are fixed in place and the vector work does not cross them.
+        auto a_step = [&](auto which_tag, int t, int u) __attribute__((always_inline)) {
+            constexpr int WHICH = decltype(which_tag)::value;
+            if (WHICH == 0) {
+                if (t == 0) mfma32_v_first(s[PAR ^ 1], rowq[0], kreg[0]);
+                else mfma32_v_acc(s[PAR ^ 1], rowq[t], kreg[t]);
+            } else {
+                if (t == 0) mfma32_v_first(dp[PAR ^ 1], rowdo[0], vreg[0]);
+                else mfma32_v_acc(dp[PAR ^ 1], rowdo[t], vreg[t]);
             }
+            constexpr int PAIRS = 4 / (NT / 2);       // 4 pairs per half over NT MFMAs: one every other step (d = 128), one per step (d = 64)
+            if (NT == 8) { if (t & 1) softmax_pair(8 * u + (t - 1)); }
+            else softmax_pair(8 * u + 2 * t);
+            (void)PAIRS;
+            __builtin_amdgcn_sched_barrier(0);
         };
+        using W0 = std::integral_constant<int, 0>;
+        using W1 = std::integral_constant<int, 1>;
 
         wait_lgkm<NT>();                              // all but the dO rows: statistics of b, Q rows of b+1
         tie_rowq();
         __builtin_amdgcn_sched_barrier(0);
         // ---- region A1: S of block b+1 (matrix pipe) || P, dS of rows 0-15 of block b (vector pipe)
-        zero(s[PAR ^ 1]);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) s[PAR ^ 1] = mfma32(rowq[t], kreg[t], s[PAR ^ 1]);
-        softmax_half(0);
-        interleave();
-        lds_tie(pb[0], dsb[0]);                       // pin the vector work here (it would sink to its use)
-        __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < NT; ++t) a_step(W0{}, t, 0);
         wait_lgkm<0>();                               // dO rows of b+1
         tie_rowdo();
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) read_transposed(slot_tag, U0{}, cb);   // for region B1; lands during A2
         __builtin_amdgcn_sched_barrier(0);
         // ---- region A2: dP of block b+1 || P, dS of rows 16-31 of block b
-        zero(dp[PAR ^ 1]);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) dp[PAR ^ 1] = mfma32(rowdo[t], vreg[t], dp[PAR ^ 1]);
-        softmax_half(1);
-        interleave();
-        lds_tie(pb[1], dsb[1]);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < NT; ++t) a_step(W1{}, t, 1);
         wait_lgkm<0>();
         tie_transposed(0);
         __builtin_amdgcn_sched_barrier(0);

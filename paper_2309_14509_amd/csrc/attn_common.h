@@ -48,6 +48,29 @@ __device__ __forceinline__ f32x16 mfma32(e16x8 a, e16x8 b, f32x16 c) {
 #endif
 }
 
+// The same MFMA with its result in vector registers.  The compiler's own MFMAs of a kernel that uses more than
+// 256 registers all accumulate in accumulation registers, from which every score would have to be copied before
+// the vector unit can touch it; written out by hand, S (and dP) land where the softmax reads them, and the fixed
+// operand comes from an accumulation register.  The compiler does not see these as MFMAs, so callers keep the
+// distance the hardware needs themselves: at least eight other MFMAs (or mfma32_v_settle) between the last
+// of these and the first vector instruction that reads the result; an accumulation chain on one register set
+// needs nothing.
+#if defined(ULY_BUILD_F16)
+#define ULY_MFMA32_ASM "v_mfma_f32_32x32x16_f16"
+#else
+#define ULY_MFMA32_ASM "v_mfma_f32_32x32x16_bf16"
+#endif
+__device__ __forceinline__ void mfma32_v_first(f32x16& d, const e16x8& a, const e16x8& b) {
+    asm volatile(ULY_MFMA32_ASM " %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma32_v_acc(f32x16& d, const e16x8& a, const e16x8& b) {
+    asm volatile(ULY_MFMA32_ASM " %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+}
+// idles until MFMAs issued just before have written their results
+__device__ __forceinline__ void mfma32_v_settle(f32x16& x, f32x16& y) {
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(x), "+v"(y));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Registers 8u..8u+7 of a C/D block, rounded to the element type: a B operand whose contraction index e

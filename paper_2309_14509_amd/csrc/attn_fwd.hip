@@ -432,22 +432,6 @@ constexpr int kQ64BK = 32;
 constexpr int kQ64Ring = 4;
 constexpr float kQ64Lazy = 8.f;
 
-// S^T MFMAs with their result in vector registers (the compiler's own MFMAs of a kernel this large all
-// accumulate in accumulation registers, from which every score would have to be copied before the vector unit
-// can touch it).  The B operand comes from an accumulation register.  Callers keep at least eight other MFMAs
-// between the last of these and the first vector instruction that reads the result.
-#if defined(ULY_BUILD_F16)
-#define ULY_MFMA32_ASM "v_mfma_f32_32x32x16_f16"
-#else
-#define ULY_MFMA32_ASM "v_mfma_f32_32x32x16_bf16"
-#endif
-__device__ __forceinline__ void mfma32_v_first(f32x16& d, const e16x8& a, const e16x8& b) {
-    asm volatile(ULY_MFMA32_ASM " %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
-}
-__device__ __forceinline__ void mfma32_v_acc(f32x16& d, const e16x8& a, const e16x8& b) {
-    asm volatile(ULY_MFMA32_ASM " %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
-}
-
 template <bool CAUSAL>
 __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
     const e16* __restrict__ Q, const e16* __restrict__ K, const e16* __restrict__ V, e16* __restrict__ O,
@@ -640,8 +624,7 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
         mfma32_v_acc(s[0][1], krow[t], qreg[1][t]);
     }
     read_krow(S1{}, S0{});
-    // the vector unit must not read the scores before the last MFMA has written them
-    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0][0]), "+v"(s[0][1]));
+    mfma32_v_settle(s[0][0], s[0][1]);            // the vector unit must not read the scores before they are written
     __builtin_amdgcn_sched_barrier(0);
     {
         float m_blk[2];
