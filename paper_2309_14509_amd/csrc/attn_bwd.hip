@@ -88,7 +88,8 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
 
     __shared__ __attribute__((aligned(1024))) e16 smem[2 * kDqRing * TILE];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ln = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: LDS tile addresses stay scalar
     // Work assignment (causal): a workgroup takes query tile n_qtiles-1-pr and then its mirror image
     // pr, so every workgroup does the same amount of work.  It walks the key blocks of the first tile
     // upwards from the start of the sequence and those of the second downwards from its diagonal: at
@@ -259,15 +260,24 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     wait_lgkm<0>();
     tie_krow();
     tie_vrow();
-    zero(s[0]); zero(dp[0]);
+    // The Q and dO operands live in accumulation registers, where the matrix unit reads them directly; S^T and
+    // dP^T come out in vector registers, where the vector unit reads them directly (mfma32_v_*).
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        s[0] = mfma32(krow[t], qreg[t], s[0]);
-        dp[0] = mfma32(vrow[t], doreg[t], dp[0]);
+        asm volatile("" : "+a"(qreg[t]));
+        asm volatile("" : "+a"(doreg[t]));
     }
-    __builtin_amdgcn_sched_barrier(0);
+    mfma32_v_first(s[0], krow[0], qreg[0]);
+    mfma32_v_first(dp[0], vrow[0], doreg[0]);
+#pragma unroll
+    for (int t = 1; t < NT; ++t) {
+        mfma32_v_acc(s[0], krow[t], qreg[t]);
+        mfma32_v_acc(dp[0], vrow[t], doreg[t]);
+    }
     read_krow(S1{});
     read_vrow(S1{});
+    mfma32_v_settle(s[0], dp[0]);
+    __builtin_amdgcn_sched_barrier(0);
 
     // LDS reads in flight at entry, oldest first: K rows of b+1, V rows of b+1.
     // ("b+1", "b+2" below mean the blocks of the next walk positions)
@@ -277,46 +287,52 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         constexpr int PAR = SL & 1;
         const int krel = klim - blk(p) * kDqBK;        // (b_next: the tile fetched into this position's slot)
         e16x8 dsb[2];
-        auto softmax_half = [&](int u) __attribute__((always_inline)) {
+        // dS^T of key rows r, r+1 (r even) of block b (vector pipe), packed as soon as both are there
+        auto softmax_pair = [&](int r) __attribute__((always_inline)) {
+            float dsv[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int r = 8 * u + e;
-                float x = __builtin_fmaf(s[PAR][r], sl2, -lse2);
-                if (MASKED) x = (8 * (r >> 2) + (r & 3) > krel) ? -INFINITY : x;
+            for (int e = 0; e < 2; ++e) {
+                const int rr = r + e;
+                float x = __builtin_fmaf(s[PAR][rr], sl2, -lse2);
+                if (MASKED) x = (8 * (rr >> 2) + (rr & 3) > krel) ? -INFINITY : x;
                 const float p = fast_exp2(x);
-                dsb[u][e] = (e16)(p * (dp[PAR][r] - delta));
+                dsv[e] = p * (dp[PAR][rr] - delta);
             }
+            e16x2 dk = {(e16)dsv[0], (e16)dsv[1]};
+            asm volatile("" : "+v"(dk));              // packed here, not wherever the values are finally used
+            dsb[r >> 3][r & 7] = dk[0];
+            dsb[r >> 3][(r & 7) + 1] = dk[1];
         };
-        auto interleave = [&]() __attribute__((always_inline)) {
-#pragma unroll
-            for (int i = 0; i < NT; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, MASKED ? 7 : 5, 0);    // VALU
-                __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // transcendental
+        // One MFMA of the next block's S^T (WHICH = 0) or dP^T (1), then this step's share of the vector work on
+        // rows 8u .. 8u+7 of block b; the MFMAs are fixed in place and the vector work does not cross them.
+        auto a_step = [&](auto which_tag, int t, int u) __attribute__((always_inline)) {
+            constexpr int WHICH = decltype(which_tag)::value;
+            if (WHICH == 0) {
+                if (t == 0) mfma32_v_first(s[PAR ^ 1], krow[0], qreg[0]);
+                else mfma32_v_acc(s[PAR ^ 1], krow[t], qreg[t]);
+            } else {
+                if (t == 0) mfma32_v_first(dp[PAR ^ 1], vrow[0], doreg[0]);
+                else mfma32_v_acc(dp[PAR ^ 1], vrow[t], doreg[t]);
             }
+            // 4 pairs per half over NT MFMAs: one every other step (d = 128), one per step (d = 64)
+            if (NT == 8) { if (t & 1) softmax_pair(8 * u + (t - 1)); }
+            else softmax_pair(8 * u + 2 * t);
+            __builtin_amdgcn_sched_barrier(0);
         };
+        using W0 = std::integral_constant<int, 0>;
+        using W1 = std::integral_constant<int, 1>;
 
         wait_lgkm<NT>();                              // K rows of b+1 (the V rows may still be in flight)
         tie_krow();
         __builtin_amdgcn_sched_barrier(0);
-        zero(s[PAR ^ 1]);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) s[PAR ^ 1] = mfma32(krow[t], qreg[t], s[PAR ^ 1]);
-        softmax_half(0);
-        interleave();
-        lds_tie(dsb[0]);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < NT; ++t) a_step(W0{}, t, 0);
         wait_lgkm<0>();
         tie_vrow();
         read_transposed(slot_tag);                    // K^T of block b, for region B
         __builtin_amdgcn_sched_barrier(0);
-        zero(dp[PAR ^ 1]);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) dp[PAR ^ 1] = mfma32(vrow[t], doreg[t], dp[PAR ^ 1]);
-        softmax_half(1);
-        interleave();
-        lds_tie(dsb[1]);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < NT; ++t) a_step(W1{}, t, 1);
 
         wait_lgkm<0>();
         tie_transposed();
@@ -724,10 +740,9 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
                 if (t == 0) mfma32_v_first(dp[PAR ^ 1], rowdo[0], vreg[0]);
                 else mfma32_v_acc(dp[PAR ^ 1], rowdo[t], vreg[t]);
             }
-            constexpr int PAIRS = 4 / (NT / 2);       // 4 pairs per half over NT MFMAs: one every other step (d = 128), one per step (d = 64)
+            // 4 pairs per half over NT MFMAs: one every other step (d = 128), one per step (d = 64)
             if (NT == 8) { if (t & 1) softmax_pair(8 * u + (t - 1)); }
             else softmax_pair(8 * u + 2 * t);
-            (void)PAIRS;
             __builtin_amdgcn_sched_barrier(0);
         };
         using W0 = std::integral_constant<int, 0>;
