@@ -43,6 +43,139 @@ def scratch_bytes(compiler_output: str) -> dict:
     return found
 
 
+# The hot kernels issue some MFMAs as inline asm so that their result lands in vector registers.  The compiler
+# takes such a result to be there at once; it neither waits before it reads the registers nor keeps them free once
+# the value is dead.  The kernels are written so that both hold anyway; this check reads the generated code and
+# refuses the build when, on some path, anything touches the result of such an MFMA too soon after it: fewer
+# than two further MFMAs and fewer than kMinCycles issue cycles of other instructions in between.
+MFMA_ASM_CHECKED = {"attn_fwd.hip", "attn_bwd.hip"}
+kMinCycles = 64
+
+
+def _regs(tok: str) -> set:
+    m = re.match(r"([va])\[(\d+):(\d+)\]", tok)
+    if m:
+        return {(m.group(1), i) for i in range(int(m.group(2)), int(m.group(3)) + 1)}
+    m = re.match(r"([va])(\d+)$", tok)
+    return {(m.group(1), int(m.group(2)))} if m else set()
+
+
+def early_touches_of_asm_mfma_results(asm_text: str) -> list:
+    """[(kernel, mfma line, touching line, cycles, mfmas between)] for every violation found in `asm_text`."""
+    found = []
+    kernel, lines, labels = None, [], {}
+    in_asm = False
+    for raw in asm_text.splitlines():
+        if ";;#ASMSTART" in raw:
+            in_asm = True
+        elif ";;#ASMEND" in raw:
+            in_asm = False
+        l = raw.split(";")[0].strip()
+        if not l:
+            continue
+        if in_asm and l.startswith("v_mfma"):
+            l = "asm." + l                             # hand-written, as opposed to the compiler's own
+        m = re.match(r"(\S+):$", l)
+        if m:
+            if not m.group(1).startswith(".L"):
+                if kernel is not None:
+                    found += _scan_kernel(kernel, lines, labels)
+                kernel, lines, labels = m.group(1), [], {}
+            else:
+                labels[m.group(1)] = len(lines)
+            continue
+        if kernel is None or l.startswith("."):
+            continue
+        lines.append(l)
+    if kernel is not None:
+        found += _scan_kernel(kernel, lines, labels)
+    return found
+
+
+def _scan_kernel(kernel: str, lines: list, labels: dict) -> list:
+    out = []
+    for i, l in enumerate(lines):
+        if not l.startswith("asm.v_mfma"):
+            continue                                   # the compiler looks after its own MFMAs
+        ops = [t.strip() for t in l.split(None, 1)[1].split(",")]
+        dst = _regs(ops[0])
+        stack, seen = [(i + 1, 0, 0)], set()
+        while stack:
+            pos, cycles, mfmas = stack.pop()
+            while pos < len(lines) and (cycles < kMinCycles and mfmas < 2):
+                if (pos, mfmas) in seen:
+                    break
+                seen.add((pos, mfmas))
+                n = lines[pos]
+                name, _, rest = n.partition(" ")
+                toks = [t.strip() for t in rest.split(",")] if rest else []
+                if name.startswith(("v_mfma", "asm.v_mfma")):
+                    if _regs(toks[0]) == dst and _regs(toks[-1]) == dst:
+                        break                          # the chain goes on in place: hardware interlocks that
+                    if any(_regs(t) & dst for t in toks):
+                        out.append((kernel, l, n, cycles, mfmas))
+                        break
+                    mfmas += 1
+                elif name == "s_nop":
+                    cycles += int(toks[0]) + 1
+                elif name in ("s_branch",):
+                    pos = labels.get(toks[0], len(lines))
+                    continue
+                elif name.startswith("s_cbranch"):
+                    if toks[0] in labels:
+                        stack.append((labels[toks[0]], cycles + 4, mfmas))
+                    cycles += 4
+                elif name == "s_endpgm":
+                    break
+                else:
+                    if any(_regs(t) & dst for t in toks):
+                        out.append((kernel, l, n, cycles, mfmas))
+                        break
+                    cycles += 4
+                pos += 1
+    return out
+
+
+# The same kernels issue LDS reads as inline asm and wait for them later.  Until that wait the compiler takes the
+# destination registers to hold their data already: if it copies or reuses one of them in between (it does when
+# it is short of registers) the copy holds stale data.  This check walks the generated code of the kernels named
+# here in program order and refuses the build if any instruction touches the destination of a read that no
+# s_waitcnt has covered yet.
+LDS_ASM_CHECKED_KERNELS = ("attn_fwd_q64_kernel", "attn_bwd_dq_kernel", "attn_bwd_dkv_kernel")
+
+
+def touches_of_lds_reads_in_flight(asm_text: str) -> list:
+    """[(kernel, read, touching instruction)] for every violation found in the kernels named above."""
+    out, kernel, fifo = [], None, []
+    for raw in asm_text.splitlines():
+        l = raw.split(";")[0].strip()
+        if not l:
+            continue
+        m = re.match(r"(\S+):$", l)
+        if m:
+            if not m.group(1).startswith(".L"):
+                kernel, fifo = m.group(1), []
+            continue
+        if kernel is None or l.startswith(".") or not any(k in kernel for k in LDS_ASM_CHECKED_KERNELS):
+            continue
+        name, _, rest = l.partition(" ")
+        toks = [t.strip() for t in rest.split(",")] if rest else []
+        if name == "s_waitcnt":
+            m = re.search(r"lgkmcnt\((\d+)\)", l)
+            if m:
+                del fifo[:max(0, len(fifo) - int(m.group(1)))]
+            continue
+        if name.startswith("ds_read"):
+            fifo.append((l, _regs(toks[0])))
+            continue
+        if name.startswith("s_load"):
+            fifo.append((l, set()))                    # scalar loads count in the same counter
+            continue
+        touched = set().union(*[_regs(t) for t in toks]) if toks else set()
+        out += [(kernel, rl, l) for rl, d in fifo if touched & d]
+    return out
+
+
 def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -64,6 +197,32 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
             print(" ".join(cmd), flush=True)
         procs.append((src, stem, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
+    asm_procs = []
+    for src, stem, extra in UNITS:
+        if src in MFMA_ASM_CHECKED:
+            asm = os.path.join(CSRC, stem + ".s")
+            cmd = [HIPCC, *FLAGS, *extra, "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", asm]
+            asm_procs.append((stem, asm, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for stem, asm, p in asm_procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            sys.stderr.write(out)
+            raise RuntimeError(f"hipcc -S failed on {stem}")
+        with open(asm) as f:
+            text = f.read()
+        os.remove(asm)
+        stale = touches_of_lds_reads_in_flight(text)
+        if stale:
+            for k, a, b in stale[:10]:
+                sys.stderr.write(f"{stem}: {k}: `{b}` while `{a}` is in flight\n")
+            raise RuntimeError(f"{stem}: registers of LDS reads in flight are touched ({len(stale)} places)")
+        bad = early_touches_of_asm_mfma_results(text)
+        if bad:
+            for k, a, b, cyc, nm in bad[:10]:
+                sys.stderr.write(f"{stem}: {k}: `{b}` {cyc} cycles and {nm} MFMAs after `{a}`\n")
+            raise RuntimeError(f"{stem}: results of hand-written MFMAs are touched too early ({len(bad)} places)")
+        if verbose:
+            print(f"{stem}: hand-written MFMA results are left alone long enough", flush=True)
     for src, stem, p in procs:
         out, _ = p.communicate()
         if p.returncode != 0:

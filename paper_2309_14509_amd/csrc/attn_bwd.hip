@@ -287,21 +287,33 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         constexpr int PAR = SL & 1;
         const int krel = klim - blk(p) * kDqBK;        // (b_next: the tile fetched into this position's slot)
         e16x8 dsb[2];
-        // dS^T of key rows r, r+1 (r even) of block b (vector pipe), packed as soon as both are there
-        auto softmax_pair = [&](int r) __attribute__((always_inline)) {
-            float dsv[2];
+        // dS^T of block b (vector pipe), a pair of key rows at a time, in three stages a step apart so that no
+        // instruction waits for the one before it: exponent, exponential, product (packed at once)
+        float xv[8], pv[8];
+        auto softmax_stage = [&](int u, int step) __attribute__((always_inline)) {
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int rr = r + e;
-                float x = __builtin_fmaf(s[PAR][rr], sl2, -lse2);
-                if (MASKED) x = (8 * (rr >> 2) + (rr & 3) > krel) ? -INFINITY : x;
-                const float p = fast_exp2(x);
-                dsv[e] = p * (dp[PAR][rr] - delta);
+            for (int j = 0; j < 4; ++j) {             // pair j: rows 8u+2j, 8u+2j+1
+                const int first = NT == 8 ? j + j / 2 : j / 2, r = 8 * u + 2 * j;
+                if (step == first) {
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int rr = r + e;
+                        float x = __builtin_fmaf(s[PAR][rr], sl2, -lse2);
+                        if (MASKED) x = (8 * (rr >> 2) + (rr & 3) > krel) ? -INFINITY : x;
+                        xv[2 * j + e] = x;
+                    }
+                }
+                if (step == first + 1) {
+                    pv[2 * j] = fast_exp2(xv[2 * j]);
+                    pv[2 * j + 1] = fast_exp2(xv[2 * j + 1]);
+                }
+                if (step == first + 2) {
+                    e16x2 dk = {(e16)(pv[2 * j] * (dp[PAR][r] - delta)), (e16)(pv[2 * j + 1] * (dp[PAR][r + 1] - delta))};
+                    asm volatile("" : "+v"(dk));      // packed here, not wherever the values are finally used
+                    dsb[u][2 * j] = dk[0];
+                    dsb[u][2 * j + 1] = dk[1];
+                }
             }
-            e16x2 dk = {(e16)dsv[0], (e16)dsv[1]};
-            asm volatile("" : "+v"(dk));              // packed here, not wherever the values are finally used
-            dsb[r >> 3][r & 7] = dk[0];
-            dsb[r >> 3][(r & 7) + 1] = dk[1];
         };
         // One MFMA of the next block's S^T (WHICH = 0) or dP^T (1), then this step's share of the vector work on
         // rows 8u .. 8u+7 of block b; the MFMAs are fixed in place and the vector work does not cross them.
@@ -314,9 +326,7 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
                 if (t == 0) mfma32_v_first(dp[PAR ^ 1], vrow[0], doreg[0]);
                 else mfma32_v_acc(dp[PAR ^ 1], vrow[t], doreg[t]);
             }
-            // 4 pairs per half over NT MFMAs: one every other step (d = 128), one per step (d = 64)
-            if (NT == 8) { if (t & 1) softmax_pair(8 * u + (t - 1)); }
-            else softmax_pair(8 * u + 2 * t);
+            softmax_stage(u, t);
             __builtin_amdgcn_sched_barrier(0);
         };
         using W0 = std::integral_constant<int, 0>;
@@ -399,9 +409,11 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         iteration(Masked{}, S3{}, S1{}, p + 3, blk(p + 3 + kDqRing)); settle();
     }
     // Nothing may still be writing LDS when this query tile ends, and the operand reads issued for a
-    // block that does not exist must have landed before their (now dead) registers are reused.
+    // block that does not exist must have landed before their (now dead) registers are reused; the same
+    // goes for the S^T and dP^T of that block, which are still on their way through the matrix unit.
     wait_vm<0>();
     wait_lgkm<0>();
+    mfma32_v_settle(s[0], s[1], dp[0], dp[1]);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) lds_tie(acc[cb]);
     __builtin_amdgcn_sched_barrier(0);
@@ -711,23 +723,37 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         const int i0 = blk(p) * kDkvBQ;
         const int jrel = jcol_g - i0;                  // (b_next: the tile fetched into this position's slot)
         e16x8 pb[2], dsb[2];
-        // P and dS of rows r, r+1 (r even) of block b (vector pipe), packed as soon as both are there
-        auto softmax_pair = [&](int r) __attribute__((always_inline)) {
-            float pv[2], dsv[2];
+        // P and dS of block b (vector pipe), a pair of query rows at a time, in three stages a step apart so that
+        // no instruction waits for the one before it: exponent, exponential, product (both packed at once)
+        float xv[8], pv[8];
+        auto softmax_stage = [&](int u, int step) __attribute__((always_inline)) {
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int rr = r + e;
-                float x = __builtin_fmaf(s[PAR][rr], sl2, -lse4[rr >> 2][rr & 3]);
-                if (MASKED && CAUSAL) x = (8 * (rr >> 2) + (rr & 3) < jrel) ? -INFINITY : x;
-                pv[e] = fast_exp2(x);
-                dsv[e] = pv[e] * (dp[PAR][rr] - del4[rr >> 2][rr & 3]);
+            for (int j = 0; j < 4; ++j) {             // pair j: rows 8u+2j, 8u+2j+1
+                const int first = NT == 8 ? j + j / 2 : j / 2, r = 8 * u + 2 * j;
+                if (step == first) {
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int rr = r + e;
+                        float x = __builtin_fmaf(s[PAR][rr], sl2, -lse4[rr >> 2][rr & 3]);
+                        if (MASKED && CAUSAL) x = (8 * (rr >> 2) + (rr & 3) < jrel) ? -INFINITY : x;
+                        xv[2 * j + e] = x;
+                    }
+                }
+                if (step == first + 1) {
+                    pv[2 * j] = fast_exp2(xv[2 * j]);
+                    pv[2 * j + 1] = fast_exp2(xv[2 * j + 1]);
+                }
+                if (step == first + 2) {
+                    e16x2 pk = {(e16)pv[2 * j], (e16)pv[2 * j + 1]};
+                    e16x2 dk = {(e16)(pv[2 * j] * (dp[PAR][r] - del4[r >> 2][r & 3])),
+                                (e16)(pv[2 * j + 1] * (dp[PAR][r + 1] - del4[(r + 1) >> 2][(r + 1) & 3]))};
+                    asm volatile("" : "+v"(pk), "+v"(dk));    // packed here, not wherever the values are finally used
+                    pb[u][2 * j] = pk[0];
+                    pb[u][2 * j + 1] = pk[1];
+                    dsb[u][2 * j] = dk[0];
+                    dsb[u][2 * j + 1] = dk[1];
+                }
             }
-            e16x2 pk = {(e16)pv[0], (e16)pv[1]}, dk = {(e16)dsv[0], (e16)dsv[1]};
-            asm volatile("" : "+v"(pk), "+v"(dk));    // packed here, not wherever the values are finally used
-            pb[r >> 3][r & 7] = pk[0];
-            pb[r >> 3][(r & 7) + 1] = pk[1];
-            dsb[r >> 3][r & 7] = dk[0];
-            dsb[r >> 3][(r & 7) + 1] = dk[1];
         };
         // One MFMA of the next block's S (WHICH = 0) or dP (1), then this step's share of the vector work on rows
         // 8u .. 8u+7 of block b; the MFMAs are fixed in place and the vector work does not cross them.
@@ -740,9 +766,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
                 if (t == 0) mfma32_v_first(dp[PAR ^ 1], rowdo[0], vreg[0]);
                 else mfma32_v_acc(dp[PAR ^ 1], rowdo[t], vreg[t]);
             }
-            // 4 pairs per half over NT MFMAs: one every other step (d = 128), one per step (d = 64)
-            if (NT == 8) { if (t & 1) softmax_pair(8 * u + (t - 1)); }
-            else softmax_pair(8 * u + 2 * t);
+            softmax_stage(u, t);
             __builtin_amdgcn_sched_barrier(0);
         };
         using W0 = std::integral_constant<int, 0>;
@@ -872,9 +896,11 @@ __global__ __launch_bounds__(kDkvThreads, 1) void attn_bwd_dkv_kernel(
         iteration(Masked{}, S3{}, S0{}, S1{}, p + 3, blk(p + 3 + kDkvRing)); settle();
     }
     // Nothing may still be writing LDS when this key tile ends, and the operand reads issued for a
-    // block that does not exist must have landed before their (now dead) registers are reused.
+    // block that does not exist must have landed before their (now dead) registers are reused; the same
+    // goes for the S and dP of that block, which are still on their way through the matrix unit.
     wait_vm<0>();
     wait_lgkm<0>();
+    mfma32_v_settle(s[0], s[1], dp[0], dp[1]);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) lds_tie(dk_acc[cb], dv_acc[cb]);
     __builtin_amdgcn_sched_barrier(0);

@@ -66,9 +66,14 @@ __device__ __forceinline__ void mfma32_v_first(f32x16& d, const e16x8& a, const 
 __device__ __forceinline__ void mfma32_v_acc(f32x16& d, const e16x8& a, const e16x8& b) {
     asm volatile(ULY_MFMA32_ASM " %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
 }
-// idles until MFMAs issued just before have written their results
-__device__ __forceinline__ void mfma32_v_settle(f32x16& x, f32x16& y) {
-    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(x), "+v"(y));
+template <typename T> __device__ __forceinline__ void lds_tie1(T& r);
+// Idles until MFMAs issued just before have written their results, and keeps those registers allocated until
+// then.  Needed wherever such a result is read right away, and also where it is never read (the S computed for
+// the block after the last one): to the compiler a register whose value is dead is free at once, and whatever it
+// put there would be overwritten when the MFMA completes.
+template <typename... T> __device__ __forceinline__ void mfma32_v_settle(T&... acc) {
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15");
+    (lds_tie1(acc), ...);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

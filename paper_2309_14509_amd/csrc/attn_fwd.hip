@@ -623,7 +623,6 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
         mfma32_v_acc(s[0][0], krow[t], qreg[0][t]);
         mfma32_v_acc(s[0][1], krow[t], qreg[1][t]);
     }
-    read_krow(S1{}, S0{});
     mfma32_v_settle(s[0][0], s[0][1]);            // the vector unit must not read the scores before they are written
     __builtin_amdgcn_sched_barrier(0);
     {
@@ -635,6 +634,10 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
             ms[qb] = (m_used[qb] == -INFINITY ? 0.f : m_used[qb]) * sl2;
         }
     }
+    // (no other work between a hand-issued read and its wait here: outside the loop the compiler moves registers
+    // around freely, also ones whose data is still on its way)
+    __builtin_amdgcn_sched_barrier(0);
+    read_krow(S1{}, S0{});
     wait_lgkm<0>();
     tie_krow(S0{});
     __builtin_amdgcn_sched_barrier(0);
@@ -661,34 +664,60 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
             pb[qb][r >> 3][r & 7] = pk[0];
             pb[qb][r >> 3][(r & 7) + 1] = pk[1];
         };
-        // S^T of block p+1, K channels 16t..16t+15, for both query blocks, each MFMA followed by the vector work
-        // of one score pair of block p (the MFMAs are fixed in place; the vector work may not cross them)
-        auto s_step = [&](int t, int j0, int j1) __attribute__((always_inline)) {
+        // The first ten score pairs of block p go through three stages one MFMA apart (exponent, exponential, sum and
+        // packing), so that no vector instruction waits for the one before it; pair j starts at step j + j / 2.
+        constexpr int kStaged = 10;
+        float xv[2 * kStaged], pv[2 * kStaged];
+        auto exp_stage = [&](int step) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = 0; j < kStaged; ++j) {
+                const int first = j + j / 2, qb = j >> 3, r = 2 * (j & 7);
+                if (step == first) {
+                    xv[2 * j] = __builtin_fmaf(s[PAR][qb][r], sl2, -ms[qb]);
+                    xv[2 * j + 1] = __builtin_fmaf(s[PAR][qb][r + 1], sl2, -ms[qb]);
+                }
+                if (step == first + 1) {
+                    pv[2 * j] = fast_exp2(xv[2 * j]);
+                    pv[2 * j + 1] = fast_exp2(xv[2 * j + 1]);
+                }
+                if (step == first + 2) {
+                    rs[qb] += pv[2 * j];
+                    rs[qb] += pv[2 * j + 1];
+                    e16x2 pk = {(e16)pv[2 * j], (e16)pv[2 * j + 1]};
+                    asm volatile("" : "+v"(pk));      // packed here, not wherever the value is finally used
+                    pb[qb][r >> 3][r & 7] = pk[0];
+                    pb[qb][r >> 3][(r & 7) + 1] = pk[1];
+                }
+            }
+        };
+        // S^T of block p+1, K channels 16t..16t+15, for both query blocks, each MFMA followed by one step of the
+        // vector work on block p (the MFMAs are fixed in place; the vector work may not cross them)
+        auto s_step = [&](int t) __attribute__((always_inline)) {
             if (t == 0) mfma32_v_first(s[PAR ^ 1][0], krow[0], qreg[0][0]);
             else mfma32_v_acc(s[PAR ^ 1][0], krow[t], qreg[0][t]);
-            if (j0 >= 0) exp_pair(j0);
+            exp_stage(2 * t);
             __builtin_amdgcn_sched_barrier(0);
             if (t == 0) mfma32_v_first(s[PAR ^ 1][1], krow[0], qreg[1][0]);
             else mfma32_v_acc(s[PAR ^ 1][1], krow[t], qreg[1][t]);
-            if (j1 >= 0) exp_pair(j1);
+            exp_stage(2 * t + 1);
             __builtin_amdgcn_sched_barrier(0);
         };
         // ---- region A, first half
         read_krow(std::integral_constant<int, (SL + 1) % kQ64Ring>{}, S1{});     // K rows of block p+1, channels 64..127
         __builtin_amdgcn_sched_barrier(0);
-        s_step(0, 0, 1);
-        s_step(1, -1, 2);
-        s_step(2, 3, -1);
-        s_step(3, 4, -1);
+        s_step(0);
+        s_step(1);
+        s_step(2);
+        s_step(3);
         // ---- region A, second half
         wait_lgkm<0>();
         tie_krow(S1{});
         read_transposed(slotv_tag, S0{});             // V^T of block p-1, keys 0..15
         __builtin_amdgcn_sched_barrier(0);
-        s_step(4, 5, 6);
-        s_step(5, -1, 7);
-        s_step(6, 8, -1);
-        s_step(7, 9, -1);
+        s_step(4);
+        s_step(5);
+        s_step(6);
+        s_step(7);
 
         // ---- region B: tiles up to p+2 (K) and p+1 (V) have landed; everyone is done with the K tile of block p
         // and the V tile of block p-2, which are refilled with the K tile of block p+4 and the V tile of block p+2
@@ -790,7 +819,9 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
         iteration(Masked{}, S3{}, S1{}, S2{}, p + 3);
     }
     // ---- the product with V of the last block (cnt is a multiple of 4: its V tile is in slot 3).  After it
-    // nothing is writing LDS any more.
+    // nothing is writing LDS any more.  The scores of the block after the last one, which nobody reads, are still
+    // on their way through the matrix unit: their registers stay untouched until they have arrived.
+    mfma32_v_settle(s[0][0], s[0][1], s[1][0], s[1][1]);
     read_transposed(S3{}, S0{});
     read_transposed(S3{}, S1{});
     wait_vm<0>();
