@@ -62,32 +62,18 @@ def _regs(tok: str) -> set:
 
 def early_touches_of_asm_mfma_results(asm_text: str) -> list:
     """[(kernel, mfma line, touching line, cycles, mfmas between)] for every violation found in `asm_text`."""
-    found = []
-    kernel, lines, labels = None, [], {}
+    marked = []
     in_asm = False
     for raw in asm_text.splitlines():
         if ";;#ASMSTART" in raw:
             in_asm = True
         elif ";;#ASMEND" in raw:
             in_asm = False
-        l = raw.split(";")[0].strip()
-        if not l:
-            continue
-        if in_asm and l.startswith("v_mfma"):
-            l = "asm." + l                             # hand-written, as opposed to the compiler's own
-        m = re.match(r"(\S+):$", l)
-        if m:
-            if not m.group(1).startswith(".L"):
-                if kernel is not None:
-                    found += _scan_kernel(kernel, lines, labels)
-                kernel, lines, labels = m.group(1), [], {}
-            else:
-                labels[m.group(1)] = len(lines)
-            continue
-        if kernel is None or l.startswith("."):
-            continue
-        lines.append(l)
-    if kernel is not None:
+        if in_asm and raw.split(";")[0].strip().startswith("v_mfma"):
+            raw = raw.replace("v_mfma", "asm.v_mfma", 1)      # hand-written, as opposed to the compiler's own
+        marked.append(raw)
+    found = []
+    for kernel, lines, labels in _split_kernels("\n".join(marked)):
         found += _scan_kernel(kernel, lines, labels)
     return found
 
@@ -138,15 +124,11 @@ def _scan_kernel(kernel: str, lines: list, labels: dict) -> list:
 
 # The same kernels issue LDS reads as inline asm and wait for them later.  Until that wait the compiler takes the
 # destination registers to hold their data already: if it copies or reuses one of them in between (it does when
-# it is short of registers) the copy holds stale data.  This check walks the generated code of the kernels named
-# here in program order and refuses the build if any instruction touches the destination of a read that no
-# s_waitcnt has covered yet.
-LDS_ASM_CHECKED_KERNELS = ("attn_fwd_q64_kernel", "attn_bwd_dq_kernel", "attn_bwd_dkv_kernel")
-
-
-def touches_of_lds_reads_in_flight(asm_text: str) -> list:
-    """[(kernel, read, touching instruction)] for every violation found in the kernels named above."""
-    out, kernel, fifo = [], None, []
+# it is short of registers, and at control-flow joins) the copy holds stale data.  This check follows every path
+# through the generated code of the attention kernels, keeps the LDS operations no s_waitcnt has covered yet,
+# and refuses the build if any instruction touches the destination of a read among them.
+def _split_kernels(asm_text: str):
+    kernel, lines, labels = None, [], {}
     for raw in asm_text.splitlines():
         l = raw.split(";")[0].strip()
         if not l:
@@ -154,25 +136,58 @@ def touches_of_lds_reads_in_flight(asm_text: str) -> list:
         m = re.match(r"(\S+):$", l)
         if m:
             if not m.group(1).startswith(".L"):
-                kernel, fifo = m.group(1), []
+                if kernel is not None:
+                    yield kernel, lines, labels
+                kernel, lines, labels = m.group(1), [], {}
+            else:
+                labels[m.group(1)] = len(lines)
             continue
-        if kernel is None or l.startswith(".") or not any(k in kernel for k in LDS_ASM_CHECKED_KERNELS):
+        if kernel is None or l.startswith("."):
             continue
-        name, _, rest = l.partition(" ")
-        toks = [t.strip() for t in rest.split(",")] if rest else []
-        if name == "s_waitcnt":
-            m = re.search(r"lgkmcnt\((\d+)\)", l)
-            if m:
-                del fifo[:max(0, len(fifo) - int(m.group(1)))]
+        lines.append(l)
+    if kernel is not None:
+        yield kernel, lines, labels
+
+
+def touches_of_lds_reads_in_flight(asm_text: str) -> list:
+    """[(kernel, read, touching instruction)] for every violation found in kernels whose name contains `attn_`."""
+    out = []
+    for kernel, lines, labels in _split_kernels(asm_text):
+        if "attn_" not in kernel:
             continue
-        if name.startswith("ds_read"):
-            fifo.append((l, _regs(toks[0])))
-            continue
-        if name.startswith("s_load"):
-            fifo.append((l, set()))                    # scalar loads count in the same counter
-            continue
-        touched = set().union(*[_regs(t) for t in toks]) if toks else set()
-        out += [(kernel, rl, l) for rl, d in fifo if touched & d]
+        found, seen, stack = set(), set(), [(0, ())]
+        while stack:
+            pos, state = stack.pop()
+            fifo = list(state)                         # (position of the LDS operation, registers it writes)
+            while pos < len(lines):
+                key = (pos, tuple(p for p, _ in fifo))
+                if key in seen:
+                    break
+                seen.add(key)
+                l = lines[pos]
+                name, _, rest = l.partition(" ")
+                toks = [t.strip() for t in rest.split(",")] if rest else []
+                if name == "s_waitcnt":
+                    m = re.search(r"lgkmcnt\((\d+)\)", l)
+                    if m:
+                        fifo = fifo[max(0, len(fifo) - int(m.group(1))):]
+                elif name.startswith("ds_read"):
+                    fifo.append((pos, frozenset(_regs(toks[0]))))
+                elif name.startswith(("ds_", "s_load")):
+                    fifo.append((pos, frozenset()))    # other LDS operations and scalar loads use the same counter
+                elif name == "s_branch":
+                    pos = labels.get(toks[0], len(lines))
+                    continue
+                elif name.startswith("s_cbranch"):
+                    if toks[0] in labels:
+                        stack.append((labels[toks[0]], tuple(fifo)))
+                elif name == "s_endpgm":
+                    break
+                else:
+                    touched = set().union(*[_regs(t) for t in toks]) if toks else set()
+                    found |= {(lines[p], l) for p, d in fifo if touched & d}
+                pos += 1
+        out += [(kernel, a, b) for a, b in sorted(found)]
     return out
 
 

@@ -213,6 +213,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
     else wait_direct_loads();
     __syncthreads();
     read_k(std::integral_constant<int, K0>{}, First{});
+    wait_k(First{});                    // before the loops are entered: at a join the compiler may copy these registers
 
     // One 32-key block: S^T (K operands already on their way) -> read V of the first 16 keys -> softmax
     // -> read the next block's K -> PV of the first 16 keys -> read V of the last 16 keys -> PV of those.
@@ -330,6 +331,14 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
             if (pos + 1 < n_kt) read_k(kn_tag, First{});
         }
         pv_half(1);
+        if (LAST) {
+            // The K reads for the next tile were issued eight MFMAs ago.  They are waited for here, before
+            // control flow joins again (end of the tile, loop edges), because at a join the compiler may copy
+            // registers without knowing that a hand-issued read into them is still on its way.
+            __builtin_amdgcn_sched_barrier(0);
+            wait_k(First{});
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     // Blocks entirely below the diagonal for every wave and inside the sequence need no mask.

@@ -52,3 +52,15 @@ def test_partial_waits_retire_the_oldest_reads_only():
 def test_kernels_that_manage_their_reads_through_the_compiler_are_not_checked():
     other = "_Z5otherv:\n\tds_read_b128 v[8:11], v2\n\tv_mov_b32_e32 v40, v8\n\ts_endpgm\n"
     assert build.touches_of_lds_reads_in_flight(other) == []
+
+
+def test_a_read_in_flight_is_followed_into_both_sides_of_a_branch():
+    text = (KERNEL + "\tds_read_b128 v[8:11], v2\n\ts_cbranch_scc1 .LBB0_2\n\ts_waitcnt lgkmcnt(0)\n\tv_mov_b32_e32 v40, v8\n\ts_endpgm\n"
+            ".LBB0_2:\n\tv_mov_b64_e32 v[50:51], v[8:9]\n\ts_waitcnt lgkmcnt(0)\n\ts_endpgm\n")
+    found = build.touches_of_lds_reads_in_flight(text)
+    assert [f[2] for f in found] == ["v_mov_b64_e32 v[50:51], v[8:9]"]
+
+
+def test_lds_writes_count_in_the_same_counter():
+    text = (KERNEL + "\tds_read_b128 v[8:11], v2\n\tds_write_b32 v3, v4\n\ts_waitcnt lgkmcnt(1)\n\tv_mov_b32_e32 v40, v8\n\ts_endpgm\n")
+    assert build.touches_of_lds_reads_in_flight(text) == []
