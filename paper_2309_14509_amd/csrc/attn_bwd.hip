@@ -130,6 +130,17 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         Loader::issue_sel(smem + (kDqRing + slot) * TILE, Vh + (int64_t)r0 * row_stride, ld, ld_tail, is_tail, wave);
     };
     const float sl2 = scale * kLog2e;
+    // For the stretch of a walk whose fetches are consecutive whole blocks (no clamp, no ragged tile): running
+    // pointers, one step per tile, instead of an address computed from the block index.
+    const e16* k_next = nullptr;
+    const e16* v_next = nullptr;
+    int64_t tile_step = 0;              // elements from one fetched block to the next (negative walking down)
+    auto load_tile_next = [&](int slot) __attribute__((always_inline)) {
+        Loader::issue(smem + slot * TILE, k_next, ld, wave);
+        Loader::issue(smem + (kDqRing + slot) * TILE, v_next, ld, wave);
+        k_next += tile_step;
+        v_next += tile_step;
+    };
 
     const uint32_t sbase = lds_addr(smem);
     uint32_t r_adr[NT];
@@ -281,8 +292,10 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
 
     // LDS reads in flight at entry, oldest first: K rows of b+1, V rows of b+1.
     // ("b+1", "b+2" below mean the blocks of the next walk positions)
-    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot2_tag, int p, int b_next) __attribute__((always_inline)) {
+    auto iteration = [&](auto masked_tag, auto slot_tag, auto slot2_tag, int p, int b_next, auto simple_tag)
+                         __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
+        constexpr bool SIMPLE = decltype(simple_tag)::value;      // fetch through the running pointers
         constexpr int SL = decltype(slot_tag)::value;
         constexpr int PAR = SL & 1;
         const int krel = klim - blk(p) * kDqBK;        // (b_next: the tile fetched into this position's slot)
@@ -348,7 +361,8 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
         tie_transposed();
         wait_vm<LPT>();                               // tile b+2 has landed; everyone is done with tile b
         barrier_no_drain();
-        load_tile(SL, b_next);
+        if (SIMPLE) load_tile_next(SL);
+        else load_tile(SL, b_next);
         read_krow(slot2_tag);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -363,6 +377,8 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
 
     using Plain = std::integral_constant<bool, false>;
     using Masked = std::integral_constant<bool, true>;
+    using General = std::integral_constant<bool, false>;
+    using Simple = std::integral_constant<bool, true>;
     // The compiler may move registers (copies at control-flow joins, spills) without knowing that a
     // hand-issued LDS read into them is still in flight, so outside the steady-state loop every
     // iteration is followed by settle(): all reads landed, their registers tied.
@@ -376,13 +392,36 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
     int p = 0;
     settle();
     if (dir < 0) {
-        iteration(Masked{}, S0{}, S2{}, 0, blk(kDqRing)); settle();
-        iteration(Masked{}, S1{}, S3{}, 1, blk(1 + kDqRing)); settle();
-        iteration(Masked{}, S2{}, S0{}, 2, blk(2 + kDqRing)); settle();
-        iteration(Masked{}, S3{}, S1{}, 3, blk(3 + kDqRing)); settle();
+        iteration(Masked{}, S0{}, S2{}, 0, blk(kDqRing), General{}); settle();
+        iteration(Masked{}, S1{}, S3{}, 1, blk(1 + kDqRing), General{}); settle();
+        iteration(Masked{}, S2{}, S0{}, 2, blk(2 + kDqRing), General{}); settle();
+        iteration(Masked{}, S3{}, S1{}, 3, blk(3 + kDqRing), General{}); settle();
         p = 4;
     }
     const int plain_end = dir > 0 ? walk - 4 : walk;
+    if constexpr (!SPARSE && !PLAN) {
+        // Groups of four iterations whose fetches (walk positions p+4 .. p+7) are neither clamped to the end of
+        // the walk nor reach the last block of the sequence (which may be ragged) or the ones after it.  The
+        // dK/dV-free region B of this kernel is short (8 MFMAs), and the scalar address arithmetic of the
+        // general fetch does not fit behind it.
+        const int hi = (dir > 0 ? (cnt < nblk - 1 ? cnt : nblk - 1) : cnt) - 7;     // groups starting below hi
+        const bool whole = dir > 0 || cnt - 1 - (p + kDqRing) <= nblk - 2;          // walking down: the first fetch
+        int simple_end = (whole && hi > p) ? p + ((hi - p + 3) / 4) * 4 : p;
+        simple_end = simple_end < plain_end ? simple_end : plain_end;
+        if (p < simple_end) {
+            const int bi = blk(p + kDqRing);
+            k_next = Kh + (int64_t)bi * kDqBK * row_stride;
+            v_next = Vh + (int64_t)bi * kDqBK * row_stride;
+            tile_step = (int64_t)dir * kDqBK * row_stride;
+            for (; p < simple_end; p += 4) {
+                iteration(Plain{}, S0{}, S2{}, p, 0, Simple{});
+                iteration(Plain{}, S1{}, S3{}, p + 1, 0, Simple{});
+                iteration(Plain{}, S2{}, S0{}, p + 2, 0, Simple{});
+                iteration(Plain{}, S3{}, S1{}, p + 3, 0, Simple{});
+            }
+            settle();
+        }
+    }
     for (; p < plain_end; p += 4) {
         // the blocks fetched during these four iterations; with a pattern they lie in one sparse block (the walk
         // position is a multiple of 4 and a sparse block holds 8), so one look-up in the pattern serves all four
@@ -396,17 +435,17 @@ __global__ __launch_bounds__(kDqThreads, 1) void attn_bwd_dq_kernel(
 #pragma unroll
             for (int i = 0; i < 4; ++i) bn[i] = blk(p + kDqRing + i);
         }
-        iteration(Plain{}, S0{}, S2{}, p, bn[0]);
-        iteration(Plain{}, S1{}, S3{}, p + 1, bn[1]);
-        iteration(Plain{}, S2{}, S0{}, p + 2, bn[2]);
-        iteration(Plain{}, S3{}, S1{}, p + 3, bn[3]);
+        iteration(Plain{}, S0{}, S2{}, p, bn[0], General{});
+        iteration(Plain{}, S1{}, S3{}, p + 1, bn[1], General{});
+        iteration(Plain{}, S2{}, S0{}, p + 2, bn[2], General{});
+        iteration(Plain{}, S3{}, S1{}, p + 3, bn[3], General{});
     }
     settle();
     if (dir > 0) {
-        iteration(Masked{}, S0{}, S2{}, p, blk(p + kDqRing)); settle();
-        iteration(Masked{}, S1{}, S3{}, p + 1, blk(p + 1 + kDqRing)); settle();
-        iteration(Masked{}, S2{}, S0{}, p + 2, blk(p + 2 + kDqRing)); settle();
-        iteration(Masked{}, S3{}, S1{}, p + 3, blk(p + 3 + kDqRing)); settle();
+        iteration(Masked{}, S0{}, S2{}, p, blk(p + kDqRing), General{}); settle();
+        iteration(Masked{}, S1{}, S3{}, p + 1, blk(p + 1 + kDqRing), General{}); settle();
+        iteration(Masked{}, S2{}, S0{}, p + 2, blk(p + 2 + kDqRing), General{}); settle();
+        iteration(Masked{}, S3{}, S1{}, p + 3, blk(p + 3 + kDqRing), General{}); settle();
     }
     // Nothing may still be writing LDS when this query tile ends, and the operand reads issued for a
     // block that does not exist must have landed before their (now dead) registers are reused; the same
