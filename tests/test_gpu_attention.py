@@ -109,6 +109,39 @@ def test_wide_logit_range(gpu_lib):
     _full_parity(gpu_lib, 1024, 2, 128, seed=8, mult=3.0)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("causal", [True, False])
+def test_row_maximum_climbs_block_after_block(gpu_lib, causal, d):
+    """Keys whose scores grow by about 7 nats (10 in the exponent of 2) from one 32-key block to the next, in
+    steps or not at all for a stretch: every kernel's running reference maximum has to move again and again,
+    also by more than any lazy threshold, and everything accumulated so far has to be rescaled each time
+    (ordinary inputs do that in the first few blocks only)."""
+    N, Hl = 1500, 2
+    scale = 1.0 / np.sqrt(d)
+    q, k, v, _ = synth.attention_inputs(N, Hl, d, 41 + d)
+    fq, fk = synth.bf16_bits_to_f32(q), synth.bf16_bits_to_f32(k)
+    u = np.zeros(d, np.float32)
+    u[: d // 8] = 1.0                                   # q.k gets a term a_j |u|^2, |u|^2 = d / 8
+    step = np.floor(np.arange(N) / 32.0)
+    step = np.where((step % 7) < 3, step - (step % 7), step)        # plateaus: blocks whose maximum does not move
+    a = (7.0 / scale / (d // 8)) * step                               # so that scale * a_j |u|^2 = 7 * step
+    fq = 0.25 * fq + u                                   # every query: u plus a little noise
+    fk = 0.25 * fk + (a[:, None, None] * u).astype(np.float32)
+    q, k = synth.f32_to_bf16_bits(fq), synth.f32_to_bf16_bits(fk)
+    tq, tk, tv = (to_gpu_bf16(x) for x in (q, k, v))
+    o, lse = gpu_lib.ulysses_attn_fwd(tq, tk, tv, scale, causal, 0)
+    torch.cuda.synchronize()
+    f64 = [oracle.bf16_to_f64(x) for x in (q, k, v)]
+    o_ref, lse_ref = oracle.attn_fwd(*f64, scale, causal, 0)
+    o_abs, _ = oracle.attn_fwd(f64[0], f64[1], np.abs(f64[2]), scale, causal, 0)
+    ok, worst, n_bad = o_within_tolerance(f64_of(o), o_ref, o_abs, TOL_O)
+    assert ok, (worst, n_bad)
+    # LSE is of the order of 300 here; fp32 carries it to about 3e-5, the kernels' own arithmetic adds a little
+    assert max_abs(f64_of(lse), lse_ref) <= 2e-3 + 4e-7 * np.abs(lse_ref).max()
+    # (Forward only: with rows this close to one-hot, dS = P (dP - delta) is the difference of two nearly equal
+    # numbers, delta comes from the bf16-rounded O, and no bf16 backward meets a relative bound on dQ.)
+
+
 def test_multi_tile_medium(gpu_lib):
     _full_parity(gpu_lib, 1536, 7, 128, seed=12)
 
