@@ -441,11 +441,15 @@ constexpr int kQ64BK = 32;
 constexpr int kQ64Ring = 4;
 constexpr float kQ64Lazy = 8.f;
 
-template <bool CAUSAL>
+// CUT: grid (heads, work items); an item is a query tile and a range of its 64-key tiles, from a device-made
+// plan (causal) or in equal pieces (no mask), as for attn_fwd_kernel; items of a cut tile write fp32 partial
+// results (unnormalised O, reference maximum, sum) that attn_fwd_combine_kernel merges.
+template <bool CAUSAL, bool CUT = false>
 __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
     const e16* __restrict__ Q, const e16* __restrict__ K, const e16* __restrict__ V, e16* __restrict__ O,
     float* __restrict__ LSE, int N, int Nk, int n_qtiles, int64_t row_stride, int64_t head_stride,
-    int64_t kv_head_stride, float scale) {
+    int64_t kv_head_stride, float scale, int cut_pieces, int cut_len, float* __restrict__ part_o,
+    float* __restrict__ part_ml, const int4* __restrict__ plan, int slots_per_head) {
     constexpr int D = 128, NT = D / 16, NCB = D / 32;
     constexpr int TILE = kQ64BK * D, TB = TILE * 2;
     constexpr int KB = 0, VB = kQ64Ring * TB;       // byte offsets of the K ring and the V ring
@@ -457,8 +461,23 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: LDS tile addresses stay scalar
-    const int head = blockIdx.x / n_qtiles;
-    const int qt = n_qtiles - 1 - (blockIdx.x - head * n_qtiles);      // causal: the longest tiles start first
+    const int head = CUT ? blockIdx.x : blockIdx.x / n_qtiles;
+    int qt = n_qtiles - 1 - (blockIdx.x - head * n_qtiles);            // causal: the longest tiles start first
+    int t_off = 0, t_len = 0, slot = -1;          // CUT: first 64-key tile of this item, their number, partial-result slot
+    if (CUT && CAUSAL) {
+        const int4 hdr = plan[0];                 // {items, items that write partial results, ..}
+        if ((int)blockIdx.y >= hdr.x) return;     // the grid is an upper bound on the number of items
+        const int4 it = plan[1 + blockIdx.y];     // {query tile, first tile, end, -}
+        qt = it.x;
+        t_off = it.y;
+        t_len = it.z - it.y;
+        slot = (int)blockIdx.y < hdr.y ? (int)blockIdx.y : -1;
+    } else if (CUT) {
+        qt = blockIdx.y / cut_pieces;
+        t_off = (blockIdx.y - qt * cut_pieces) * cut_len;
+        t_len = cut_len;
+        slot = blockIdx.y;
+    }
     const int64_t hoff = (int64_t)head * head_stride;
     const e16* Kh = K + (int64_t)head * kv_head_stride;
     const e16* Vh = V + (int64_t)head * kv_head_stride;
@@ -493,17 +512,27 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
     }
 
     const int q0 = qt * kFwdBQ;
-    // key blocks to process, a multiple of 4; causal: up to the end of this tile's diagonal
-    const int cnt = CAUSAL ? (q0 + kFwdBQ) / kQ64BK : (nblk + 3) & ~3;
+    // Key blocks b_lo .. b_hi-1, walked as cnt (a multiple of 4) local positions; causal: up to the end of this
+    // tile's diagonal.  Blocks from b_hi on are masked entirely.
+    int b_lo = 0, b_hi = CAUSAL ? (q0 + kFwdBQ) / kQ64BK : nblk;
+    if (CUT) {
+        int k_end = Nk;
+        if (CAUSAL) { const int lim = q0 + kFwdBQ; k_end = lim < Nk ? lim : Nk; }
+        const int n_kt = (k_end + kFwdBK - 1) / kFwdBK - t_off;          // 64-key tiles left from t_off on
+        b_lo = 2 * t_off;
+        b_hi = b_lo + 2 * (n_kt < t_len ? n_kt : t_len);
+    }
+    const int cnt = (b_hi - b_lo + 3) & ~3;
     // K tiles of blocks 0..3; V tiles of blocks 0, 1 and, in slot 3, block 0 once more: the first iteration
     // multiplies zeros with that slot, which therefore has to hold finite numbers
 #pragma unroll
-    for (int i = 0; i < kQ64Ring; ++i) load_tile(smem + i * TILE, Kh, i);
-    load_tile(smem + (kQ64Ring + 0) * TILE, Vh, 0);
-    load_tile(smem + (kQ64Ring + 1) * TILE, Vh, 1);
-    load_tile(smem + (kQ64Ring + 3) * TILE, Vh, 0);
-    const e16* k_next = Kh + kQ64Ring * tile_elems;      // the tiles iteration 0 fetches: K of block 4, V of block 2
-    const e16* v_next = Vh + 2 * tile_elems;
+    for (int i = 0; i < kQ64Ring; ++i) load_tile(smem + i * TILE, Kh, b_lo + i);
+    load_tile(smem + (kQ64Ring + 0) * TILE, Vh, b_lo);
+    load_tile(smem + (kQ64Ring + 1) * TILE, Vh, b_lo + 1);
+    load_tile(smem + (kQ64Ring + 3) * TILE, Vh, b_lo);
+    // the tiles iteration 0 fetches: K of the fifth block, V of the third
+    const e16* k_next = Kh + (b_lo + kQ64Ring) * tile_elems;
+    const e16* v_next = Vh + (b_lo + 2) * tile_elems;
 
     // ---- this lane's two queries: Q rows as B operands
     int q_row[2], klim[2];
@@ -513,7 +542,9 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
         q_row[qb] = q0 + wave * 64 + qb * 32 + ln;
         const int q_ld = q_row[qb] < N ? q_row[qb] : N - 1;
         // key offset c_r (inside a block starting at k0) is masked iff c_r > klim - k0
-        klim[qb] = (CAUSAL ? (q_row[qb] < Nk - 1 ? q_row[qb] : Nk - 1) : Nk - 1) - 4 * g;
+        int last = CAUSAL ? (q_row[qb] < Nk - 1 ? q_row[qb] : Nk - 1) : Nk - 1;        // last visible key
+        if (CUT) last = last < b_hi * kQ64BK - 1 ? last : b_hi * kQ64BK - 1;
+        klim[qb] = last - 4 * g;
 #pragma unroll
         for (int t = 0; t < NT; ++t)
             qreg[qb][t] = *reinterpret_cast<const e16x8*>(Q + hoff + (int64_t)q_ld * row_stride + 16 * t + 8 * g);
@@ -636,7 +667,7 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
     __builtin_amdgcn_sched_barrier(0);
     {
         float m_blk[2];
-        block_max(0, true, 0, m_blk);
+        block_max(0, true, b_lo, m_blk);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             m_used[qb] = m_blk[qb];
@@ -733,8 +764,8 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
         wait_vm<LPT>();
         barrier_no_drain();
         if (MASKED) {
-            load_tile(smem + SL * TILE, Kh, p + kQ64Ring);
-            load_tile(smem + (kQ64Ring + (SLV + 3) % kQ64Ring) * TILE, Vh, p + 2);
+            load_tile(smem + SL * TILE, Kh, b_lo + p + kQ64Ring);
+            load_tile(smem + (kQ64Ring + (SLV + 3) % kQ64Ring) * TILE, Vh, b_lo + p + 2);
         } else {                                      // block p+4 is not the last one here: no clamp, no ragged tile
             Loader::issue(smem + SL * TILE, k_next, ld, wave);
             Loader::issue(smem + (kQ64Ring + (SLV + 3) % kQ64Ring) * TILE, v_next, ld, wave);
@@ -761,7 +792,7 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
         pv_half(S1{});
         exp_pair(13); exp_pair(14); exp_pair(15);
         float m_blk[2];
-        const bool moved = block_max(PAR ^ 1, MASKED, p + 1, m_blk);
+        const bool moved = block_max(PAR ^ 1, MASKED, b_lo + p + 1, m_blk);
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -810,10 +841,14 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
 
     using Plain = std::integral_constant<bool, false>;
     using Masked = std::integral_constant<bool, true>;
-    // Blocks that need the mask: the diagonal of this tile (its last 8 blocks) when causal; otherwise the last
-    // group, which holds the end of the key sequence.  An iteration looks at the block after its own, so the
-    // masking variant starts one group earlier; the block after the last does not exist and is masked entirely.
-    const int plain_end = (CAUSAL ? cnt - 8 : cnt - 4) - 4;
+    // An iteration at local position p needs no mask if block b_lo+p+1, whose maxima it takes, is entirely
+    // visible (before this tile's diagonal, inside the sequence and the item), and may fetch through the running
+    // pointers if the blocks it fetches (K: b_lo+p+4, V: b_lo+p+2) are not the last, possibly ragged, block of
+    // the sequence or one after it.  The block after the last does not exist and is masked entirely.
+    int fb = CAUSAL ? q0 / kQ64BK : Nk / kQ64BK;              // first block that needs the mask
+    fb = fb < b_hi ? fb : b_hi;
+    int plain_end = (fb - b_lo - 1 < nblk - 5 - b_lo ? fb - b_lo - 1 : nblk - 5 - b_lo) & ~3;
+    plain_end = plain_end > 0 ? plain_end : 0;
     int p = 0;
     for (; p < plain_end; p += 4) {
         iteration(Plain{}, S0{}, S2{}, S3{}, p);
@@ -853,7 +888,25 @@ __global__ __launch_bounds__(kQ64Threads, 1) void attn_fwd_q64_kernel(
     for (int qb = 0; qb < 2; ++qb) {
         const float l_tot = xhalf_sum(l_run[qb]);
         const float inv = 1.f / l_tot;
-        if (q_row[qb] < N) {
+        if (CUT && slot >= 0) {
+            // one of several items of this query tile: fp32 partial results [slot][query][channel], [slot][query][m, l]
+            const int64_t at = (int64_t)head * slots_per_head + slot;
+            const int row = wave * 64 + qb * 32 + ln;
+            float* prow = part_o + (at * kFwdBQ + row) * D;
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    f32x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = oacc[qb][cb][4 * rq + e];
+                    *reinterpret_cast<f32x4*>(prow + 32 * cb + 8 * rq + 4 * g) = w;
+                }
+            if (g == 0) {
+                part_ml[(at * kFwdBQ + row) * 2] = m_used[qb];
+                part_ml[(at * kFwdBQ + row) * 2 + 1] = l_tot;
+            }
+        } else if (q_row[qb] < N) {
             e16* orow = O + hoff + (int64_t)q_row[qb] * row_stride;
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb)
@@ -985,9 +1038,14 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
         const int64_t items = n_qtiles * cut.pieces;
         float* part_o = ws;
         float* part_ml = ws + items * Hl * (int64_t)kFwdBQ * D;
-        attn_fwd_kernel<D, false, false, true><<<dim3((uint32_t)Hl, (uint32_t)items), dim3(kFwdThreads), 0, stream>>>(
-            (const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
-            kv.head, scale, nullptr, nullptr, cut.pieces, cut.len, part_o, part_ml, nullptr, (int)items);
+        if constexpr (D == 128)
+            attn_fwd_q64_kernel<false, true><<<dim3((uint32_t)Hl, (uint32_t)items), dim3(kQ64Threads), 0, stream>>>(
+                (const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
+                kv.head, scale, cut.pieces, cut.len, part_o, part_ml, nullptr, (int)items);
+        else
+            attn_fwd_kernel<D, false, false, true><<<dim3((uint32_t)Hl, (uint32_t)items), dim3(kFwdThreads), 0, stream>>>(
+                (const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
+                kv.head, scale, nullptr, nullptr, cut.pieces, cut.len, part_o, part_ml, nullptr, (int)items);
         if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
         attn_fwd_combine_kernel<D><<<dim3((uint32_t)(n_qtiles * (kFwdBQ / 8)), (uint32_t)Hl), dim3(256), 0, stream>>>(
             part_o, part_ml, cut.pieces, nullptr, (int)items, (e16*)o, lse, (int)N, st.row, st.head, scale);
@@ -1002,10 +1060,16 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
             float* part_ml = ws + w.part_ml_at;
             if (sparse_plan_launch(3, nullptr, n_qtiles, N, Hl, w.slots_per_head, kFwdRowPlanTarget, plan, red, stream) != ULY_OK)
                 return ULY_ERR_LAUNCH;
-            attn_fwd_kernel<D, true, false, true>
-                <<<dim3((uint32_t)Hl, (uint32_t)w.items_bound), dim3(kFwdThreads), 0, stream>>>(
-                    (const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row, st.head,
-                    kv.head, scale, nullptr, nullptr, 1, 0, part_o, part_ml, plan, w.slots_per_head);
+            if constexpr (D == 128)
+                attn_fwd_q64_kernel<true, true>
+                    <<<dim3((uint32_t)Hl, (uint32_t)w.items_bound), dim3(kQ64Threads), 0, stream>>>(
+                        (const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row,
+                        st.head, kv.head, scale, 1, 0, part_o, part_ml, plan, w.slots_per_head);
+            else
+                attn_fwd_kernel<D, true, false, true>
+                    <<<dim3((uint32_t)Hl, (uint32_t)w.items_bound), dim3(kFwdThreads), 0, stream>>>(
+                        (const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse, (int)N, (int)Nk, (int)n_qtiles, st.row,
+                        st.head, kv.head, scale, nullptr, nullptr, 1, 0, part_o, part_ml, plan, w.slots_per_head);
             if (hipGetLastError() != hipSuccess) return ULY_ERR_LAUNCH;
             attn_fwd_combine_kernel<D><<<dim3((uint32_t)(n_qtiles * (kFwdBQ / 8)), (uint32_t)Hl), dim3(256), 0, stream>>>(
                 part_o, part_ml, 0, red, w.slots_per_head, (e16*)o, lse, (int)N, st.row, st.head, scale);
@@ -1020,11 +1084,11 @@ static int launch_fwd(const void* q, const void* k, const void* v, void* o, floa
         if (causal)
             attn_fwd_q64_kernel<true><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse,
                                                                   (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head,
-                                                                  scale);
+                                                                  scale, 1, 0, nullptr, nullptr, nullptr, 0);
         else
             attn_fwd_q64_kernel<false><<<grid, block, 0, stream>>>((const e16*)q, (const e16*)k, (const e16*)v, (e16*)o, lse,
                                                                    (int)N, (int)Nk, (int)n_qtiles, st.row, st.head, kv.head,
-                                                                   scale);
+                                                                   scale, 1, 0, nullptr, nullptr, nullptr, 0);
     } else {
         dim3 grid((uint32_t)blocks), block(kFwdThreads);
         if (causal)
