@@ -429,7 +429,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void attn_fwd_kernel(const e16* __r
 // V^T operand read from LDS feeds two MFMAs.  That takes 128 accumulator + 64 Q-operand registers,
 // so it runs one wave per SIMD (4 waves = 256 queries per workgroup, one workgroup per CU) and
 // overlaps its vector work with its matrix work inside the wave.  Iteration p:
-//     region A   matrix: S^T of block p+1              vector: exponentials of block p (3/4 of them)
+//     region A   matrix: S^T of block p+1              vector: exponentials of block p (10 of its 16 score pairs)
 //     region B   matrix: O^T += V^T P^T of block p-1   vector: the other exponentials, row maxima of block p+1
 // The product with V lags one block behind the exponentials so that neither region waits for the
 // vector unit.  K and V stream through rings of four 32-key LDS tiles.  The reference maximum of a
